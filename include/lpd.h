@@ -1,0 +1,184 @@
+/*
+ * lpd.h -- C ABI of the MI355X (gfx950) low-rank stage of the LPD-SVM solver
+ * (T. Glasmachers, "Recipe for Fast Large-scale SVM Training: Polishing,
+ * Parallelism, and more RAM!").
+ *
+ * The library computes, on one GPU, the hot path of the method's two stages:
+ *
+ *   stage 1, Figure 1 step 1d:  G = Z W^T,  Z[i,b] = exp(-gamma ||x_i - l_b||^2)
+ *   stage 2, Figure 1 step 2a:  m_i = G_i w
+ *
+ * plus the one-off host preparation of steps 1a-1c (landmark kernel matrix,
+ * symmetric eigendecomposition, inverse-square-root factor with small
+ * components dropped, Section 3).
+ *
+ * Symbols.  The paper calls the B x B factor of step 1c "L = U sqrt(D^-1)" and
+ * sets G = Z L.  This interface stores its transpose W = sqrt(D^-1) U^T, one
+ * whitened direction per ROW (r rows of length B, r <= B the number of kept
+ * components), so that G = Z W^T and both products on the device contract
+ * over the contiguous axis of two row-major operands.  "L" in this header is
+ * the B x d matrix of landmark points (the random subset of step 1a).
+ *
+ * Conventions for every call.
+ *   - All matrices are row-major fp32 with an explicit leading dimension
+ *     (elements, >= number of columns).
+ *   - "device" pointers are HIP device memory of the current device, owned by
+ *     the caller (e.g. torch tensors); "host" pointers are ordinary memory.
+ *     Device matrix pointers and leading dimensions need no alignment, but the
+ *     fast path needs 16-byte aligned pointers and leading dimensions that are
+ *     multiples of 4; anything else takes a slower element-wise loader.
+ *   - Device calls only enqueue work on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and return; results are ready once the
+ *     stream has been synchronised.  The library allocates no device memory.
+ *   - Sizes may be zero: the call then does nothing and returns LPD_OK.
+ *   - Every function returns an lpd_status; nothing throws or exits.
+ *     Execution faults of an enqueued kernel surface at the caller's next
+ *     synchronisation, launch failures are returned as LPD_ERR_HIP.
+ *   - Inputs and outputs must not overlap.
+ */
+#ifndef LPD_H
+#define LPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LPD_OK = 0,
+    LPD_ERR_NULL = -1,      /* a required pointer is NULL                       */
+    LPD_ERR_SHAPE = -2,     /* negative size, r > B, or a size above the limits */
+    LPD_ERR_LD = -3,        /* a leading dimension is smaller than the row      */
+    LPD_ERR_WORKSPACE = -4, /* workspace missing, misaligned or too small       */
+    LPD_ERR_HIP = -5,       /* a HIP runtime call or kernel launch failed       */
+    LPD_ERR_NUMERIC = -6    /* eigensolver did not converge / kernel matrix not
+                               positive (largest eigenvalue <= 0)               */
+} lpd_status;
+
+/* Library version, major * 100 + minor. */
+int lpd_version(void);
+
+/* Static description of a status code (never NULL). */
+const char *lpd_strerror(int status);
+
+/*
+ * Process-wide tuning knobs (not part of the method; defaults are chosen per
+ * shape).  Not synchronised: set them while no other call is in flight.
+ *   LPD_OPT_GEMM_TILE  workgroup tile of the two MFMA products:
+ *                      0 = choose by shape, 1 = 128x128, 2 = 256x128, 3 = 256x256
+ * Errors: LPD_ERR_SHAPE for an unknown option or value.
+ */
+typedef enum { LPD_OPT_GEMM_TILE = 1 } lpd_option;
+int lpd_set_option(int option, int64_t value);
+
+/*
+ * Host preparation, Figure 1 steps 1a-1c with the dropping rule of Section 3
+ * (second bullet).  Runs on the calling host in double precision, blocking.
+ *
+ *   K_LL[a,b] = exp(-gamma ||l_a - l_b||^2)                        (1a, Section 4 kernel)
+ *   K_LL = U D U^T, eigenvalues sorted descending                  (1b)
+ *   r = #{ j : D_j >= clip_ratio * D_0 and D_j > 0 }
+ *   W[j,:] = D_j^-1/2 u_j^T  for j < r, rows r..B-1 are zero       (1c)
+ *
+ * Each kept eigenvector's sign makes its largest-magnitude entry positive
+ * (first such entry on ties).  The paper leaves the threshold open ("close to
+ * machine precision times the largest eigenvalue"); callers pass it, 1e-10 in
+ * this project's workloads.
+ *
+ *   L_host   in   B x d landmarks, leading dimension ldl
+ *   W_host   out  B x B, leading dimension ldw
+ *   eig_host out  B eigenvalues, descending (may be NULL)
+ *   rank     out  r
+ * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE, LPD_ERR_LD, LPD_ERR_NUMERIC.
+ */
+int lpd_whiten_host(const float *L_host, int64_t B, int64_t d, int64_t ldl,
+                    double gamma, double clip_ratio,
+                    float *W_host, int64_t ldw, double *eig_host, int64_t *rank);
+
+/*
+ * Device scratch for lpd_nystrom_factor / lpd_kernel_block: squared row norms
+ * of X and L plus one row panel of the kernel block Z.  `*bytes` receives the
+ * recommended size for this shape; any 256-byte aligned buffer of at least
+ * `*min_bytes` (may be NULL) works, larger ones allow larger panels.
+ */
+int lpd_nystrom_factor_workspace(int64_t n, int64_t d, int64_t B,
+                                 size_t *bytes, size_t *min_bytes);
+
+/*
+ * Figure 1 step 1d on the device:  G[i, j] = sum_b W[j,b] * Z[i,b]  for j < r,
+ * G[i, j] = 0 for r <= j < B, with Z[i,b] = exp(-gamma ||x_i - l_b||^2)
+ * (Gaussian kernel of Section 4).  The n x B block Z is produced panel by
+ * panel into the workspace and consumed at once; it never exists as a whole.
+ *
+ *   X  device in   n x d, ldx          L  device in   B x d, ldl
+ *   W  device in   r x B, ldw          G  device out  n x B, ldg
+ *   workspace      device, 256-byte aligned, see lpd_nystrom_factor_workspace
+ * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE, LPD_ERR_LD, LPD_ERR_WORKSPACE, LPD_ERR_HIP.
+ */
+int lpd_nystrom_factor(const float *X, int64_t n, int64_t d, int64_t ldx,
+                       const float *L, int64_t B, int64_t ldl,
+                       float gamma,
+                       const float *W, int64_t r, int64_t ldw,
+                       float *G, int64_t ldg,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Per-call device timing filled by lpd_nystrom_factor_profiled (milliseconds
+ * summed over the launches of each kernel, from HIP events on `hip_stream`). */
+typedef struct {
+    int32_t launches_norms, launches_kernel_block, launches_whiten;
+    int32_t panel_rows;
+    float ms_norms, ms_kernel_block, ms_whiten;
+} lpd_factor_profile;
+
+/*
+ * Same work as lpd_nystrom_factor, with a HIP event recorded on `hip_stream`
+ * before and after every kernel launch.  Unlike the plain call it BLOCKS until
+ * the stream has drained, then fills *profile (host).  Meant for benchmarks.
+ */
+int lpd_nystrom_factor_profiled(const float *X, int64_t n, int64_t d, int64_t ldx,
+                                const float *L, int64_t B, int64_t ldl,
+                                float gamma,
+                                const float *W, int64_t r, int64_t ldw,
+                                float *G, int64_t ldg,
+                                void *workspace, size_t workspace_bytes, void *hip_stream,
+                                lpd_factor_profile *profile);
+
+/*
+ * The kernel block alone (Figure 1 steps 1a / 1d, Section 4 kernel):
+ * Z[i,b] = exp(-gamma ||x_i - l_b||^2), written in full to device memory.
+ * With X = L this is the landmark kernel matrix K_LL of step 1a.
+ *
+ *   X device in n x d, ldx;  L device in B x d, ldl;  Z device out n x B, ldz
+ *   workspace: at least 4 * (n + B) bytes rounded up to 256 (row norms only).
+ */
+int lpd_kernel_block(const float *X, int64_t n, int64_t d, int64_t ldx,
+                     const float *L, int64_t B, int64_t ldl,
+                     float gamma, float *Z, int64_t ldz,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Figure 1 step 2a for every row at once:  m[i] = sum_{j<r} G[i,j] * w[j].
+ * Raw margins: no label, no offset (the method has no bias term, Section 2).
+ *
+ *   G device in n x r (ldg >= r);  w device in r;  m device out n
+ */
+int lpd_margins(const float *G, int64_t n, int64_t r, int64_t ldg,
+                const float *w, float *m, void *hip_stream);
+
+/*
+ * Step 2a over a subset of rows, as the solver's shrinking re-check and
+ * cross-validation folds need it (Section 3, "Shrinking" and
+ * "Cross Validation"):  m[t] = sum_{j<r} G[rows[t], j] * w[j],  t < n_rows.
+ *
+ *   rows device in  n_rows int64 indices, each in [0, n)  (not checked on the device)
+ */
+int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg,
+                     const int64_t *rows, int64_t n_rows,
+                     const float *w, float *m, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LPD_H */

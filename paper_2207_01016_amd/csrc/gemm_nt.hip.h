@@ -1,0 +1,227 @@
+// fp32 MFMA GEMM for gfx950:  C[M x N] = epilogue( A[M x K] * B[N x K]^T ).
+//
+// Both operands are row-major and contracted over their contiguous axis, which
+// is the shape of both products of Figure 1 step 1d: the distance contraction
+// X L^T (contraction over the d features) and the whitening product Z W^T
+// (contraction over the B landmarks).
+//
+// Design for CDNA4:
+//   * one workgroup = WGM x WGN wavefronts of 64 lanes, each wavefront owns a
+//     (BM/WGM) x (BN/WGN) block of C as 32x32 accumulator tiles of
+//     v_mfma_f32_32x32x2_f32 (lane l feeds A[row l%32][k l/32] and
+//     B[col l%32][k l/32]; accumulator register v of lane l is
+//     C[8*(v/4) + 4*(l/32) + v%4][l%32]).
+//   * global -> registers -> LDS with 16-byte accesses, double-buffered LDS,
+//     one barrier per k-tile.  LDS rows keep the k index contiguous
+//     ([row][BK+4] floats): the +4 pad makes the 16-byte reads of 16 consecutive
+//     rows hit 16 distinct bank groups.  Each lane reads 4 consecutive k with
+//     one ds_read_b128; lanes 0-31 take k0..k0+3 and lanes 32-63 k0+4..k0+7, so
+//     the 4 MFMA steps of a read pair k = (k0+t, k0+4+t).  A and B use the same
+//     pairing, and a sum does not care in which order k is visited.
+//   * workgroup ids are remapped so that the ids one XCD receives (id mod 8)
+//     form a contiguous range of tiles, and tiles are walked in groups of GM
+//     tile rows, so the 32 workgroups resident on an XCD share A and B strips
+//     in that XCD's L2.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lpd {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+enum { EPI_STORE = 0, EPI_GAUSS = 1 };
+
+struct GemmArgs {
+    const float *A;  // M x K
+    const float *B;  // N x K
+    float *C;        // M x n_store
+    int64_t lda, ldb, ldc;
+    int M, N, K;
+    int n_store;     // columns [N, n_store) of C are written as zeros
+    int tiles_m, tiles_n;
+    // EPI_GAUSS: C = exp2(scale * max(0, na[row] + nb[col] - 2 acc)), scale = -gamma * log2(e)
+    const float *na, *nb;
+    float scale;
+};
+
+constexpr int GEMM_BK = 16;
+constexpr int GEMM_LDK = GEMM_BK + 4;
+
+template <int BM, int BN>
+constexpr size_t gemm_lds_bytes() { return size_t(2) * (BM + BN) * GEMM_LDK * sizeof(float); }
+
+template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
+{
+    constexpr int BK = GEMM_BK, LDK = GEMM_LDK;
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int CPR = BK / 4;        // 16-byte chunks per tile row
+    constexpr int RPP = NT / CPR;      // tile rows filled per pass of the workgroup
+    constexpr int PA = BM / RPP, PB = BN / RPP;
+    constexpr int STAGE = (BM + BN) * LDK;
+    static_assert(BM % RPP == 0 && BN % RPP == 0, "tile rows must be a multiple of the loader pass");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 MFMA tiles");
+
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    // ---- workgroup id -> tile, XCD-aware and grouped
+    int tm, tn;
+    {
+        const int nwg = gridDim.x;
+        const int id = blockIdx.x;
+        const int per = nwg >> 3;
+        const int lin = (id < (per << 3)) ? (id & 7) * per + (id >> 3) : id;
+        constexpr int GM = 8;
+        const int group_sz = GM * p.tiles_n;
+        const int g = lin / group_sz;
+        const int first_m = g * GM;
+        const int gm = min(p.tiles_m - first_m, GM);
+        const int within = lin - g * group_sz;
+        tm = first_m + within % gm;
+        tn = within / gm;
+    }
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    // Tiles that lie entirely in the zero-filled columns do no arithmetic.
+    if (EPI == EPI_STORE && n0 >= p.N) {
+        for (int e = tid; e < BM * BN; e += NT) {
+            const int rr = m0 + e / BN, cc = n0 + e % BN;
+            if (rr < p.M && cc < p.n_store) p.C[int64_t(rr) * p.ldc + cc] = 0.0f;
+        }
+        return;
+    }
+
+    // ---- global loader set-up: thread -> (row within pass, 16-byte chunk)
+    const int lrow = tid / CPR, lch = tid % CPR;
+    const float *ga[PA], *gb[PB];
+#pragma unroll
+    for (int q = 0; q < PA; ++q) {
+        const int rr = min(m0 + lrow + q * RPP, p.M - 1);
+        ga[q] = p.A + int64_t(rr) * p.lda + lch * 4;
+    }
+#pragma unroll
+    for (int q = 0; q < PB; ++q) {
+        const int rr = min(n0 + lrow + q * RPP, p.N - 1);
+        gb[q] = p.B + int64_t(rr) * p.ldb + lch * 4;
+    }
+
+    f32x4 ra[PA], rb[PB];
+    auto gload = [&](int k0) {
+        const int k = k0 + lch * 4;
+        if (ALIGNED) {
+            if (k < p.K) {
+#pragma unroll
+                for (int q = 0; q < PA; ++q) ra[q] = *reinterpret_cast<const f32x4 *>(ga[q] + k0);
+#pragma unroll
+                for (int q = 0; q < PB; ++q) rb[q] = *reinterpret_cast<const f32x4 *>(gb[q] + k0);
+            } else {
+#pragma unroll
+                for (int q = 0; q < PA; ++q) ra[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int q = 0; q < PB; ++q) rb[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < PA; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ra[q][e] = (k + e < p.K) ? ga[q][k0 + e] : 0.0f;
+#pragma unroll
+            for (int q = 0; q < PB; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rb[q][e] = (k + e < p.K) ? gb[q][k0 + e] : 0.0f;
+        }
+    };
+    auto lstore = [&](int buf) {
+        float *As = lds + buf * STAGE;
+        float *Bs = As + BM * LDK;
+#pragma unroll
+        for (int q = 0; q < PA; ++q)
+            *reinterpret_cast<f32x4 *>(&As[(lrow + q * RPP) * LDK + lch * 4]) = ra[q];
+#pragma unroll
+        for (int q = 0; q < PB; ++q)
+            *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) = rb[q];
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int frag_row = lane & 31;
+    const int frag_k = (lane >> 5) * 4;
+    const int a_off = (wm * WM + frag_row) * LDK + frag_k;
+    const int b_off = BM * LDK + (wn * WN + frag_row) * LDK + frag_k;
+
+    const int nk = (p.K + BK - 1) / BK;
+    gload(0);
+    lstore(0);
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < nk;
+        if (more) gload((kt + 1) * BK);
+
+        const float *S = lds + cur * STAGE;
+#pragma unroll
+        for (int kc = 0; kc < BK / 8; ++kc) {
+            f32x4 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                a[i] = *reinterpret_cast<const f32x4 *>(&S[a_off + i * 32 * LDK + kc * 8]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                b[j] = *reinterpret_cast<const f32x4 *>(&S[b_off + j * 32 * LDK + kc * 8]);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[j][t], acc[i][j], 0, 0, 0);
+        }
+
+        if (more) lstore(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: accumulator register v of lane l is C[8*(v/4) + 4*(l/32) + v%4][l%32]
+    const int col_in = lane & 31;
+    const int row_in = (lane >> 5) * 4;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int cc = n0 + wn * WN + j * 32 + col_in;
+        if (cc >= p.n_store) continue;
+        const bool live = cc < p.N;
+        float nbv = 0.0f;
+        if (EPI == EPI_GAUSS) nbv = live ? p.nb[cc] : 0.0f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = m0 + wm * WM + i * 32 + 8 * (v >> 2) + row_in + (v & 3);
+                if (rr >= p.M) continue;
+                float out = acc[i][j][v];
+                if (EPI == EPI_GAUSS) {
+                    const float dist = fmaxf(p.na[rr] + nbv - 2.0f * out, 0.0f);
+                    out = __builtin_amdgcn_exp2f(p.scale * dist);
+                }
+                p.C[int64_t(rr) * p.ldc + cc] = live ? out : 0.0f;
+            }
+        }
+    }
+}
+
+}  // namespace lpd

@@ -1,0 +1,373 @@
+// C ABI of the library (see include/lpd.h): argument checks, workspace
+// carving, the row-panel schedule of Figure 1 step 1d, and kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <vector>
+
+#include "../../include/lpd.h"
+#include "gemm_nt.hip.h"
+#include "rowops.hip.h"
+
+namespace {
+
+using namespace lpd;
+
+constexpr int64_t kMaxDim = int64_t(1) << 30;   // n, d, B limits (32-bit tile arithmetic inside kernels)
+constexpr size_t kAlign = 256;
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Leading dimension of the Z panel inside the workspace: a multiple of 4 floats
+// (16-byte rows), nudged off large powers of two so the rows of one tile do not
+// all start in the same memory channel.
+inline int64_t panel_ld(int64_t B)
+{
+    int64_t ld = (B + 3) / 4 * 4;
+    if (ld % 512 == 0) ld += 16;
+    return ld;
+}
+
+struct Carve {
+    size_t off_nx, off_nl, off_z, min_bytes, rec_bytes;
+    int64_t ldz, rec_rows, min_rows;
+};
+
+Carve carve(int64_t n, int64_t B)
+{
+    Carve c;
+    c.ldz = panel_ld(B);
+    c.off_nx = 0;
+    c.off_nl = round_up(size_t(n) * 4, kAlign);
+    c.off_z = c.off_nl + round_up(size_t(B) * 4, kAlign);
+    c.min_rows = std::min<int64_t>(n, 256);
+    // recommended panel: about 64 Mi elements of Z, a whole number of 256-row tiles
+    int64_t rows = (int64_t(64) << 20) / std::max<int64_t>(c.ldz, 1);
+    rows = std::max<int64_t>(256, rows / 256 * 256);
+    c.rec_rows = std::min<int64_t>(rows, (n + 255) / 256 * 256);
+    c.rec_rows = std::max<int64_t>(c.rec_rows, c.min_rows);
+    c.min_bytes = c.off_z + round_up(size_t(c.min_rows) * c.ldz * 4, kAlign);
+    c.rec_bytes = c.off_z + round_up(size_t(c.rec_rows) * c.ldz * 4, kAlign);
+    return c;
+}
+
+// ---------------------------------------------------------------- GEMM launch
+
+enum TileId { TILE_AUTO = 0, TILE_128x128 = 1, TILE_256x128 = 2, TILE_256x256 = 3 };
+
+int g_tile_option = TILE_AUTO;   // lpd_set_option(LPD_OPT_GEMM_TILE, ...)
+
+int tile_choice(const GemmArgs &a)
+{
+    if (g_tile_option != TILE_AUTO) return g_tile_option;
+    (void)a;
+    return TILE_128x128;
+}
+
+template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI>
+hipError_t launch_one(GemmArgs a, hipStream_t s)
+{
+    constexpr size_t lds = gemm_lds_bytes<BM, BN>();
+    auto kern = gemm_nt_kernel<BM, BN, WGM, WGN, ALIGNED, EPI>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    a.tiles_m = (a.M + BM - 1) / BM;
+    a.tiles_n = (a.n_store + BN - 1) / BN;
+    const int64_t wgs = int64_t(a.tiles_m) * a.tiles_n;
+    if (wgs <= 0) return hipSuccess;
+    if (wgs > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3(unsigned(wgs)), dim3(WGM * WGN * 64), lds, s, a);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int WGM, int WGN>
+hipError_t launch_tile(const GemmArgs &a, bool aligned, int epi, hipStream_t s)
+{
+    if (epi == EPI_GAUSS)
+        return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS>(a, s)
+                       : launch_one<BM, BN, WGM, WGN, false, EPI_GAUSS>(a, s);
+    return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_STORE>(a, s)
+                   : launch_one<BM, BN, WGM, WGN, false, EPI_STORE>(a, s);
+}
+
+hipError_t launch_gemm(const GemmArgs &a, int epi, hipStream_t s)
+{
+    const bool aligned = aligned16(a.A) && aligned16(a.B) && a.lda % 4 == 0 && a.ldb % 4 == 0 && a.K % 4 == 0;
+    switch (tile_choice(a)) {
+    case TILE_256x256: return launch_tile<256, 256, 2, 2>(a, aligned, epi, s);
+    case TILE_256x128: return launch_tile<256, 128, 2, 2>(a, aligned, epi, s);
+    default: return launch_tile<128, 128, 2, 2>(a, aligned, epi, s);
+    }
+}
+
+// ---------------------------------------------------------------- row kernels
+
+inline unsigned row_grid(int64_t rows, int groups)
+{
+    const int64_t need = (rows + groups - 1) / groups;
+    return unsigned(std::max<int64_t>(1, std::min<int64_t>(need, 4096)));
+}
+
+hipError_t launch_sqnorm(const float *X, int64_t n, int64_t d, int64_t ldx, float *out, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    const bool vec = aligned16(X) && ldx % 4 == 0;
+    if (d >= 256) {
+        if (vec) hipLaunchKernelGGL((sqnorm_kernel<64, true>), dim3(row_grid(n, 4)), dim3(256), 0, s, X, n, int(d), ldx, out);
+        else hipLaunchKernelGGL((sqnorm_kernel<64, false>), dim3(row_grid(n, 4)), dim3(256), 0, s, X, n, int(d), ldx, out);
+    } else {
+        if (vec) hipLaunchKernelGGL((sqnorm_kernel<8, true>), dim3(row_grid(n, 32)), dim3(256), 0, s, X, n, int(d), ldx, out);
+        else hipLaunchKernelGGL((sqnorm_kernel<8, false>), dim3(row_grid(n, 32)), dim3(256), 0, s, X, n, int(d), ldx, out);
+    }
+    return hipGetLastError();
+}
+
+template <int LPR, bool INDEXED>
+hipError_t launch_margins_lpr(const float *G, int64_t n_out, int r, int64_t ldg, const int64_t *rows,
+                              const float *w, float *m, bool vec, hipStream_t s)
+{
+    const unsigned grid = row_grid(n_out, 256 / LPR);
+    if (vec) hipLaunchKernelGGL((margins_kernel<LPR, true, INDEXED>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m);
+    else hipLaunchKernelGGL((margins_kernel<LPR, false, INDEXED>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m);
+    return hipGetLastError();
+}
+
+template <bool INDEXED>
+hipError_t launch_margins(const float *G, int64_t n_out, int64_t r, int64_t ldg, const int64_t *rows,
+                          const float *w, float *m, hipStream_t s)
+{
+    const bool vec = aligned16(G) && aligned16(w) && ldg % 4 == 0;
+    const int ri = int(r);
+    if (r >= 256) return launch_margins_lpr<64, INDEXED>(G, n_out, ri, ldg, rows, w, m, vec, s);
+    if (r >= 128) return launch_margins_lpr<32, INDEXED>(G, n_out, ri, ldg, rows, w, m, vec, s);
+    if (r >= 64) return launch_margins_lpr<16, INDEXED>(G, n_out, ri, ldg, rows, w, m, vec, s);
+    return launch_margins_lpr<8, INDEXED>(G, n_out, ri, ldg, rows, w, m, vec, s);
+}
+
+// ---------------------------------------------------------------- factor schedule
+
+struct EventLog {
+    struct Span { int kind; hipEvent_t a, b; };
+    std::vector<Span> spans;
+    bool on = false;
+    hipError_t begin(int kind, hipStream_t s)
+    {
+        if (!on) return hipSuccess;
+        Span sp{kind, nullptr, nullptr};
+        hipError_t e = hipEventCreate(&sp.a);
+        if (e != hipSuccess) return e;
+        e = hipEventCreate(&sp.b);
+        if (e != hipSuccess) { (void)hipEventDestroy(sp.a); return e; }
+        spans.push_back(sp);
+        return hipEventRecord(sp.a, s);
+    }
+    hipError_t end(hipStream_t s) { return on ? hipEventRecord(spans.back().b, s) : hipSuccess; }
+    void destroy()
+    {
+        for (auto &sp : spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+        spans.clear();
+    }
+};
+
+int check_factor_args(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,
+                      const float *W, int64_t r, int64_t ldw, const float *G, int64_t ldg)
+{
+    if (n < 0 || d < 0 || B < 0 || r < 0 || r > B || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
+    if (n == 0 || B == 0) return LPD_OK;
+    if (!G) return LPD_ERR_NULL;
+    if (ldg < B) return LPD_ERR_LD;
+    if (d > 0 && (!X || !L)) return LPD_ERR_NULL;
+    if (d > 0 && (ldx < d || ldl < d)) return LPD_ERR_LD;
+    if (r > 0 && !W) return LPD_ERR_NULL;
+    if (r > 0 && ldw < B) return LPD_ERR_LD;
+    return LPD_OK;
+}
+
+#define LPD_HIP(call)                                  \
+    do {                                               \
+        hipError_t e__ = (call);                       \
+        if (e__ != hipSuccess) { status = LPD_ERR_HIP; goto done; } \
+    } while (0)
+
+int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,
+                float gamma, const float *W, int64_t r, int64_t ldw, float *G, int64_t ldg, void *workspace,
+                size_t workspace_bytes, hipStream_t s, lpd_factor_profile *prof)
+{
+    int status = check_factor_args(X, n, d, ldx, L, B, ldl, W, r, ldw, G, ldg);
+    if (prof) std::memset(prof, 0, sizeof(*prof));
+    if (status != LPD_OK || n == 0 || B == 0) return status;
+
+    const Carve c = carve(n, B);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < c.min_bytes)
+        return LPD_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace);
+    float *nx = reinterpret_cast<float *>(ws + c.off_nx);
+    float *nl = reinterpret_cast<float *>(ws + c.off_nl);
+    float *Z = reinterpret_cast<float *>(ws + c.off_z);
+    int64_t panel = int64_t((workspace_bytes - c.off_z) / (size_t(c.ldz) * 4));
+    if (panel >= n) panel = n;
+    else panel = std::max<int64_t>(c.min_rows, panel / 256 * 256);
+
+    EventLog log;
+    log.on = prof != nullptr;
+
+    LPD_HIP(log.begin(0, s));
+    LPD_HIP(launch_sqnorm(X, n, d, ldx, nx, s));
+    LPD_HIP(launch_sqnorm(L, B, d, ldl, nl, s));
+    LPD_HIP(log.end(s));
+
+    for (int64_t p0 = 0; p0 < n; p0 += panel) {
+        const int64_t rows = std::min<int64_t>(panel, n - p0);
+        GemmArgs k1{};
+        k1.A = X + p0 * ldx; k1.lda = ldx;
+        k1.B = L; k1.ldb = ldl;
+        k1.C = Z; k1.ldc = c.ldz;
+        k1.M = int(rows); k1.N = int(B); k1.K = int(d); k1.n_store = int(B);
+        k1.na = nx + p0; k1.nb = nl;
+        k1.scale = -gamma * 1.44269504088896340736f;
+        LPD_HIP(log.begin(1, s));
+        LPD_HIP(launch_gemm(k1, EPI_GAUSS, s));
+        LPD_HIP(log.end(s));
+
+        GemmArgs k2{};
+        k2.A = Z; k2.lda = c.ldz;
+        k2.B = W; k2.ldb = ldw;
+        k2.C = G + p0 * ldg; k2.ldc = ldg;
+        k2.M = int(rows); k2.N = int(r); k2.K = int(B); k2.n_store = int(B);
+        LPD_HIP(log.begin(2, s));
+        LPD_HIP(launch_gemm(k2, EPI_STORE, s));
+        LPD_HIP(log.end(s));
+    }
+
+    if (prof) {
+        LPD_HIP(hipStreamSynchronize(s));
+        prof->panel_rows = int32_t(panel);
+        for (auto &sp : log.spans) {
+            float ms = 0.f;
+            LPD_HIP(hipEventElapsedTime(&ms, sp.a, sp.b));
+            if (sp.kind == 0) { prof->ms_norms += ms; prof->launches_norms += 2; }
+            else if (sp.kind == 1) { prof->ms_kernel_block += ms; prof->launches_kernel_block += 1; }
+            else { prof->ms_whiten += ms; prof->launches_whiten += 1; }
+        }
+    }
+done:
+    log.destroy();
+    return status;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lpd_version(void) { return 100; }
+
+const char *lpd_strerror(int status)
+{
+    switch (status) {
+    case LPD_OK: return "ok";
+    case LPD_ERR_NULL: return "a required pointer is NULL";
+    case LPD_ERR_SHAPE: return "invalid size (negative, r > B, or above the supported limit)";
+    case LPD_ERR_LD: return "leading dimension smaller than the row length";
+    case LPD_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
+    case LPD_ERR_HIP: return "HIP runtime call or kernel launch failed";
+    case LPD_ERR_NUMERIC: return "eigendecomposition failed or kernel matrix not positive";
+    default: return "unknown status";
+    }
+}
+
+int lpd_set_option(int option, int64_t value)
+{
+    if (option == LPD_OPT_GEMM_TILE && value >= TILE_AUTO && value <= TILE_256x256) {
+        g_tile_option = int(value);
+        return LPD_OK;
+    }
+    return LPD_ERR_SHAPE;
+}
+
+int lpd_nystrom_factor_workspace(int64_t n, int64_t d, int64_t B, size_t *bytes, size_t *min_bytes)
+{
+    if (!bytes) return LPD_ERR_NULL;
+    if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
+    const Carve c = carve(n, B);
+    *bytes = c.rec_bytes;
+    if (min_bytes) *min_bytes = c.min_bytes;
+    return LPD_OK;
+}
+
+int lpd_nystrom_factor(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,
+                       float gamma, const float *W, int64_t r, int64_t ldw, float *G, int64_t ldg,
+                       void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return factor_impl(X, n, d, ldx, L, B, ldl, gamma, W, r, ldw, G, ldg, workspace, workspace_bytes,
+                       static_cast<hipStream_t>(hip_stream), nullptr);
+}
+
+int lpd_nystrom_factor_profiled(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B,
+                                int64_t ldl, float gamma, const float *W, int64_t r, int64_t ldw, float *G,
+                                int64_t ldg, void *workspace, size_t workspace_bytes, void *hip_stream,
+                                lpd_factor_profile *profile)
+{
+    if (!profile) return LPD_ERR_NULL;
+    return factor_impl(X, n, d, ldx, L, B, ldl, gamma, W, r, ldw, G, ldg, workspace, workspace_bytes,
+                       static_cast<hipStream_t>(hip_stream), profile);
+}
+
+int lpd_kernel_block(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,
+                     float gamma, float *Z, int64_t ldz, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
+    if (n == 0 || B == 0) return LPD_OK;
+    if (!Z) return LPD_ERR_NULL;
+    if (ldz < B) return LPD_ERR_LD;
+    if (d > 0 && (!X || !L)) return LPD_ERR_NULL;
+    if (d > 0 && (ldx < d || ldl < d)) return LPD_ERR_LD;
+    const size_t off_nl = round_up(size_t(n) * 4, kAlign);
+    const size_t need = off_nl + round_up(size_t(B) * 4, kAlign);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < need)
+        return LPD_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    float *nx = reinterpret_cast<float *>(workspace);
+    float *nl = reinterpret_cast<float *>(static_cast<char *>(workspace) + off_nl);
+    if (launch_sqnorm(X, n, d, ldx, nx, s) != hipSuccess) return LPD_ERR_HIP;
+    if (launch_sqnorm(L, B, d, ldl, nl, s) != hipSuccess) return LPD_ERR_HIP;
+    GemmArgs k1{};
+    k1.A = X; k1.lda = ldx;
+    k1.B = L; k1.ldb = ldl;
+    k1.C = Z; k1.ldc = ldz;
+    k1.M = int(n); k1.N = int(B); k1.K = int(d); k1.n_store = int(B);
+    k1.na = nx; k1.nb = nl;
+    k1.scale = -gamma * 1.44269504088896340736f;
+    return launch_gemm(k1, EPI_GAUSS, s) == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+}
+
+int lpd_margins(const float *G, int64_t n, int64_t r, int64_t ldg, const float *w, float *m, void *hip_stream)
+{
+    if (n < 0 || r < 0 || n > kMaxDim * 4 || r > kMaxDim) return LPD_ERR_SHAPE;
+    if (n == 0) return LPD_OK;
+    if (!m) return LPD_ERR_NULL;
+    if (r > 0 && (!G || !w)) return LPD_ERR_NULL;
+    if (ldg < r) return LPD_ERR_LD;
+    hipError_t e = launch_margins<false>(G, n, r, ldg, nullptr, w, m, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+}
+
+int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg, const int64_t *rows, int64_t n_rows,
+                     const float *w, float *m, void *hip_stream)
+{
+    if (n < 0 || r < 0 || n_rows < 0 || n > kMaxDim * 4 || r > kMaxDim || n_rows > kMaxDim * 4) return LPD_ERR_SHAPE;
+    if (n_rows == 0) return LPD_OK;
+    if (!m || !rows) return LPD_ERR_NULL;
+    if (r > 0 && (!G || !w)) return LPD_ERR_NULL;
+    if (ldg < r) return LPD_ERR_LD;
+    hipError_t e = launch_margins<true>(G, n_rows, r, ldg, rows, w, m, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,237 @@
+"""Thin ctypes binding over the C-ABI library ``liblpd.so`` (see ``include/lpd.h``).
+
+Argument marshalling only: every function takes torch tensors (device memory and
+the current stream come from PyTorch), checks dtype / device / contiguity, and
+passes raw pointers, sizes and leading dimensions to the entry point of the same
+name.  All arithmetic happens in the library's HIP kernels (or, for
+``lpd_whiten_host``, in its host routine).  There is no fallback: if the shared
+library is missing, loading fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblpd.so")
+
+_i64 = ctypes.c_int64
+_vp = ctypes.c_void_p
+_sz = ctypes.c_size_t
+
+LPD_OK = 0
+
+
+class LpdError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lib().lpd_strerror(status).decode()} (status {status})")
+
+
+class FactorProfile(ctypes.Structure):
+    _fields_ = [
+        ("launches_norms", ctypes.c_int32),
+        ("launches_kernel_block", ctypes.c_int32),
+        ("launches_whiten", ctypes.c_int32),
+        ("panel_rows", ctypes.c_int32),
+        ("ms_norms", ctypes.c_float),
+        ("ms_kernel_block", ctypes.c_float),
+        ("ms_whiten", ctypes.c_float),
+    ]
+
+
+_FACTOR_ARGS = [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _i64, _vp, _i64, _vp, _sz, _vp]
+
+SIGNATURES = {
+    "lpd_version": (ctypes.c_int, []),
+    "lpd_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "lpd_set_option": (ctypes.c_int, [ctypes.c_int, _i64]),
+    "lpd_whiten_host": (ctypes.c_int, [_vp, _i64, _i64, _i64, ctypes.c_double, ctypes.c_double, _vp, _i64, _vp,
+                                       ctypes.POINTER(_i64)]),
+    "lpd_nystrom_factor_workspace": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
+    "lpd_nystrom_factor": (ctypes.c_int, _FACTOR_ARGS),
+    "lpd_nystrom_factor_profiled": (ctypes.c_int, _FACTOR_ARGS + [ctypes.POINTER(FactorProfile)]),
+    "lpd_kernel_block": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _vp, _sz,
+                                        _vp]),
+    "lpd_margins": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "lpd_margins_rows": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
+}
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load liblpd.so (built by ``__graft_entry__.build()``); raise loudly if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} not found: the HIP library is not built. Run `python -c 'import __graft_entry__ as g; "
+                "g.build()'` at the repository root (needs hipcc); there is no CPU fallback.")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != LPD_OK:
+        raise LpdError(status, where)
+
+
+def _dev_f32(t: torch.Tensor, name: str, ndim: int) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or t.dtype != torch.float32 or t.dim() != ndim:
+        raise TypeError(f"{name}: expected a {ndim}-D float32 tensor")
+    if not t.is_cuda:
+        raise ValueError(f"{name}: expected a tensor in device memory")
+    if ndim == 2 and t.numel() > 0 and t.stride(1) != 1:
+        raise ValueError(f"{name}: rows must be contiguous (stride(1) == 1)")
+    if ndim == 1 and t.numel() > 1 and t.stride(0) != 1:
+        raise ValueError(f"{name}: must be contiguous")
+    return t
+
+
+def _ld(t: torch.Tensor) -> int:
+    return int(t.stride(0)) if t.shape[0] > 1 else max(int(t.shape[1]), 1)
+
+
+def _stream(dev: torch.device) -> int:
+    return int(torch.cuda.current_stream(dev).cuda_stream)
+
+
+def lpd_version() -> int:
+    return int(lib().lpd_version())
+
+
+LPD_OPT_GEMM_TILE = 1
+GEMM_TILES = {"auto": 0, "128x128": 1, "256x128": 2, "256x256": 3}
+
+
+def lpd_set_option(option: int, value: int) -> None:
+    """Process-wide tuning knob (see include/lpd.h)."""
+    _check(lib().lpd_set_option(int(option), int(value)), "lpd_set_option")
+
+
+def lpd_whiten_host(L: torch.Tensor, gamma: float, clip_ratio: float = 1e-10):
+    """Steps 1a-1c on the host. L: B x d float32 CPU tensor. Returns (W B x B float32 CPU, eig float64, rank)."""
+    if L.dtype != torch.float32 or L.dim() != 2 or L.is_cuda:
+        raise TypeError("L: expected a 2-D float32 CPU tensor")
+    L = L.contiguous()
+    B, d = L.shape
+    W = torch.empty((B, B), dtype=torch.float32)
+    eig = torch.empty(B, dtype=torch.float64)
+    rank = _i64(0)
+    st = lib().lpd_whiten_host(L.data_ptr(), B, d, max(d, 1), float(gamma), float(clip_ratio), W.data_ptr(),
+                               max(B, 1), eig.data_ptr(), ctypes.byref(rank))
+    _check(st, "lpd_whiten_host")
+    return W, eig, int(rank.value)
+
+
+def lpd_nystrom_factor_workspace(n: int, d: int, B: int):
+    """(recommended bytes, minimum bytes) of device scratch for a factor call of this shape."""
+    rec, mn = _sz(0), _sz(0)
+    _check(lib().lpd_nystrom_factor_workspace(n, d, B, ctypes.byref(rec), ctypes.byref(mn)),
+           "lpd_nystrom_factor_workspace")
+    return int(rec.value), int(mn.value)
+
+
+def alloc_workspace(n: int, d: int, B: int, device, nbytes: int | None = None) -> torch.Tensor:
+    """Device scratch as a uint8 tensor (torch's allocator returns 256-byte aligned blocks)."""
+    rec, mn = lpd_nystrom_factor_workspace(n, d, B)
+    nbytes = rec if nbytes is None else max(int(nbytes), mn)
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def _factor_args(X, L, gamma, W, r, G, workspace):
+    X = _dev_f32(X, "X", 2)
+    L = _dev_f32(L, "L", 2)
+    W = _dev_f32(W, "W", 2)
+    G = _dev_f32(G, "G", 2)
+    n, d = X.shape
+    B = L.shape[0]
+    if L.shape[1] != d or W.shape[1] != B or G.shape != (n, B):
+        raise ValueError("shape mismatch: X n x d, L B x d, W r x B, G n x B")
+    r = W.shape[0] if r is None else int(r)
+    if r > W.shape[0]:
+        raise ValueError("r exceeds the rows of W")
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda:
+        raise TypeError("workspace: expected a uint8 device tensor")
+    return (X.data_ptr(), n, d, _ld(X), L.data_ptr(), B, _ld(L), float(gamma), W.data_ptr(), r, _ld(W),
+            G.data_ptr(), _ld(G), workspace.data_ptr(), workspace.numel(), _stream(X.device))
+
+
+def lpd_nystrom_factor(X, L, gamma: float, W, G, workspace, r: int | None = None) -> torch.Tensor:
+    """Step 1d: G[:, :r] = K(X, L) W[:r]^T, G[:, r:] = 0. Enqueued on torch's current stream."""
+    args = _factor_args(X, L, gamma, W, r, G, workspace)
+    _check(lib().lpd_nystrom_factor(*args), "lpd_nystrom_factor")
+    return G
+
+
+def lpd_nystrom_factor_profiled(X, L, gamma: float, W, G, workspace, r: int | None = None) -> FactorProfile:
+    """Same work, blocking, returning the per-kernel HIP-event timings."""
+    args = _factor_args(X, L, gamma, W, r, G, workspace)
+    prof = FactorProfile()
+    _check(lib().lpd_nystrom_factor_profiled(*args, ctypes.byref(prof)), "lpd_nystrom_factor_profiled")
+    return prof
+
+
+def lpd_kernel_block(X, L, gamma: float, Z, workspace) -> torch.Tensor:
+    """Z = K(X, L) in full (steps 1a / 1d)."""
+    X = _dev_f32(X, "X", 2)
+    L = _dev_f32(L, "L", 2)
+    Z = _dev_f32(Z, "Z", 2)
+    n, d = X.shape
+    B = L.shape[0]
+    if L.shape[1] != d or Z.shape != (n, B):
+        raise ValueError("shape mismatch: X n x d, L B x d, Z n x B")
+    st = lib().lpd_kernel_block(X.data_ptr(), n, d, _ld(X), L.data_ptr(), B, _ld(L), float(gamma), Z.data_ptr(),
+                                _ld(Z), workspace.data_ptr(), workspace.numel(), _stream(X.device))
+    _check(st, "lpd_kernel_block")
+    return Z
+
+
+def lpd_margins(G, w, m=None, r: int | None = None) -> torch.Tensor:
+    """Step 2a for all rows: m = G[:, :r] w."""
+    G = _dev_f32(G, "G", 2)
+    w = _dev_f32(w, "w", 1)
+    n = G.shape[0]
+    r = w.shape[0] if r is None else int(r)
+    if r > w.shape[0] or r > G.shape[1]:
+        raise ValueError("r exceeds w or the columns of G")
+    if m is None:
+        m = torch.empty(n, dtype=torch.float32, device=G.device)
+    m = _dev_f32(m, "m", 1)
+    if m.shape[0] != n:
+        raise ValueError("m must have one entry per row of G")
+    _check(lib().lpd_margins(G.data_ptr(), n, r, _ld(G), w.data_ptr(), m.data_ptr(), _stream(G.device)),
+           "lpd_margins")
+    return m
+
+
+def lpd_margins_rows(G, rows, w, m=None, r: int | None = None) -> torch.Tensor:
+    """Step 2a over a list of rows (int64 device tensor)."""
+    G = _dev_f32(G, "G", 2)
+    w = _dev_f32(w, "w", 1)
+    if rows.dtype != torch.int64 or rows.dim() != 1 or not rows.is_cuda or (rows.numel() > 1 and rows.stride(0) != 1):
+        raise TypeError("rows: expected a contiguous 1-D int64 device tensor")
+    n = G.shape[0]
+    k = rows.shape[0]
+    if k > 0 and (int(rows.min()) < 0 or int(rows.max()) >= n):   # the kernel does not bounds-check
+        raise IndexError("rows: index outside [0, n)")
+    r = w.shape[0] if r is None else int(r)
+    if r > w.shape[0] or r > G.shape[1]:
+        raise ValueError("r exceeds w or the columns of G")
+    if m is None:
+        m = torch.empty(k, dtype=torch.float32, device=G.device)
+    m = _dev_f32(m, "m", 1)
+    if m.shape[0] != k:
+        raise ValueError("m must have one entry per listed row")
+    st = lib().lpd_margins_rows(G.data_ptr(), n, r, _ld(G), rows.data_ptr(), k, w.data_ptr(), m.data_ptr(),
+                                _stream(G.device))
+    _check(st, "lpd_margins_rows")
+    return m

@@ -1,0 +1,155 @@
+"""CPU-side checks of the C-ABI library: exported symbols, argument validation, host whitening.
+
+No kernel is launched here; every device entry point is only driven down its error paths, which
+return before any HIP call.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2207_01016_amd import lpd
+    return lpd.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "lpd.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(lpd_[a-z_]+)\s*\(", header))
+    assert {"lpd_nystrom_factor", "lpd_margins", "lpd_whiten_host", "lpd_kernel_block"} <= declared
+    from paper_2207_01016_amd import lpd
+    assert declared == set(lpd.SIGNATURES), declared ^ set(lpd.SIGNATURES)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_version_and_strerror(L):
+    assert L.lpd_version() >= 100
+    for st in range(-7, 1):
+        assert len(L.lpd_strerror(st)) > 0
+
+
+def test_workspace_query(L):
+    rec, mn = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    assert L.lpd_nystrom_factor_workspace(1000, 16, 128, ctypes.byref(rec), ctypes.byref(mn)) == 0
+    assert rec.value >= mn.value > 4 * (1000 + 128)
+    assert rec.value % 256 == 0
+    assert L.lpd_nystrom_factor_workspace(-1, 16, 128, ctypes.byref(rec), None) == -2
+    assert L.lpd_nystrom_factor_workspace(10, 16, 128, None, None) == -1
+    # the recommended panel never exceeds about 64 Mi kernel values plus the norms
+    assert L.lpd_nystrom_factor_workspace(2_000_000, 256, 16384, ctypes.byref(rec), ctypes.byref(mn)) == 0
+    assert rec.value < 4 * (2_000_000 + 16384 + (64 << 20) + 16384 * 300)
+
+
+def test_factor_argument_errors(L):
+    buf = (ctypes.c_float * 4096)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    f = L.lpd_nystrom_factor
+    #        X  n   d  ldx L  B  ldl gamma W  r  ldw G  ldg ws  bytes stream
+    assert f(p, 0, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, None, 0, None) == 0          # n = 0: nothing to do
+    assert f(p, 4, 4, 4, p, 0, 4, 0.5, p, 0, 1, p, 1, None, 0, None) == 0          # B = 0
+    assert f(p, -1, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, None, 0, None) == -2
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 9, 8, p, 8, None, 0, None) == -2         # r > B
+    assert f(None, 4, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, None, 0, None) == -1
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, None, 8, 8, p, 8, None, 0, None) == -1
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, 8, None, 8, None, 0, None) == -1
+    assert f(p, 4, 4, 3, p, 8, 4, 0.5, p, 8, 8, p, 8, None, 0, None) == -3         # ldx < d
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, 7, p, 8, None, 0, None) == -3         # ldw < B
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 7, None, 0, None) == -3         # ldg < B
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, None, 0, None) == -4         # no workspace
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, p, 16, None) == -4           # too small
+
+
+def test_margins_and_kernel_block_argument_errors(L):
+    buf = (ctypes.c_float * 1024)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    assert L.lpd_margins(p, 0, 8, 8, p, p, None) == 0
+    assert L.lpd_margins(p, 4, 8, 7, p, p, None) == -3
+    assert L.lpd_margins(None, 4, 8, 8, p, p, None) == -1
+    assert L.lpd_margins(p, 4, 8, 8, p, None, None) == -1
+    assert L.lpd_margins(p, 4, -8, 8, p, p, None) == -2
+    assert L.lpd_margins_rows(p, 4, 8, 8, p, 0, p, p, None) == 0
+    assert L.lpd_margins_rows(p, 4, 8, 8, None, 2, p, p, None) == -1
+    assert L.lpd_kernel_block(p, 4, 4, 4, p, 8, 4, 0.5, p, 7, p, 4096, None) == -3
+    assert L.lpd_kernel_block(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, None, 0, None) == -4
+    assert L.lpd_kernel_block(p, 0, 4, 4, p, 8, 4, 0.5, p, 8, None, 0, None) == 0
+    assert L.lpd_set_option(1, 3) == 0 and L.lpd_set_option(1, 0) == 0
+    assert L.lpd_set_option(1, 9) == -2 and L.lpd_set_option(77, 0) == -2
+
+
+def test_binding_rejects_host_tensors():
+    from paper_2207_01016_amd import lpd
+    with pytest.raises(ValueError):
+        lpd.lpd_margins(torch.zeros(4, 8), torch.zeros(8))
+    with pytest.raises(TypeError):
+        lpd.lpd_margins(torch.zeros(4, 8, dtype=torch.float64), torch.zeros(8))
+
+
+# ---------------------------------------------------------------- host whitening (steps 1a-1c)
+
+@pytest.mark.parametrize("name,B", [("tiny", 128), ("small", 200), ("digit", 97), ("cnn", 64), ("highrank", 333)])
+def test_whiten_host_against_oracle(oracle, name, B):
+    """Rotation-invariant comparison: eigenvalues, rank, W K W^T = I, and the sign convention."""
+    from paper_2207_01016_amd import lpd, workloads
+    wl = workloads.WORKLOADS[name].with_shape(n=max(2 * B, 1000), B=B)
+    X = workloads.make_X(wl)
+    Lm = X[workloads.landmark_indices(wl)].contiguous()
+    W, eig, rank = lpd.lpd_whiten_host(Lm, wl.gamma)
+    Wo, eo, ro, K = oracle.whiten(Lm.numpy(), wl.gamma, method="lapack")
+    assert rank == ro == B
+    assert np.max(np.abs(eig.numpy() - eo)) <= 1e-10 * eo[0]
+    Wd = W.double().numpy()
+    assert np.linalg.norm(Wd @ K @ Wd.T - np.eye(B)) <= 2e-6 * B
+    # eigenvalues here are simple, so rows agree with the oracle's up to fp32 rounding of W
+    gap = np.min(np.abs(np.diff(eo)))
+    if gap > 1e-6:
+        assert np.max(np.abs(Wd - Wo)) <= 1e-5 * np.max(np.abs(Wo)) / min(1.0, gap * 1e3)
+    for j in range(B):
+        assert Wd[j, np.argmax(np.abs(Wd[j]))] > 0.0
+
+
+def test_whiten_host_degenerate_cases(oracle):
+    from paper_2207_01016_amd import lpd
+    g = torch.Generator().manual_seed(5)
+    X = torch.randn((40, 6), generator=g)
+    # gamma = 0: rank one, W[0] = 1/B
+    W, eig, rank = lpd.lpd_whiten_host(X[:9].contiguous(), 0.0)
+    assert rank == 1
+    assert abs(eig[0].item() - 9.0) < 1e-12
+    assert torch.allclose(W[0], torch.full((9,), 1.0 / 9.0), atol=1e-7) and torch.all(W[1:] == 0)
+    # duplicated landmark: one component dropped, remaining ones still whiten K
+    Ld = torch.cat([X[:12], X[3:4]]).contiguous()
+    W, eig, rank = lpd.lpd_whiten_host(Ld, 0.15)
+    assert rank == 12 and abs(eig[-1].item()) < 1e-12
+    K = oracle.kernel_block(Ld.numpy(), Ld.numpy(), 0.15)
+    Wd = W.double().numpy()[:12]
+    assert np.linalg.norm(Wd @ K @ Wd.T - np.eye(12)) < 1e-5
+    assert torch.all(W[12:] == 0)
+    # B = 1 and B = 2
+    W, eig, rank = lpd.lpd_whiten_host(X[:1].contiguous(), 0.3)
+    assert rank == 1 and W.item() == 1.0
+    W, eig, rank = lpd.lpd_whiten_host(torch.tensor([[0.0], [1.0]]), float(np.log(2.0)))
+    assert rank == 2
+    assert torch.allclose(eig, torch.tensor([1.5, 0.5], dtype=torch.float64), atol=1e-14)
+    assert torch.allclose(W, torch.tensor([[3 ** -0.5, 3 ** -0.5], [1.0, -1.0]]), atol=1e-7)
+    # B = 0
+    W, eig, rank = lpd.lpd_whiten_host(torch.zeros((0, 3)), 0.3)
+    assert rank == 0 and W.shape == (0, 0)
+
+
+def test_whiten_host_errors(L):
+    r = ctypes.c_int64(0)
+    buf = (ctypes.c_float * 64)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    assert L.lpd_whiten_host(p, 4, 2, 1, 0.5, 1e-10, p, 4, None, ctypes.byref(r)) == -3
+    assert L.lpd_whiten_host(p, 4, 2, 2, 0.5, 1e-10, None, 4, None, ctypes.byref(r)) == -1
+    assert L.lpd_whiten_host(p, 4, 2, 2, 0.5, 1e-10, p, 4, None, None) == -1
+    assert L.lpd_whiten_host(p, -4, 2, 2, 0.5, 1e-10, p, 4, None, ctypes.byref(r)) == -2

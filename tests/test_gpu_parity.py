@@ -1,0 +1,281 @@
+"""GPU parity: the HIP path, called through the C ABI, against the double-precision CPU oracle.
+
+Tolerances (relative Frobenius error over the compared rows):
+    factor G   <= 1e-4      margins  <= 1e-5
+The factor is compared with ONE shared W (the fp32 W handed to the GPU is the W the oracle uses):
+the eigenvector basis is a convention, the product G = Z W^T is not.  Margins are a function of G:
+the oracle sweeps the same fp32 G buffer the GPU kernel read.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+TOL_G = 1e-4
+TOL_M = 1e-5
+
+
+def relfro(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch.device("cuda:0")
+
+
+@pytest.fixture(scope="module")
+def lpd():
+    from paper_2207_01016_amd import lpd as mod
+    mod.lib()   # fails loudly when the HIP library is not built
+    return mod
+
+
+@pytest.fixture(scope="module")
+def wls():
+    from paper_2207_01016_amd import workloads
+    return workloads
+
+
+def _prepare(lpd, wls, wl, dev):
+    X = wls.make_X(wl, dev)
+    idx = wls.landmark_indices(wl)
+    L = X[idx.to(dev)].contiguous()
+    W, eig, rank = lpd.lpd_whiten_host(L.cpu(), wl.gamma)
+    return X, idx, L, W, eig, rank
+
+
+def _factor(lpd, X, L, gamma, W, rank, ws_bytes=None):
+    n, d = X.shape
+    B = L.shape[0]
+    G = torch.full((n, B), float("nan"), dtype=torch.float32, device=X.device)
+    ws = lpd.alloc_workspace(n, d, B, X.device, ws_bytes)
+    lpd.lpd_nystrom_factor(X, L, gamma, W.to(X.device), G, ws, r=rank)
+    torch.cuda.synchronize()
+    return G
+
+
+# ---------------------------------------------------------------- kernel block (GEMM-1 + exp epilogue)
+
+@pytest.mark.parametrize("n,d,B,gamma", [
+    (300, 20, 70, 0.05),       # nothing a multiple of a tile, d % 4 == 0
+    (257, 19, 33, 0.07),       # d % 4 != 0: element-wise loader
+    (1, 5, 1, 0.3),
+    (513, 128, 260, 1.0 / 128),
+    (130, 1, 129, 0.5),
+])
+@pytest.mark.parametrize("tile", ["128x128", "256x128", "256x256"])
+def test_kernel_block_matches_oracle(lpd, oracle, dev, n, d, B, gamma, tile):
+    g = torch.Generator().manual_seed(1000 + n + d + B)
+    X = torch.randn((n, d), generator=g).to(dev)
+    L = torch.cat([X[: min(B, n) // 2].cpu(), torch.randn((B - min(B, n) // 2, d), generator=g)]).to(dev)
+    Z = torch.full((n, B), float("nan"), dtype=torch.float32, device=dev)
+    ws = torch.empty(4 * (n + B) + 1024, dtype=torch.uint8, device=dev)
+    lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, lpd.GEMM_TILES[tile])
+    try:
+        lpd.lpd_kernel_block(X, L, gamma, Z, ws)
+        torch.cuda.synchronize()
+    finally:
+        lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, 0)
+    ref = oracle.kernel_block(X.cpu().numpy(), L.cpu().numpy(), gamma)
+    Zh = Z.cpu().numpy()
+    assert np.all(np.isfinite(Zh))
+    assert np.all(Zh <= 1.0) and np.all(Zh >= 0.0)
+    assert relfro(Zh, ref) <= 1e-5
+    assert np.max(np.abs(Zh - ref)) <= 2e-5
+
+
+def test_kernel_block_strided_operands(lpd, oracle, dev):
+    """Leading dimensions larger than the rows, including ones that break 16-byte alignment."""
+    g = torch.Generator().manual_seed(7)
+    for ldx, ldl, ldz in [(24, 28, 80), (21, 23, 71)]:
+        Xs = torch.randn((200, ldx), generator=g).to(dev)
+        Ls = torch.randn((70, ldl), generator=g).to(dev)
+        Zs = torch.zeros((200, ldz), dtype=torch.float32, device=dev)
+        ws = torch.empty(4096, dtype=torch.uint8, device=dev)
+        lpd.lpd_kernel_block(Xs[:, :20], Ls[:, :20], 0.04, Zs[:, :70], ws)
+        torch.cuda.synchronize()
+        ref = oracle.kernel_block(Xs[:, :20].cpu().numpy(), Ls[:, :20].cpu().numpy(), 0.04)
+        assert relfro(Zs[:, :70].cpu().numpy(), ref) <= 1e-5
+        assert torch.all(Zs[:, 70:] == 0)           # padding columns untouched
+
+
+# ---------------------------------------------------------------- factor on the workload recipes
+
+def test_factor_tiny_all_rows(lpd, wls, oracle, dev):
+    wl = wls.WORKLOADS["tiny"]
+    X, idx, L, W, eig, rank = _prepare(lpd, wls, wl, dev)
+    assert rank == wl.B
+    G = _factor(lpd, X, L, wl.gamma, W, rank)
+    ref = oracle.nystrom_factor(X.cpu().numpy(), L.cpu().numpy(), wl.gamma, W.numpy())
+    Gh = G.cpu().numpy()
+    assert relfro(Gh, ref) <= TOL_G
+    # projection bound: ||g_i||^2 <= 1 on every row, = 1 on landmark rows
+    sq = (Gh.astype(np.float64) ** 2).sum(axis=1)
+    assert np.all(sq <= 1.0 + 1e-4)
+    assert np.allclose(sq[idx.numpy()], 1.0, atol=1e-4)
+    # G_L G_L^T reproduces K_LL
+    GL = Gh[idx.numpy()].astype(np.float64)
+    K = oracle.kernel_block(L.cpu().numpy(), L.cpu().numpy(), wl.gamma)
+    assert relfro(GL @ GL.T, K) <= 1e-4
+
+
+@pytest.mark.parametrize("name,n,B", [
+    ("small", 20_000, 1024),
+    ("digit", 5_000, 700),
+    ("cnn", 3_000, 520),
+    ("highrank", 6_000, 1111),
+])
+@pytest.mark.parametrize("tile", ["128x128", "256x256"])
+def test_factor_scaled_workloads_sampled_rows(lpd, wls, oracle, dev, name, n, B, tile):
+    """Recipe-shaped inputs with fewer rows / landmarks; oracle on a row sample that includes landmarks."""
+    wl = wls.WORKLOADS[name].with_shape(n=n, B=B)
+    X, idx, L, W, eig, rank = _prepare(lpd, wls, wl, dev)
+    lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, lpd.GEMM_TILES[tile])
+    try:
+        # a workspace of three 256-row panels' worth forces several panels and a ragged last one
+        _, mn = lpd.lpd_nystrom_factor_workspace(n, wl.d, B)
+        G = _factor(lpd, X, L, wl.gamma, W, rank, ws_bytes=mn * 3)
+    finally:
+        lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, 0)
+    rows = wls.sample_rows(wl, 600, include=idx[:64])
+    ref = oracle.nystrom_factor(X[rows.to(dev)].cpu().numpy(), L.cpu().numpy(), wl.gamma, W.numpy(), r=rank)
+    Gs = G[rows.to(dev)].cpu().numpy()
+    assert np.all(np.isfinite(Gs))
+    assert relfro(Gs[:, :rank], ref) <= TOL_G
+    sq = (G.double() ** 2).sum(dim=1)
+    assert float(sq.max()) <= 1.0 + 1e-4
+    assert torch.allclose(sq[idx.to(dev)], torch.ones(B, dtype=torch.float64, device=dev), atol=1e-4)
+
+
+def test_factor_rank_deficient_zero_fills(lpd, wls, oracle, dev):
+    """Duplicated landmarks: dropped components give r < B; columns r..B-1 of G are exact zeros."""
+    wl = wls.WORKLOADS["tiny"].with_shape(n=900, B=150)
+    X = wls.make_X(wl, dev)
+    L = torch.cat([X[:140], X[5:15]]).contiguous()         # 10 duplicates
+    W, eig, rank = lpd.lpd_whiten_host(L.cpu(), wl.gamma)
+    assert rank == 140
+    G = _factor(lpd, X, L, wl.gamma, W, rank)
+    ref = oracle.nystrom_factor(X.cpu().numpy(), L.cpu().numpy(), wl.gamma, W.numpy(), r=rank)
+    Gh = G.cpu().numpy()
+    assert relfro(Gh[:, :rank], ref) <= TOL_G
+    assert np.all(Gh[:, rank:] == 0.0)
+    # r = 0 writes only zeros
+    G0 = _factor(lpd, X, L, wl.gamma, W, 0)
+    assert torch.all(G0 == 0)
+
+
+def test_factor_gamma_zero(lpd, wls, dev):
+    wl = wls.WORKLOADS["tiny"].with_shape(n=500, B=40)
+    X = wls.make_X(wl, dev)
+    L = X[:40].contiguous()
+    W, eig, rank = lpd.lpd_whiten_host(L.cpu(), 0.0)
+    assert rank == 1
+    G = _factor(lpd, X, L, 0.0, W, rank)
+    assert torch.allclose(G[:, 0], torch.ones(500, device=dev), atol=1e-6)
+    assert torch.all(G[:, 1:] == 0)
+
+
+def test_factor_is_deterministic_and_tile_independent(lpd, wls, dev):
+    wl = wls.WORKLOADS["small"].with_shape(n=3000, B=384)
+    X, idx, L, W, eig, rank = _prepare(lpd, wls, wl, dev)
+    outs = {}
+    for tile in ["128x128", "256x128", "256x256"]:
+        lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, lpd.GEMM_TILES[tile])
+        try:
+            a = _factor(lpd, X, L, wl.gamma, W, rank)
+            b = _factor(lpd, X, L, wl.gamma, W, rank)
+        finally:
+            lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, 0)
+        assert torch.equal(a, b), tile                 # bitwise: no atomics, fixed summation order
+        outs[tile] = a
+    ref = outs["128x128"].double()
+    for tile, a in outs.items():
+        assert float((a.double() - ref).norm() / ref.norm()) <= 1e-6, tile
+
+
+def test_factor_profiled_matches_plain(lpd, wls, dev):
+    wl = wls.WORKLOADS["small"].with_shape(n=5000, B=256)
+    X, idx, L, W, eig, rank = _prepare(lpd, wls, wl, dev)
+    G1 = _factor(lpd, X, L, wl.gamma, W, rank)
+    G2 = torch.empty_like(G1)
+    ws = lpd.alloc_workspace(wl.n, wl.d, wl.B, dev)
+    prof = lpd.lpd_nystrom_factor_profiled(X, L, wl.gamma, W.to(dev), G2, ws, r=rank)
+    assert torch.equal(G1, G2)
+    assert prof.launches_whiten == prof.launches_kernel_block >= 1
+    assert prof.ms_whiten > 0 and prof.ms_kernel_block > 0
+
+
+def test_factor_zero_sizes(lpd, dev):
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+    X = torch.zeros((0, 8), device=dev)
+    L = torch.zeros((4, 8), device=dev)
+    W = torch.zeros((4, 4), device=dev)
+    G = torch.zeros((0, 4), device=dev)
+    lpd.lpd_nystrom_factor(X, L, 0.5, W, G, ws)
+    torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------- margins (GEMV sweep)
+
+@pytest.mark.parametrize("n,r,ld", [
+    (2000, 128, 128),      # tiny's shape: 32 lanes per row
+    (777, 1024, 1024),     # 64 lanes per row
+    (1000, 64, 64),        # 16 lanes per row
+    (513, 20, 20),         # 8 lanes per row
+    (300, 1000, 1040),     # ld > r, r % 4 == 0
+    (300, 1001, 1044),     # ragged tail columns
+    (301, 517, 517),       # ld % 4 != 0: scalar loader
+    (5, 3, 3),
+    (64, 4100, 4100),
+])
+def test_margins_match_oracle(lpd, oracle, dev, n, r, ld):
+    g = torch.Generator().manual_seed(n * 31 + r)
+    Gfull = torch.randn((n, ld), generator=g).to(dev)
+    w = (torch.randn(r, generator=g) / r ** 0.5).to(dev)
+    m = lpd.lpd_margins(Gfull[:, :r] if ld > r else Gfull, w, r=r)
+    torch.cuda.synchronize()
+    ref = oracle.margins(Gfull.cpu().numpy(), w.cpu().numpy(), r=r)
+    assert relfro(m.cpu().numpy(), ref) <= TOL_M
+
+
+def test_margins_unit_vector_and_rows(lpd, oracle, dev):
+    g = torch.Generator().manual_seed(99)
+    G = torch.randn((1500, 300), generator=g).to(dev)
+    e = torch.zeros(300, device=dev)
+    e[123] = 1.0
+    assert torch.equal(lpd.lpd_margins(G, e), G[:, 123])
+    w = torch.randn(300, generator=g).to(dev)
+    rows = torch.randperm(1500, generator=g)[:400].to(dev)
+    mr = lpd.lpd_margins_rows(G, rows, w)
+    mall = lpd.lpd_margins(G, w)
+    torch.cuda.synchronize()
+    assert torch.equal(mr, mall[rows])
+    ref = oracle.margins(G[rows].cpu().numpy(), w.cpu().numpy())
+    assert relfro(mr.cpu().numpy(), ref) <= TOL_M
+    with pytest.raises(IndexError):
+        lpd.lpd_margins_rows(G, torch.tensor([0, 1500], device=dev), w)
+
+
+def test_margins_on_factor_output_tiny(lpd, wls, oracle, dev):
+    """Whole path on the tiny workload: factor, then sweep; plus the chained error as information."""
+    wl = wls.WORKLOADS["tiny"]
+    X, idx, L, W, eig, rank = _prepare(lpd, wls, wl, dev)
+    G = _factor(lpd, X, L, wl.gamma, W, rank)
+    w = wls.make_w(wl).to(dev)
+    m = lpd.lpd_margins(G, w, r=rank)
+    torch.cuda.synchronize()
+    ref = oracle.margins(G.cpu().numpy(), w.cpu().numpy(), r=rank)
+    assert relfro(m.cpu().numpy(), ref) <= TOL_M
+    # w = G_a^T for a landmark row returns the kernel column Z[:, a]
+    a = 17
+    ma = lpd.lpd_margins(G, G[idx[a]].contiguous(), r=rank)
+    Z = oracle.kernel_block(X.cpu().numpy(), L.cpu().numpy(), wl.gamma)
+    assert np.max(np.abs(ma.cpu().numpy() - Z[:, a])) <= 2e-4
+    chained = oracle.margins_f64(oracle.nystrom_factor(X.cpu().numpy(), L.cpu().numpy(), wl.gamma, W.numpy()),
+                                 w.cpu().numpy().astype(np.float64))
+    print("chained rel error (oracle G -> oracle m vs GPU G -> GPU m):", relfro(m.cpu().numpy(), chained))

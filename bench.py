@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: Nystrom factor G = K(X, L) W^T followed by the margin sweep G w.
+
+One "step" is one pass of the whole path over the workload: squared norms, kernel block panels
+(distance contraction with fused exp), whitening product, then the sweep over all rows of G.
+Inputs (X, L, W, w) are resident in HBM before the timed region; the one-off host preparation of W
+(landmark kernel matrix + eigendecomposition) is timed separately and reported, not counted.
+
+Prints ONE JSON line.  `value` is rows per second through the whole path (factor + sweep).
+`roofline` describes the dominant kernel (the whitening product) from HIP events recorded on the
+launch stream around every launch inside the timed steps; `roofline_sweep` does the same for the
+margin sweep against HBM bandwidth; `cpu_baseline` is the double-precision oracle timed on the host
+cores on a bounded row sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP32_MFMA_PEAK_TFLOPS = 157.3   # 256 CU x 256 FLOP/clk x 2.4 GHz
+HBM_PEAK_GBPS = 8000.0
+
+# HBM bytes per whitening-product launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/), keyed by workload; None where not collected.
+MEASURED_TRAFFIC = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="digit", choices=["tiny", "small", "digit", "cnn", "highrank"])
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tile", default="auto", choices=["auto", "128x128", "256x128", "256x256"])
+    ap.add_argument("--workspace-mult", type=float, default=1.0)
+    ap.add_argument("--random-w", action="store_true",
+                    help="skip the host eigendecomposition and use a random W (tuning only; marks the line invalid)")
+    return ap.parse_args()
+
+
+def cpu_baseline(orc, wl, Xs, L, W, w, target_s):
+    """Oracle (factor rows + margins over them) on a row sample sized for about `target_s` seconds."""
+    import numpy as np
+    probe = min(32, Xs.shape[0])
+    t0 = time.perf_counter()
+    orc.nystrom_factor(Xs[:probe], L, wl.gamma, W)
+    per_row = (time.perf_counter() - t0) / probe
+    m = int(max(probe, min(Xs.shape[0], target_s / max(per_row, 1e-9))))
+    t0 = time.perf_counter()
+    G = orc.nystrom_factor(Xs[:m], L, wl.gamma, W)
+    t_factor = time.perf_counter() - t0
+    G32 = G.astype(np.float32)
+    t0 = time.perf_counter()
+    orc.margins(G32, w)
+    t_sweep = time.perf_counter() - t0
+    flop_row = 2.0 * wl.B * (wl.d + W.shape[0])
+    return {
+        "value": m / (t_factor + t_sweep), "unit": "rows/s", "cores": orc.num_threads(), "kind": "oracle",
+        "sample": f"first {m} of {wl.n} rows of the '{wl.name}' workload (all {wl.B} landmarks, full W); "
+                  f"factor {t_factor:.2f} s + sweep {t_sweep:.4f} s in double precision",
+        "factor_gflops": m * flop_row / t_factor / 1e9,
+        "sweep_gbps": 4.0 * m * W.shape[0] / max(t_sweep, 1e-9) / 1e9,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              f"--gpus {args.gpus} is not supported. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2207_01016_amd import lpd, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(2)
+    lpd.lib()
+    dev = torch.device("cuda:0")
+    wl = workloads.WORKLOADS[args.workload]
+
+    # ---- inputs, resident in HBM
+    X = workloads.make_X(wl, dev)
+    idx = workloads.landmark_indices(wl)
+    L = X[idx.to(dev)].contiguous()
+    L_host = L.cpu()
+    t0 = time.perf_counter()
+    if args.random_w:
+        g = torch.Generator().manual_seed(1)
+        W_host = torch.randn((wl.B, wl.B), generator=g) / wl.B ** 0.5
+        rank = wl.B
+    else:
+        W_host, eig, rank = lpd.lpd_whiten_host(L_host, wl.gamma)
+    t_whiten = time.perf_counter() - t0
+    W = W_host.to(dev)
+    w = workloads.make_w(wl).to(dev)
+    G = torch.empty((wl.n, wl.B), dtype=torch.float32, device=dev)
+    m = torch.empty(wl.n, dtype=torch.float32, device=dev)
+    rec, _ = lpd.lpd_nystrom_factor_workspace(wl.n, wl.d, wl.B)
+    ws = lpd.alloc_workspace(wl.n, wl.d, wl.B, dev, int(rec * args.workspace_mult))
+    lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, lpd.GEMM_TILES[args.tile])
+
+    def step(collect):
+        prof = lpd.lpd_nystrom_factor_profiled(X, L, wl.gamma, W, G, ws, r=rank)   # blocks; events per launch
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        lpd.lpd_margins(G, w, m, r=rank)
+        e1.record()
+        if collect is not None:
+            collect.append((prof, e0, e1))
+
+    for _ in range(args.warmup):
+        step(None)
+    torch.cuda.synchronize()
+    records = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(records)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    steps = max(args.steps, 1)
+    ms_step = elapsed * 1e3 / steps
+    ms_whiten = sum(p.ms_whiten for p, _, _ in records)
+    ms_kb = sum(p.ms_kernel_block for p, _, _ in records)
+    ms_norms = sum(p.ms_norms for p, _, _ in records)
+    launches = sum(p.launches_whiten for p, _, _ in records)
+    ms_sweep = sum(a.elapsed_time(b) for _, a, b in records)
+    ms_factor = ms_whiten + ms_kb + ms_norms
+
+    flop_factor = 2.0 * wl.n * wl.B * (wl.d + rank)
+    flop_whiten_launch = 2.0 * wl.n * wl.B * rank * steps / max(launches, 1)
+    whiten_tflops = 2.0 * wl.n * wl.B * rank * steps / (ms_whiten * 1e-3) / 1e12
+    factor_tflops = flop_factor * steps / (ms_factor * 1e-3) / 1e12
+    sweep_bytes = 4.0 * wl.n * rank
+    sweep_gbps = sweep_bytes * steps / (ms_sweep * 1e-3) / 1e9
+
+    out = {
+        "metric": "nystrom_factor_plus_margin_sweep_rows_per_s",
+        "value": wl.n * steps / elapsed,
+        "unit": "rows/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic" + (" (random W: tuning run, not a valid measurement)" if args.random_w else ""),
+        "config": {"workload": wl.name, "n": wl.n, "d": wl.d, "B": wl.B, "rank": rank, "gamma": wl.gamma,
+                   "panel_rows": records[0][0].panel_rows if records else None, "gemm_tile": args.tile},
+        "factor": {"ms_per_step": ms_factor / steps, "rows_per_s": wl.n * steps / (ms_factor * 1e-3),
+                   "tflops": factor_tflops, "frac_of_fp32_mfma_peak": factor_tflops / FP32_MFMA_PEAK_TFLOPS,
+                   "ms_kernel_block": ms_kb / steps, "ms_whiten": ms_whiten / steps, "ms_norms": ms_norms / steps},
+        "sweep": {"ms_per_step": ms_sweep / steps, "gbps": sweep_gbps, "frac_of_hbm_peak": sweep_gbps / HBM_PEAK_GBPS},
+        "whiten_host_s": None if args.random_w else t_whiten,
+        "roofline": {"kernel": "gemm_nt_kernel<EPI_STORE> (whitening product Z W^T)", "bound": "mfma",
+                     "achieved": whiten_tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": whiten_tflops / FP32_MFMA_PEAK_TFLOPS,
+                     "flop_per_launch": flop_whiten_launch, "avg_launch_ms": ms_whiten / max(launches, 1),
+                     "launches": launches, "traffic": MEASURED_TRAFFIC.get(wl.name)},
+        "roofline_sweep": {"kernel": "margins_kernel", "bound": "hbm", "achieved": sweep_gbps, "peak": HBM_PEAK_GBPS,
+                           "unit": "GB/s", "frac": sweep_gbps / HBM_PEAK_GBPS, "bytes_per_launch": sweep_bytes,
+                           "avg_launch_ms": ms_sweep / steps, "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import lpd_oracle as orc
+        Xs = X[: min(wl.n, 1 << 16)].cpu().numpy()   # the baseline picks how many of these it needs
+        out["cpu_baseline"] = cpu_baseline(orc, wl, Xs, L_host.numpy(), W_host[:rank].numpy(), w[:rank].cpu().numpy(),
+                                           args.cpu_seconds)
+        out["cpu_baseline"]["gpu_over_cpu"] = out["value"] / out["cpu_baseline"]["value"]
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

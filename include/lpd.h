@@ -68,9 +68,11 @@ const char *lpd_strerror(int status);
  * shape).  Not synchronised: set them while no other call is in flight.
  *   LPD_OPT_GEMM_TILE  workgroup tile of the two MFMA products:
  *                      0 = choose by shape, 1 = 128x128, 2 = 256x128, 3 = 256x256
+ *   LPD_OPT_GEMM_PIPELINE  main-loop schedule of the MFMA products: 1 (default) =
+ *                      software-pipelined across the barrier, 0 = plain load/compute/store
  * Errors: LPD_ERR_SHAPE for an unknown option or value.
  */
-typedef enum { LPD_OPT_GEMM_TILE = 1 } lpd_option;
+typedef enum { LPD_OPT_GEMM_TILE = 1, LPD_OPT_GEMM_PIPELINE = 2 } lpd_option;
 int lpd_set_option(int option, int64_t value);
 
 /*

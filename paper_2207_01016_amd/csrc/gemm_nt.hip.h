@@ -52,7 +52,7 @@ constexpr int GEMM_LDK = GEMM_BK + 4;
 template <int BM, int BN>
 constexpr size_t gemm_lds_bytes() { return size_t(2) * (BM + BN) * GEMM_LDK * sizeof(float); }
 
-template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI>
+template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI, int PIPE>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
 {
     constexpr int BK = GEMM_BK, LDK = GEMM_LDK;
@@ -165,36 +165,99 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
     const int b_off = BM * LDK + (wn * WN + frag_row) * LDK + frag_k;
 
     const int nk = (p.K + BK - 1) / BK;
-    gload(0);
-    lstore(0);
-    __syncthreads();
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < nk;
-        if (more) gload((kt + 1) * BK);
+    if (PIPE == 0) {
+        // Plain schedule: load next tile, compute the current one, store, barrier.
+        gload(0);
+        lstore(0);
+        __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            const int cur = kt & 1;
+            const bool more = kt + 1 < nk;
+            if (more) gload((kt + 1) * BK);
 
-        const float *S = lds + cur * STAGE;
+            const float *S = lds + cur * STAGE;
 #pragma unroll
-        for (int kc = 0; kc < BK / 8; ++kc) {
-            f32x4 a[TM], b[TN];
+            for (int kc = 0; kc < BK / 8; ++kc) {
+                f32x4 a[TM], b[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    a[i] = *reinterpret_cast<const f32x4 *>(&S[a_off + i * 32 * LDK + kc * 8]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    b[j] = *reinterpret_cast<const f32x4 *>(&S[b_off + j * 32 * LDK + kc * 8]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[j][t], acc[i][j], 0, 0, 0);
+            }
+
+            if (more) lstore(cur ^ 1);
+            __syncthreads();
+        }
+    } else {
+        // Software-pipelined schedule (BK = 16 = two 8-k chunks per tile).  The barrier sits
+        // between the two chunks and operand fragments are fetched one chunk ahead, across the
+        // barrier, so a wavefront always has MFMA work queued while it waits for LDS, for global
+        // memory or for the other wavefronts:
+        //   phase A  MFMA chunk 0 of tile kt | fetch chunk 1 fragments | registers (tile kt+1) -> LDS
+        //   barrier
+        //   phase B  MFMA chunk 1 of tile kt | issue global loads of tile kt+2 | fetch chunk 0 of tile kt+1
+        // Buffer (kt+1)&1 is overwritten in phase A of iteration kt: its previous tile kt-1 was last
+        // read before the barrier of iteration kt-1, and every wavefront drains its LDS reads
+        // (s_waitcnt) before arriving at a barrier.
+        static_assert(BK == 16, "the pipelined schedule assumes two chunks per tile");
+        f32x4 a0[TM], b0[TN], a1[TM], b1[TN];
+        auto fetch = [&](f32x4(&a)[TM], f32x4(&b)[TN], int buf, int kc) {
+            const float *S = lds + buf * STAGE;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
                 a[i] = *reinterpret_cast<const f32x4 *>(&S[a_off + i * 32 * LDK + kc * 8]);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 b[j] = *reinterpret_cast<const f32x4 *>(&S[b_off + j * 32 * LDK + kc * 8]);
+        };
+        auto mma = [&](const f32x4(&a)[TM], const f32x4(&b)[TN], int t) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[j][t], acc[i][j], 0, 0, 0);
-        }
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[j][t], acc[i][j], 0, 0, 0);
+        };
 
-        if (more) lstore(cur ^ 1);
+        gload(0);
+        lstore(0);
+        if (nk > 1) gload(BK);
         __syncthreads();
+        fetch(a0, b0, 0, 0);
+
+        for (int kt = 0; kt < nk; ++kt) {
+            const int cur = kt & 1;
+            // ---- phase A
+            fetch(a1, b1, cur, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a0, b0, 0);
+            mma(a0, b0, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kt + 1 < nk) lstore(cur ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a0, b0, 2);
+            mma(a0, b0, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            // ---- phase B
+            if (kt + 2 < nk) gload((kt + 2) * BK);
+            if (kt + 1 < nk) fetch(a0, b0, cur ^ 1, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a1, b1, 0);
+            mma(a1, b1, 1);
+            mma(a1, b1, 2);
+            mma(a1, b1, 3);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     // ---- epilogue: accumulator register v of lane l is C[8*(v/4) + 4*(l/32) + v%4][l%32]

@@ -57,6 +57,7 @@ Carve carve(int64_t n, int64_t B)
 
 enum TileId { TILE_AUTO = 0, TILE_128x128 = 1, TILE_256x128 = 2, TILE_256x256 = 3 };
 
+int g_pipe_option = 1;            // lpd_set_option(LPD_OPT_GEMM_PIPELINE, ...)
 int g_tile_option = TILE_AUTO;   // lpd_set_option(LPD_OPT_GEMM_TILE, ...)
 
 int tile_choice(const GemmArgs &a)
@@ -66,11 +67,11 @@ int tile_choice(const GemmArgs &a)
     return TILE_128x128;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI>
+template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI, int PIPE>
 hipError_t launch_one(GemmArgs a, hipStream_t s)
 {
     constexpr size_t lds = gemm_lds_bytes<BM, BN>();
-    auto kern = gemm_nt_kernel<BM, BN, WGM, WGN, ALIGNED, EPI>;
+    auto kern = gemm_nt_kernel<BM, BN, WGM, WGN, ALIGNED, EPI, PIPE>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -90,11 +91,18 @@ hipError_t launch_one(GemmArgs a, hipStream_t s)
 template <int BM, int BN, int WGM, int WGN>
 hipError_t launch_tile(const GemmArgs &a, bool aligned, int epi, hipStream_t s)
 {
+    if (g_pipe_option == 0) {
+        if (epi == EPI_GAUSS)
+            return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS, 0>(a, s)
+                           : launch_one<BM, BN, WGM, WGN, false, EPI_GAUSS, 0>(a, s);
+        return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_STORE, 0>(a, s)
+                       : launch_one<BM, BN, WGM, WGN, false, EPI_STORE, 0>(a, s);
+    }
     if (epi == EPI_GAUSS)
-        return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS>(a, s)
-                       : launch_one<BM, BN, WGM, WGN, false, EPI_GAUSS>(a, s);
-    return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_STORE>(a, s)
-                   : launch_one<BM, BN, WGM, WGN, false, EPI_STORE>(a, s);
+        return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS, 1>(a, s)
+                       : launch_one<BM, BN, WGM, WGN, false, EPI_GAUSS, 1>(a, s);
+    return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_STORE, 1>(a, s)
+                   : launch_one<BM, BN, WGM, WGN, false, EPI_STORE, 1>(a, s);
 }
 
 hipError_t launch_gemm(const GemmArgs &a, int epi, hipStream_t s)
@@ -286,6 +294,10 @@ int lpd_set_option(int option, int64_t value)
 {
     if (option == LPD_OPT_GEMM_TILE && value >= TILE_AUTO && value <= TILE_256x256) {
         g_tile_option = int(value);
+        return LPD_OK;
+    }
+    if (option == LPD_OPT_GEMM_PIPELINE && (value == 0 || value == 1)) {
+        g_pipe_option = int(value);
         return LPD_OK;
     }
     return LPD_ERR_SHAPE;

@@ -109,6 +109,7 @@ def lpd_version() -> int:
 
 
 LPD_OPT_GEMM_TILE = 1
+LPD_OPT_GEMM_PIPELINE = 2
 GEMM_TILES = {"auto": 0, "128x128": 1, "256x128": 2, "256x256": 3}
 
 

@@ -166,7 +166,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
 
     const int nk = (p.K + BK - 1) / BK;
 
-    if (PIPE == 0) {
+    if constexpr (PIPE == 0) {
         // Plain schedule: load next tile, compute the current one, store, barrier.
         gload(0);
         lstore(0);
@@ -199,64 +199,129 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
             __syncthreads();
         }
     } else {
-        // Software-pipelined schedule (BK = 16 = two 8-k chunks per tile).  The barrier sits
-        // between the two chunks and operand fragments are fetched one chunk ahead, across the
-        // barrier, so a wavefront always has MFMA work queued while it waits for LDS, for global
-        // memory or for the other wavefronts:
-        //   phase A  MFMA chunk 0 of tile kt | fetch chunk 1 fragments | registers (tile kt+1) -> LDS
+        // Software-pipelined schedule for the aligned fast path (BK = 16 = two 8-k chunks per tile).
+        //
+        //   phase A  MFMA chunk 0 of tile kt | fetch chunk-1 fragments | staged registers (tile kt+1) -> LDS
         //   barrier
-        //   phase B  MFMA chunk 1 of tile kt | issue global loads of tile kt+2 | fetch chunk 0 of tile kt+1
-        // Buffer (kt+1)&1 is overwritten in phase A of iteration kt: its previous tile kt-1 was last
-        // read before the barrier of iteration kt-1, and every wavefront drains its LDS reads
-        // (s_waitcnt) before arriving at a barrier.
+        //   phase B  MFMA chunk 1 of tile kt | global loads of tile kt+2 | fetch chunk-0 fragments of tile kt+1
+        //
+        // The barrier sits between the chunks and fragments are fetched one chunk ahead, across it,
+        // so a wavefront always has MFMAs queued while LDS, global memory or the other wavefronts
+        // catch up.  A wavefront issues in order: a burst of LDS or global instructions that fills
+        // the memory queues would hold back the MFMAs behind it, so the scheduler is told to place
+        // one memory instruction per MPG MFMAs.  The loop body is branch-free: tiles past the last
+        // full one are redirected to the last full one (redundant, in-bounds, unused), global
+        // addresses are a wave-uniform base plus a per-lane 32-bit byte offset fixed before the loop.
+        // Buffer (kt+1)&1 is overwritten in phase A of iteration kt; its previous tile kt-1 was last
+        // read before the barrier of iteration kt-1, and each wavefront drains its LDS reads before a
+        // barrier.  A partial last tile (K % 16 != 0) is handled after the loop by the plain schedule.
         static_assert(BK == 16, "the pipelined schedule assumes two chunks per tile");
-        f32x4 a0[TM], b0[TN], a1[TM], b1[TN];
-        auto fetch = [&](f32x4(&a)[TM], f32x4(&b)[TN], int buf, int kc) {
-            const float *S = lds + buf * STAGE;
+        static_assert(ALIGNED, "the pipelined schedule is for the 16-byte aligned fast path");
+        constexpr int MEMOPS = TM + TN + PA + PB;
+        constexpr int MPG = (4 * TM * TN) / MEMOPS > 0 ? (4 * TM * TN) / MEMOPS : 1;
+        const int nfull = p.K / BK;
+
+        if (nfull > 0) {
+            const char *baseA = reinterpret_cast<const char *>(p.A + int64_t(m0) * p.lda);
+            const char *baseB = reinterpret_cast<const char *>(p.B + int64_t(n0) * p.ldb);
+            uint32_t oa[PA], ob[PB];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                a[i] = *reinterpret_cast<const f32x4 *>(&S[a_off + i * 32 * LDK + kc * 8]);
+            for (int q = 0; q < PA; ++q)
+                oa[q] = uint32_t(min(lrow + q * RPP, p.M - 1 - m0)) * uint32_t(p.lda) * 4u + lch * 16u;
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                b[j] = *reinterpret_cast<const f32x4 *>(&S[b_off + j * 32 * LDK + kc * 8]);
-        };
-        auto mma = [&](const f32x4(&a)[TM], const f32x4(&b)[TN], int t) {
+            for (int q = 0; q < PB; ++q)
+                ob[q] = uint32_t(min(lrow + q * RPP, p.N - 1 - n0)) * uint32_t(p.ldb) * 4u + lch * 16u;
+            auto gload_full = [&](int tile) {
+                const char *pa = baseA + size_t(tile) * (BK * 4);
+                const char *pb = baseB + size_t(tile) * (BK * 4);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int q = 0; q < PA; ++q) ra[q] = *reinterpret_cast<const f32x4 *>(pa + oa[q]);
+#pragma unroll
+                for (int q = 0; q < PB; ++q) rb[q] = *reinterpret_cast<const f32x4 *>(pb + ob[q]);
+            };
+            f32x4 a0[TM], b0[TN], a1[TM], b1[TN];
+            auto fetch = [&](f32x4(&a)[TM], f32x4(&b)[TN], int buf, int kc) {
+                const float *S = lds + buf * STAGE;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    a[i] = *reinterpret_cast<const f32x4 *>(&S[a_off + i * 32 * LDK + kc * 8]);
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[j][t], acc[i][j], 0, 0, 0);
-        };
+                    b[j] = *reinterpret_cast<const f32x4 *>(&S[b_off + j * 32 * LDK + kc * 8]);
+            };
+            auto mma = [&](const f32x4(&a)[TM], const f32x4(&b)[TN]) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[j][t], acc[i][j], 0, 0, 0);
+            };
 
-        gload(0);
-        lstore(0);
-        if (nk > 1) gload(BK);
-        __syncthreads();
-        fetch(a0, b0, 0, 0);
-
-        for (int kt = 0; kt < nk; ++kt) {
-            const int cur = kt & 1;
-            // ---- phase A
-            fetch(a1, b1, cur, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            mma(a0, b0, 0);
-            mma(a0, b0, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            if (kt + 1 < nk) lstore(cur ^ 1);
-            __builtin_amdgcn_sched_barrier(0);
-            mma(a0, b0, 2);
-            mma(a0, b0, 3);
-            __builtin_amdgcn_sched_barrier(0);
+            gload_full(0);
+            lstore(0);
+            gload_full(min(1, nfull - 1));
             __syncthreads();
-            // ---- phase B
-            if (kt + 2 < nk) gload((kt + 2) * BK);
-            if (kt + 1 < nk) fetch(a0, b0, cur ^ 1, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            mma(a1, b1, 0);
-            mma(a1, b1, 1);
-            mma(a1, b1, 2);
-            mma(a1, b1, 3);
-            __builtin_amdgcn_sched_barrier(0);
+            fetch(a0, b0, 0, 0);
+
+            for (int kt = 0; kt < nfull; ++kt) {
+                const int cur = kt & 1;
+                // ---- phase A
+                fetch(a1, b1, cur, 1);
+                mma(a0, b0);
+                lstore(cur ^ 1);
+#pragma unroll
+                for (int g = 0; g < TM + TN; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                    __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0); // MPG MFMAs
+                }
+#pragma unroll
+                for (int g = 0; g < PA + PB; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
+                    __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0);
+                }
+                __syncthreads();
+                // ---- phase B
+                gload_full(min(kt + 2, nfull - 1));
+                fetch(a0, b0, cur ^ 1, 0);
+                mma(a1, b1);
+#pragma unroll
+                for (int g = 0; g < PA + PB; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+                    __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0);
+                }
+#pragma unroll
+                for (int g = 0; g < TM + TN; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0);
+                }
+            }
+            __syncthreads();
+        }
+        if (nfull < nk) {
+            // partial last tile, zero-filled past K
+            gload(nfull * BK);
+            lstore(0);
+            __syncthreads();
+            const float *S = lds;
+#pragma unroll
+            for (int kc = 0; kc < BK / 8; ++kc) {
+                f32x4 a[TM], b[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    a[i] = *reinterpret_cast<const f32x4 *>(&S[a_off + i * 32 * LDK + kc * 8]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    b[j] = *reinterpret_cast<const f32x4 *>(&S[b_off + j * 32 * LDK + kc * 8]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[j][t], acc[i][j], 0, 0, 0);
+            }
         }
     }
 

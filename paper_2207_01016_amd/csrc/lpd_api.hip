@@ -63,8 +63,11 @@ int g_tile_option = TILE_AUTO;   // lpd_set_option(LPD_OPT_GEMM_TILE, ...)
 int tile_choice(const GemmArgs &a)
 {
     if (g_tile_option != TILE_AUTO) return g_tile_option;
-    (void)a;
-    return TILE_128x128;
+    // 256x256 tiles (8 wavefronts, one workgroup per CU) halve the L2 traffic per FLOP; they pay
+    // off once the contraction is long enough to amortise their larger prologue and epilogue and
+    // there are enough of them to give every CU at least one.  Measured cross-over: K about 2048.
+    const int64_t big = int64_t((a.M + 255) / 256) * ((a.n_store + 255) / 256);
+    return (big >= 256 && a.K >= 2048) ? TILE_256x256 : TILE_128x128;
 }
 
 template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI, int PIPE>
@@ -91,26 +94,26 @@ hipError_t launch_one(GemmArgs a, hipStream_t s)
 template <int BM, int BN, int WGM, int WGN>
 hipError_t launch_tile(const GemmArgs &a, bool aligned, int epi, hipStream_t s)
 {
-    if (g_pipe_option == 0) {
-        if (epi == EPI_GAUSS)
-            return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS, 0>(a, s)
-                           : launch_one<BM, BN, WGM, WGN, false, EPI_GAUSS, 0>(a, s);
-        return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_STORE, 0>(a, s)
-                       : launch_one<BM, BN, WGM, WGN, false, EPI_STORE, 0>(a, s);
+    // The pipelined schedule needs the aligned fast path and per-lane byte offsets inside one
+    // tile strip that fit 32 bits.
+    const bool pipe = g_pipe_option != 0 && aligned && int64_t(BM) * a.lda * 4 < (int64_t(1) << 31) &&
+                      int64_t(BN) * a.ldb * 4 < (int64_t(1) << 31);
+    if (epi == EPI_GAUSS) {
+        if (pipe) return launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS, 1>(a, s);
+        return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS, 0>(a, s)
+                       : launch_one<BM, BN, WGM, WGN, false, EPI_GAUSS, 0>(a, s);
     }
-    if (epi == EPI_GAUSS)
-        return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS, 1>(a, s)
-                       : launch_one<BM, BN, WGM, WGN, false, EPI_GAUSS, 1>(a, s);
-    return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_STORE, 1>(a, s)
-                   : launch_one<BM, BN, WGM, WGN, false, EPI_STORE, 1>(a, s);
+    if (pipe) return launch_one<BM, BN, WGM, WGN, true, EPI_STORE, 1>(a, s);
+    return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_STORE, 0>(a, s)
+                   : launch_one<BM, BN, WGM, WGN, false, EPI_STORE, 0>(a, s);
 }
 
 hipError_t launch_gemm(const GemmArgs &a, int epi, hipStream_t s)
 {
     const bool aligned = aligned16(a.A) && aligned16(a.B) && a.lda % 4 == 0 && a.ldb % 4 == 0 && a.K % 4 == 0;
     switch (tile_choice(a)) {
-    case TILE_256x256: return launch_tile<256, 256, 2, 2>(a, aligned, epi, s);
-    case TILE_256x128: return launch_tile<256, 128, 2, 2>(a, aligned, epi, s);
+    case TILE_256x256: return launch_tile<256, 256, 4, 2>(a, aligned, epi, s);
+    case TILE_256x128: return launch_tile<256, 128, 4, 2>(a, aligned, epi, s);
     default: return launch_tile<128, 128, 2, 2>(a, aligned, epi, s);
     }
 }

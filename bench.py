@@ -29,7 +29,10 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per whitening-product launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/), keyed by workload; None where not collected.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/factor_and_sweep_cnn_hbm_traffic.txt: FETCH_SIZE 1.7087e6 KiB x 2.0 + WRITE_SIZE 2.5284e5 KiB x 1.0
+    "cnn": 1.7087e6 * 1024 * 2.0 + 2.5284e5 * 1024 * 1.0,
+}
 
 
 def parse_args():
@@ -37,7 +40,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="digit", choices=["tiny", "small", "digit", "cnn", "highrank"])
+    ap.add_argument("--workload", default="cnn", choices=["tiny", "small", "digit", "cnn", "highrank"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", default="auto", choices=["auto", "128x128", "256x128", "256x256"])

@@ -13,6 +13,8 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <numeric>
 #include <vector>
@@ -348,12 +350,22 @@ extern "C" int lpd_whiten_host(const float *L_host, int64_t B, int64_t d, int64_
     if (ldw < B || (d > 0 && ldl < d)) return LPD_ERR_LD;
 
     const int64_t n = B;
+    const char *venv = std::getenv("LPD_VERBOSE");      // progress lines on stderr for long runs
+    const bool verbose = venv && venv[0] == '1';
+    auto say = [&](const char *what) {
+        if (verbose) { std::fprintf(stderr, "[lpd_whiten_host B=%lld] %s\n", (long long)n, what); std::fflush(stderr); }
+    };
     std::vector<double> A(size_t(n) * n), Zt(size_t(n) * n, 0.0), dg(n), e(n), tau(n);
+    say("landmark kernel matrix");
     landmark_kernel(L_host, n, d, ldl, gamma, A.data());
+    say("tridiagonalisation");
     tridiagonalise(A.data(), n, dg.data(), e.data(), tau.data());
     for (int64_t i = 0; i < n; ++i) Zt[i * n + i] = 1.0;
+    say("QL iteration");
     if (!tridiag_ql(dg.data(), e.data(), n, Zt.data())) return LPD_ERR_NUMERIC;
+    say("back-transformation");
     back_transform(A.data(), tau.data(), n, Zt.data());
+    say("ordering and scaling");
 
     std::vector<int64_t> ord(n);
     std::iota(ord.begin(), ord.end(), int64_t(0));

@@ -43,9 +43,11 @@ Carve carve(int64_t n, int64_t B)
     c.off_nl = round_up(size_t(n) * 4, kAlign);
     c.off_z = c.off_nl + round_up(size_t(B) * 4, kAlign);
     c.min_rows = std::min<int64_t>(n, 256);
-    // recommended panel: about 64 Mi elements of Z, a whole number of 256-row tiles
-    int64_t rows = (int64_t(64) << 20) / std::max<int64_t>(c.ldz, 1);
-    rows = std::max<int64_t>(256, rows / 256 * 256);
+    // recommended panel: about 64 Mi kernel values.  Rows = 64 Mi / B rounded to 256 makes the
+    // 256x256 tile count of a panel a multiple of the 256 CUs whenever B is a power of two
+    // (B >= 256), so the last round of workgroups of a launch is a full one.
+    int64_t rows = (int64_t(64) << 20) / std::max<int64_t>(B, 1);
+    rows = std::max<int64_t>(256, (rows + 128) / 256 * 256);
     c.rec_rows = std::min<int64_t>(rows, (n + 255) / 256 * 256);
     c.rec_rows = std::max<int64_t>(c.rec_rows, c.min_rows);
     c.min_bytes = c.off_z + round_up(size_t(c.min_rows) * c.ldz * 4, kAlign);

@@ -25,6 +25,21 @@ namespace {
 
 constexpr int NB = 32;   // Householder panel width
 
+bool g_verbose = false;  // LPD_VERBOSE=1: progress lines on stderr (long runs are otherwise silent for minutes)
+
+void progress(const char *phase, int64_t done, int64_t total)
+{
+    static int last_decile = -1;
+    if (!g_verbose || total <= 0) return;
+    const int decile = int(done * 10 / total);
+    if (done == 0) last_decile = -1;
+    if (decile != last_decile) {
+        last_decile = decile;
+        std::fprintf(stderr, "[lpd_whiten_host] %s %d%%\n", phase, decile * 10);
+        std::fflush(stderr);
+    }
+}
+
 inline double sq(double x) { return x * x; }
 
 // ---- step 1a: K[a,b] = exp(-gamma ||l_a - l_b||^2), direct differences, full symmetric storage
@@ -57,6 +72,7 @@ void tridiagonalise(double *A, int64_t n, double *dg, double *e, double *tau)
     std::vector<double> p(n), t1(NB), t2(NB);
 
     for (int64_t k0 = 0; k0 < n - 2; k0 += NB) {
+        progress("tridiagonalisation", k0, n);
         const int nb = int(std::min<int64_t>(NB, n - 2 - k0));
         for (int i = 0; i < nb; ++i) {
             const int64_t j = k0 + i;
@@ -211,6 +227,7 @@ bool tridiag_ql(double *dg, double *e, int64_t n, double *Zt)
     cs.reserve(size_t(BATCH) * 2 * n);
     const double eps = 2.220446049250313e-16;
     for (int64_t l = 0; l < n; ++l) {
+        progress("QL iteration", l, n);
         int iter = 0;
         while (true) {
             int64_t m = l;
@@ -277,6 +294,7 @@ void back_transform(const double *A, const double *tau, int64_t n, double *Zt)
     std::vector<double> T(NB * NB);
     constexpr int64_t RB = 16;                  // rows of Zt per task
     for (int64_t pi = npanel - 1; pi >= 0; --pi) {
+        progress("back-transformation", npanel - 1 - pi, npanel);
         const int64_t k0 = pi * NB;
         const int nb = int(std::min<int64_t>(NB, nref - k0));
         const int64_t c0 = k0 + 1;              // first column any reflector of the panel touches
@@ -351,9 +369,9 @@ extern "C" int lpd_whiten_host(const float *L_host, int64_t B, int64_t d, int64_
 
     const int64_t n = B;
     const char *venv = std::getenv("LPD_VERBOSE");      // progress lines on stderr for long runs
-    const bool verbose = venv && venv[0] == '1';
+    g_verbose = venv && venv[0] == '1';
     auto say = [&](const char *what) {
-        if (verbose) { std::fprintf(stderr, "[lpd_whiten_host B=%lld] %s\n", (long long)n, what); std::fflush(stderr); }
+        if (g_verbose) { std::fprintf(stderr, "[lpd_whiten_host B=%lld] %s\n", (long long)n, what); std::fflush(stderr); }
     };
     std::vector<double> A(size_t(n) * n), Zt(size_t(n) * n, 0.0), dg(n), e(n), tau(n);
     say("landmark kernel matrix");

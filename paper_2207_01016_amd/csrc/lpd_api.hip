@@ -142,13 +142,13 @@ hipError_t launch_sqnorm(const float *X, int64_t n, int64_t d, int64_t ldx, floa
     return hipGetLastError();
 }
 
-template <int LPR, bool INDEXED>
+template <int LPR, bool INDEXED, int ROWS>
 hipError_t launch_margins_lpr(const float *G, int64_t n_out, int r, int64_t ldg, const int64_t *rows,
                               const float *w, float *m, bool vec, hipStream_t s)
 {
-    const unsigned grid = row_grid(n_out, 256 / LPR);
-    if (vec) hipLaunchKernelGGL((margins_kernel<LPR, true, INDEXED>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m);
-    else hipLaunchKernelGGL((margins_kernel<LPR, false, INDEXED>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m);
+    const unsigned grid = row_grid(n_out, 256 / LPR * ROWS);
+    if (vec) hipLaunchKernelGGL((margins_kernel<LPR, true, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m);
+    else hipLaunchKernelGGL((margins_kernel<LPR, false, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m);
     return hipGetLastError();
 }
 
@@ -158,10 +158,11 @@ hipError_t launch_margins(const float *G, int64_t n_out, int64_t r, int64_t ldg,
 {
     const bool vec = aligned16(G) && aligned16(w) && ldg % 4 == 0;
     const int ri = int(r);
-    if (r >= 256) return launch_margins_lpr<64, INDEXED>(G, n_out, ri, ldg, rows, w, m, vec, s);
-    if (r >= 128) return launch_margins_lpr<32, INDEXED>(G, n_out, ri, ldg, rows, w, m, vec, s);
-    if (r >= 64) return launch_margins_lpr<16, INDEXED>(G, n_out, ri, ldg, rows, w, m, vec, s);
-    return launch_margins_lpr<8, INDEXED>(G, n_out, ri, ldg, rows, w, m, vec, s);
+    if (r >= 1024) return launch_margins_lpr<64, INDEXED, 2>(G, n_out, ri, ldg, rows, w, m, vec, s);
+    if (r >= 256) return launch_margins_lpr<64, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, vec, s);
+    if (r >= 128) return launch_margins_lpr<32, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, vec, s);
+    if (r >= 64) return launch_margins_lpr<16, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, vec, s);
+    return launch_margins_lpr<8, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, vec, s);
 }
 
 // ---------------------------------------------------------------- factor schedule

@@ -30,8 +30,8 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per whitening-product launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/), keyed by workload; None where not collected.
 MEASURED_TRAFFIC = {
-    # profiles/factor_and_sweep_cnn_hbm_traffic.txt: FETCH_SIZE 1.7087e6 KiB x 2.0 + WRITE_SIZE 2.5284e5 KiB x 1.0
-    "cnn": 1.7087e6 * 1024 * 2.0 + 2.5284e5 * 1024 * 1.0,
+    # profiles/factor_and_sweep_cnn_hbm_traffic.txt: FETCH_SIZE 1.5676e6 KiB x 2.0 + WRITE_SIZE 2.6089e5 KiB x 1.0
+    "cnn": 1.5676e6 * 1024 * 2.0 + 2.6089e5 * 1024 * 1.0,
 }
 
 

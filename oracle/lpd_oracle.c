@@ -223,3 +223,168 @@ void orc_set_num_threads(int t) { omp_set_num_threads(t); }
 int orc_num_threads(void) { return 1; }
 void orc_set_num_threads(int t) { (void)t; }
 #endif
+
+/* ------------------------------------------------------------------------
+ * Stage 2: dual coordinate ascent on the linear problem whose data points are
+ * the rows of G (Section 2, equation (2) and the truncated Newton step;
+ * Section 3, "Shrinking"; Figure 1 steps 2a-2b).
+ *
+ *   maximise  D(alpha) = sum_i alpha_i - 1/2 ||w||^2,   0 <= alpha_i <= C,
+ *   w = sum_i alpha_i y_i g_i,   Q_ij = y_i y_j g_i . g_j
+ *
+ * One step on variable i (2a, 2b):
+ *   f = g_i . w ;  grad = 1 - y_i f ;  alpha_i <- clip(alpha_i + grad / Q_ii, 0, C) ;
+ *   w <- w + (alpha_new - alpha_old) y_i g_i.
+ * A row with Q_ii = 0 cannot change w; its alpha goes to C (grad = 1 > 0).
+ *
+ * The paper fixes k = 5 and eta = 5 % for shrinking and names the stopping rule
+ * only as "standard, similar to LIBLINEAR"; the reading implemented here, step
+ * for step the same as the GPU solver's:
+ *   - variables are visited round-robin in the order of the active list, which
+ *     starts as the caller's order; an epoch is one pass over that list;
+ *   - a variable whose step left alpha exactly unchanged k times in a row is
+ *     removed (appended to a FIFO queue of removed variables);
+ *   - after every S = round((1 - eta) / eta) steps on active variables one step
+ *     is spent on the head of that queue: if the step changes alpha the variable
+ *     is reactivated (joins the next epoch's list), otherwise it returns to the
+ *     tail.  Every step costs one inner product, so a fraction eta of the work
+ *     goes into re-checking removed variables;
+ *   - KKT violation of a variable, measured before its step: max(grad, 0) at
+ *     alpha = 0, max(-grad, 0) at alpha = C, |grad| inside;
+ *   - when the largest violation seen in an epoch is <= eps, all removed
+ *     variables are checked with w fixed (a margin sweep over their rows);
+ *     those violating by more than eps are reactivated; if there are none the
+ *     solver stops.
+ *
+ * G: fp32 factor (ldg), rows/y: the problem's np variables in visiting order,
+ * alpha: in (warm start) / out, w: out (r doubles).  stats (6 doubles): epochs,
+ * steps (inner products spent), converged (0/1), final active count, last
+ * epoch's largest violation, dual objective.
+ * ------------------------------------------------------------------------ */
+static double orc_dot_row(const float *g, const double *w, int64_t r)
+{
+    double s = 0.0;
+    for (int64_t j = 0; j < r; ++j) s += (double)g[j] * w[j];
+    return s;
+}
+
+static double orc_violation(double alpha, double grad, double C)
+{
+    if (alpha <= 0.0) return grad > 0.0 ? grad : 0.0;
+    if (alpha >= C) return grad < 0.0 ? -grad : 0.0;
+    return fabs(grad);
+}
+
+void orc_cd_solve(const float *G, int64_t r, int64_t ldg,
+                  const int64_t *rows, const float *y, int64_t np, double C,
+                  double eps, int64_t max_epochs, int64_t shrink_k, double eta,
+                  double *alpha, double *w, double *stats)
+{
+    int64_t *act = (int64_t *)malloc((size_t)(np + 1) * sizeof(int64_t));
+    int64_t *nxt = (int64_t *)malloc((size_t)(np + 1) * sizeof(int64_t));
+    int64_t *rem = (int64_t *)malloc((size_t)(np + 1) * sizeof(int64_t));   /* circular FIFO */
+    int64_t *cnt = (int64_t *)calloc((size_t)(np + 1), sizeof(int64_t));
+    int64_t n_act = np, n_rem = 0, head = 0, steps = 0, since = 0, epochs = 0;
+    int converged = 0;
+    double maxviol = 0.0;
+    const int64_t S = eta > 0.0 ? (int64_t)floor((1.0 - eta) / eta + 0.5) : 0;
+
+    for (int64_t j = 0; j < r; ++j) w[j] = 0.0;
+    for (int64_t t = 0; t < np; ++t) {
+        act[t] = t;
+        if (alpha[t] != 0.0) {
+            const float *g = G + rows[t] * ldg;
+            for (int64_t j = 0; j < r; ++j) w[j] += alpha[t] * (double)y[t] * (double)g[j];
+        }
+    }
+
+    while (epochs < max_epochs && !converged) {
+        int64_t n_nxt = 0;
+        maxviol = 0.0;
+        for (int64_t pos = 0; pos < n_act; ++pos) {
+            /* the eta share: one step on the head of the removed queue */
+            if (shrink_k > 0 && S > 0 && since >= S && n_rem > 0) {
+                const int64_t t = rem[head];
+                head = (head + 1) % (np + 1);
+                --n_rem;
+                const float *g = G + rows[t] * ldg;
+                double q = 0.0;
+                for (int64_t j = 0; j < r; ++j) q += (double)g[j] * (double)g[j];
+                const double grad = 1.0 - (double)y[t] * orc_dot_row(g, w, r);
+                double an = q > 0.0 ? alpha[t] + grad / q : C;
+                an = an < 0.0 ? 0.0 : (an > C ? C : an);
+                ++steps;
+                since = 0;
+                if (an != alpha[t]) {
+                    const double dl = (an - alpha[t]) * (double)y[t];
+                    for (int64_t j = 0; j < r; ++j) w[j] += dl * (double)g[j];
+                    alpha[t] = an;
+                    cnt[t] = 0;
+                    nxt[n_nxt++] = t;
+                } else {
+                    rem[(head + n_rem) % (np + 1)] = t;
+                    ++n_rem;
+                }
+            }
+            const int64_t t = act[pos];
+            const float *g = G + rows[t] * ldg;
+            double q = 0.0;
+            for (int64_t j = 0; j < r; ++j) q += (double)g[j] * (double)g[j];
+            const double grad = 1.0 - (double)y[t] * orc_dot_row(g, w, r);   /* step 2a */
+            const double v = orc_violation(alpha[t], grad, C);
+            if (v > maxviol) maxviol = v;
+            double an = q > 0.0 ? alpha[t] + grad / q : C;                   /* step 2b */
+            an = an < 0.0 ? 0.0 : (an > C ? C : an);
+            ++steps;
+            ++since;
+            if (an != alpha[t]) {
+                const double dl = (an - alpha[t]) * (double)y[t];
+                for (int64_t j = 0; j < r; ++j) w[j] += dl * (double)g[j];
+                alpha[t] = an;
+                cnt[t] = 0;
+                nxt[n_nxt++] = t;
+            } else if (shrink_k > 0 && ++cnt[t] >= shrink_k) {
+                rem[(head + n_rem) % (np + 1)] = t;
+                ++n_rem;
+            } else {
+                nxt[n_nxt++] = t;
+            }
+        }
+        ++epochs;
+        if (maxviol <= eps) {
+            /* sweep over the removed variables with w fixed */
+            int64_t back = 0;
+            const int64_t m = n_rem;
+            for (int64_t c = 0; c < m; ++c) {
+                const int64_t t = rem[head];
+                head = (head + 1) % (np + 1);
+                --n_rem;
+                const float *g = G + rows[t] * ldg;
+                const double grad = 1.0 - (double)y[t] * orc_dot_row(g, w, r);
+                ++steps;
+                if (orc_violation(alpha[t], grad, C) > eps) {
+                    cnt[t] = 0;
+                    nxt[n_nxt++] = t;
+                    ++back;
+                } else {
+                    rem[(head + n_rem) % (np + 1)] = t;
+                    ++n_rem;
+                }
+            }
+            if (back == 0) converged = 1;
+        }
+        { int64_t *tmp = act; act = nxt; nxt = tmp; }
+        n_act = n_nxt;
+        if (n_act == 0 && n_rem == 0) converged = 1;
+    }
+    double sa = 0.0, ww = 0.0;
+    for (int64_t t = 0; t < np; ++t) sa += alpha[t];
+    for (int64_t j = 0; j < r; ++j) ww += w[j] * w[j];
+    stats[0] = (double)epochs;
+    stats[1] = (double)steps;
+    stats[2] = (double)converged;
+    stats[3] = (double)n_act;
+    stats[4] = maxviol;
+    stats[5] = sa - 0.5 * ww;
+    free(act); free(nxt); free(rem); free(cnt);
+}

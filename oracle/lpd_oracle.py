@@ -61,6 +61,9 @@ def _load():
         lib.orc_margins.restype = None
         lib.orc_margins_f64.argtypes = [_f64p, _i64, _i64, _i64, _f64p, _f64p]
         lib.orc_margins_f64.restype = None
+        lib.orc_cd_solve.argtypes = [_f32p, _i64, _i64, ctypes.POINTER(_i64), _f32p, _i64, ctypes.c_double,
+                                     ctypes.c_double, _i64, _i64, ctypes.c_double, _f64p, _f64p, _f64p]
+        lib.orc_cd_solve.restype = None
         lib.orc_num_threads.restype = ctypes.c_int
         lib.orc_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -179,3 +182,24 @@ def margins_f64(G, w) -> np.ndarray:
     m = np.empty(n, dtype=np.float64)
     _load().orc_margins_f64(_p64(G), n, r, r, _p64(w), _p64(m))
     return m
+
+
+def cd_solve(G, rows, y, C: float, eps: float = 1e-3, max_epochs: int = 1000, shrink_k: int = 5, eta: float = 0.05,
+             alpha0=None, r: int | None = None):
+    """Dual coordinate ascent with shrinking on the rows of G (Figure 1 steps 2a-2b; Section 3 "Shrinking").
+
+    G: fp32 factor; rows: the problem's row indices in visiting order; y: +-1 per listed row.
+    Returns (alpha float64 per listed row, w float64 (r), stats dict)."""
+    G = _f32(G)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    y = _f32(y)
+    n_p = rows.shape[0]
+    assert y.shape[0] == n_p and G.ndim == 2
+    r = G.shape[1] if r is None else int(r)
+    alpha = np.zeros(n_p, dtype=np.float64) if alpha0 is None else _f64(alpha0).copy()
+    w = np.zeros(r, dtype=np.float64)
+    stats = np.zeros(6, dtype=np.float64)
+    _load().orc_cd_solve(_p32(G), r, G.shape[1], rows.ctypes.data_as(ctypes.POINTER(_i64)), _p32(y), n_p, float(C),
+                         float(eps), int(max_epochs), int(shrink_k), float(eta), _p64(alpha), _p64(w), _p64(stats))
+    return alpha, w, {"epochs": int(stats[0]), "steps": int(stats[1]), "converged": bool(stats[2]),
+                      "active": int(stats[3]), "max_violation": float(stats[4]), "dual": float(stats[5])}

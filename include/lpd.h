@@ -180,6 +180,72 @@ int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg,
                      const int64_t *rows, int64_t n_rows,
                      const float *w, float *m, void *hip_stream);
 
+/*
+ * Squared norms of the rows of the factor, gsq[i] = sum_{j<r} G[i,j]^2: the
+ * diagonal Q_ii of the dual problem (Section 2, equation (2)) that the
+ * coordinate step divides by.  G device in n x r (ldg); gsq device out, n floats.
+ */
+int lpd_row_sqnorms(const float *G, int64_t n, int64_t r, int64_t ldg, float *gsq, void *hip_stream);
+
+/* Result record of one binary problem of lpd_cd_solve. */
+typedef struct {
+    int64_t steps;        /* inner products spent: active steps, re-checks, final sweeps */
+    int32_t epochs;       /* passes over the active list                               */
+    int32_t converged;    /* 1: stopped by the rule below, 0: hit max_epochs            */
+    int32_t active;       /* size of the active list at exit                            */
+    float max_violation;  /* largest KKT violation seen in the last epoch               */
+    float dual;           /* sum alpha - 1/2 ||w||^2                                    */
+    int32_t reserved;
+} lpd_cd_status;
+
+/* Bytes of device scratch lpd_cd_solve needs (active / next / removed lists and counters). */
+int lpd_cd_solve_workspace(int64_t n_problems, int64_t total_rows, size_t *bytes);
+
+/*
+ * Stage 2 of the method on the device: dual coordinate ascent with shrinking on
+ * the rows of G, for a batch of independent binary problems that share G (grid
+ * search over C, cross-validation folds, one-versus-one pairs; Section 3).
+ * Per problem p (Section 2, equation (2); Figure 1 steps 2a-2b):
+ *
+ *   maximise sum_t alpha_t - 1/2 ||w||^2,  0 <= alpha_t <= C[p],
+ *   w = sum_t alpha_t y_t g_{rows[t]},   t over the problem's listed rows;
+ *   step on t: f = g.w;  alpha_t <- clip(alpha_t + (1 - y_t f)/||g||^2, 0, C);  w += d_alpha y_t g.
+ *
+ * Order, shrinking and stopping (the paper fixes k = 5 and eta = 5 % and leaves
+ * the stopping rule as "similar to LIBLINEAR"; this reading is shared with the
+ * CPU oracle): round-robin over the active list, initially the listed order; a
+ * variable whose step left alpha bit-for-bit unchanged shrink_k times in a row is
+ * removed; after every round((1-eta)/eta) active steps one step is spent on the
+ * oldest removed variable, which rejoins if the step changes it; when an epoch's
+ * largest violation (max(grad,0) at 0, max(-grad,0) at C, |grad| inside, measured
+ * before each step) is <= eps, w is recomputed from alpha (the incremental fp32
+ * updates drift), all removed variables are swept with that w, violators
+ * rejoin; the problem is done when there are none and the epoch itself had
+ * started from a recomputed w.  shrink_k = 0
+ * switches shrinking off, eta = 0 the interleaved re-checks.
+ *
+ *   G        device in   n x r (ldg), r <= 16384; 16-byte aligned rows take the fast loader
+ *   gsq      device in   n, from lpd_row_sqnorms
+ *   prob_off device in   n_problems + 1 offsets into rows / y / alpha; prob_off[0] = 0,
+ *                        non-decreasing, prob_off[n_problems] = total_rows (not checked on the device)
+ *   rows     device in   total_rows indices into G, each in [0, n) (not checked on the device)
+ *   y        device in   total_rows labels, +1 or -1
+ *   C        device in   n_problems upper bounds
+ *   alpha    device i/o  total_rows; start values (zeros, or a warm start) in, solution out
+ *   w        device out  n_problems x r (ldw)
+ *   status   device out  n_problems records
+ * One workgroup per problem; problems run concurrently.  Calls with the same
+ * alpha / workspace must not overlap.
+ * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE (incl. r > 16384, shrink_k > 255, eta outside [0,1)),
+ * LPD_ERR_LD (ldg < r, ldw < r), LPD_ERR_WORKSPACE, LPD_ERR_HIP.
+ */
+int lpd_cd_solve(const float *G, int64_t n, int64_t r, int64_t ldg, const float *gsq,
+                 int64_t n_problems, const int64_t *prob_off, int64_t total_rows,
+                 const int64_t *rows, const float *y, const float *C,
+                 float *alpha, float *w, int64_t ldw, lpd_cd_status *status,
+                 float eps, int32_t max_epochs, int32_t shrink_k, float eta,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

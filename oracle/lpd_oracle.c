@@ -251,10 +251,12 @@ void orc_set_num_threads(int t) { (void)t; }
  *     goes into re-checking removed variables;
  *   - KKT violation of a variable, measured before its step: max(grad, 0) at
  *     alpha = 0, max(-grad, 0) at alpha = C, |grad| inside;
- *   - when the largest violation seen in an epoch is <= eps, all removed
- *     variables are checked with w fixed (a margin sweep over their rows);
- *     those violating by more than eps are reactivated; if there are none the
- *     solver stops.
+ *   - when the largest violation seen in an epoch is <= eps, w is recomputed
+ *     from alpha and all removed variables are checked with that w (a margin
+ *     sweep over their rows); those violating by more than eps are reactivated;
+ *     the solver stops when there are none and the epoch itself had started
+ *     from a recomputed w (so every variable was verified against a w free of
+ *     the rounding drift of the incremental updates).
  *
  * G: fp32 factor (ldg), rows/y: the problem's np variables in visiting order,
  * alpha: in (warm start) / out, w: out (r doubles).  stats (6 doubles): epochs,
@@ -285,7 +287,7 @@ void orc_cd_solve(const float *G, int64_t r, int64_t ldg,
     int64_t *rem = (int64_t *)malloc((size_t)(np + 1) * sizeof(int64_t));   /* circular FIFO */
     int64_t *cnt = (int64_t *)calloc((size_t)(np + 1), sizeof(int64_t));
     int64_t n_act = np, n_rem = 0, head = 0, steps = 0, since = 0, epochs = 0;
-    int converged = 0;
+    int converged = 0, fresh = 1;   /* the start w is computed from the start alpha */
     double maxviol = 0.0;
     const int64_t S = eta > 0.0 ? (int64_t)floor((1.0 - eta) / eta + 0.5) : 0;
 
@@ -352,7 +354,15 @@ void orc_cd_solve(const float *G, int64_t r, int64_t ldg,
         }
         ++epochs;
         if (maxviol <= eps) {
-            /* sweep over the removed variables with w fixed */
+            /* recompute w from alpha (sheds the rounding drift of the incremental updates; a
+             * no-op in exact arithmetic), then sweep over the removed variables with w fixed */
+            for (int64_t j = 0; j < r; ++j) w[j] = 0.0;
+            for (int64_t t = 0; t < np; ++t) {
+                if (alpha[t] == 0.0) continue;
+                const float *g = G + rows[t] * ldg;
+                for (int64_t j = 0; j < r; ++j) w[j] += alpha[t] * (double)y[t] * (double)g[j];
+                ++steps;
+            }
             int64_t back = 0;
             const int64_t m = n_rem;
             for (int64_t c = 0; c < m; ++c) {
@@ -371,11 +381,13 @@ void orc_cd_solve(const float *G, int64_t r, int64_t ldg,
                     ++n_rem;
                 }
             }
-            if (back == 0) converged = 1;
+            if (back == 0 && fresh) converged = 1;   /* the epoch itself started from a recomputed w */
+            fresh = 1;
+        } else {
+            fresh = 0;
         }
         { int64_t *tmp = act; act = nxt; nxt = tmp; }
         n_act = n_nxt;
-        if (n_act == 0 && n_rem == 0) converged = 1;
     }
     double sa = 0.0, ww = 0.0;
     for (int64_t t = 0; t < np; ++t) sa += alpha[t];

@@ -1,0 +1,390 @@
+// Dual coordinate ascent with shrinking on the rows of the factor G, many
+// independent binary problems at once (Section 2, equation (2) and the truncated
+// Newton step; Section 3, "Shrinking"; Figure 1 steps 2a-2b).
+//
+//   maximise  sum_i alpha_i - 1/2 ||w||^2,  0 <= alpha_i <= C,  w = sum_i alpha_i y_i g_i
+//   step on i:  f = g_i . w (2a);  alpha_i <- clip(alpha_i + (1 - y_i f) / ||g_i||^2, 0, C);
+//               w <- w + (alpha_new - alpha_old) y_i g_i (2b)
+//
+// The loop is sequential inside a problem (the paper keeps one problem on one
+// multiprocessor with w in its scratchpad); the parallelism is across problems
+// (grid search, folds, one-versus-one pairs share one G).  Mapping for CDNA4:
+//   * one problem = one workgroup of WAVES wavefronts (1 for r <= 4096, 4 above);
+//     w and the current row of G live in registers, 4*NCH consecutive-by-lane
+//     columns per lane, so the row load is one coalesced 16-byte access per lane
+//     and chunk, the inner product ends in a butterfly over the 64 lanes (plus a
+//     4-entry LDS exchange when WAVES = 4), and the update of w reuses the row
+//     registers: G is read once per step, 4r bytes.
+//   * everything that depends only on the visiting order -- variable index, row
+//     index, label, alpha, unchanged-counter, ||g||^2 -- is gathered for 64 steps
+//     at a time, one step per lane, into LDS; the next row of G is requested
+//     before the current step's reduction.  Only the reduction and a handful of
+//     scalar operations sit on the dependent path of a step.
+//   * every lane executes the scalar logic on identical values (the butterfly
+//     leaves the same bits in all lanes), so control flow is uniform; one lane
+//     writes alpha, counters and the lists.
+//
+// Shrinking and stopping rule (the paper fixes k = 5, eta = 5 % and calls the
+// stopping rule "similar to LIBLINEAR"); this is the reading the CPU oracle
+// implements step for step:
+//   - round-robin over the active list (initially the caller's order), one pass
+//     = one epoch; a variable whose step left alpha bit-for-bit unchanged k times
+//     in a row moves to a FIFO queue of removed variables;
+//   - after every S = round((1-eta)/eta) active steps one step goes to the head of
+//     that queue: if it changes alpha the variable rejoins the next epoch's list,
+//     else it returns to the tail;
+//   - violation before a step: max(grad,0) at alpha = 0, max(-grad,0) at alpha = C,
+//     |grad| inside; when an epoch's largest violation is <= eps, w is recomputed
+//     from alpha (the incremental updates drift in fp32), all removed variables
+//     are swept with that w, violators rejoin; the problem is solved when there
+//     are none and the epoch itself had started from a recomputed w.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lpd {
+
+typedef float cf32x4 __attribute__((ext_vector_type(4)));
+
+struct CdStatus {          // one per problem, mirrors lpd_cd_status
+    int64_t steps;         // inner products spent (active steps + re-checks + final sweeps)
+    int32_t epochs;
+    int32_t converged;
+    int32_t active;        // size of the active list at exit
+    float max_violation;   // largest violation seen in the last epoch
+    float dual;            // sum alpha - 1/2 ||w||^2
+    int32_t reserved;
+};
+
+struct CdArgs {
+    const float *G; int64_t ldg; int r;
+    const float *gsq;               // ||g_i||^2 per row of G
+    const int64_t *prob_off;        // n_problems + 1 offsets into rows / y / alpha
+    const int64_t *rows;            // concatenated row lists (visiting order)
+    const float *y;                 // +-1 per listed row
+    const float *C;                 // per problem
+    float *alpha;                   // in: start (warm start), out: solution
+    float *w; int64_t ldw;          // n_problems x r out
+    CdStatus *status;
+    int32_t *lists;                 // 3 * (total + n_problems) ints: active, next, removed
+    uint8_t *cnt;                   // total bytes: unchanged-counters
+    int64_t total;                  // prob_off[n_problems]
+    int64_t n_problems;
+    float eps; int max_epochs; int shrink_k; int check_every;   // check_every = S, 0 = no re-checks
+};
+
+template <typename T>
+__device__ __forceinline__ T ld_l2(const T *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+template <typename T>
+__device__ __forceinline__ void st_l2(T *p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+__device__ __forceinline__ float wave_allsum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__device__ __forceinline__ float cd_violation(float alpha, float grad, float C)
+{
+    if (alpha <= 0.0f) return fmaxf(grad, 0.0f);
+    if (alpha >= C) return fmaxf(-grad, 0.0f);
+    return fabsf(grad);
+}
+
+// VEC: rows of G are 16-byte aligned (pointer and leading dimension); otherwise element-wise loads.
+template <int WAVES, int NCH, bool VEC>
+__global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
+{
+    constexpr int T = 64 * WAVES;
+    constexpr int BLK = 64;                  // steps whose metadata is gathered at once
+    __shared__ int32_t s_t[BLK];
+    __shared__ int64_t s_row[BLK];
+    __shared__ float s_y[BLK], s_alpha[BLK], s_q[BLK];
+    __shared__ int32_t s_cnt[BLK];
+    __shared__ float s_part[2][WAVES];
+
+    const int p = blockIdx.x;
+    const int gl = threadIdx.x;
+    const int wave = gl >> 6;
+    const int64_t o0 = a.prob_off[p];
+    const int np = int(a.prob_off[p + 1] - o0);
+    const int64_t *rows = a.rows + o0;
+    const float *y = a.y + o0;
+    float *alpha = a.alpha + o0;
+    uint8_t *cnt = a.cnt + o0;
+    const int64_t stride = a.total + a.n_problems;
+    int32_t *act = a.lists + (o0 + p);
+    int32_t *nxt = act + stride;
+    int32_t *rem = nxt + stride;
+    const int cap = np + 1;
+    const float C = a.C[p];
+    const int r = a.r;
+
+    // lane -> columns: chunk c covers columns (c*T + gl)*4 .. +3
+    bool live[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) live[c] = (c * T + gl) * 4 < r;
+    auto load_row = [&](cf32x4(&g)[NCH], int64_t row) {
+        const float *base = a.G + row * a.ldg + gl * 4;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            cf32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (live[c]) {
+                const int col = (c * T + gl) * 4;
+                if (VEC) {
+                    v = *reinterpret_cast<const cf32x4 *>(base + c * T * 4);
+                    if (col + 1 >= r) v.y = 0.f;
+                    if (col + 2 >= r) v.z = 0.f;
+                    if (col + 3 >= r) v.w = 0.f;
+                } else {
+                    const float *e = base + c * T * 4;
+                    v.x = e[0];
+                    if (col + 1 < r) v.y = e[1];
+                    if (col + 2 < r) v.z = e[2];
+                    if (col + 3 < r) v.w = e[3];
+                }
+            }
+            g[c] = v;
+        }
+    };
+    int parity = 0;
+    auto block_sum = [&](float part) -> float {
+        float s = wave_allsum(part);
+        if (WAVES > 1) {
+            if ((gl & 63) == 0) s_part[parity][wave] = s;
+            __syncthreads();
+            s = 0.f;
+#pragma unroll
+            for (int v = 0; v < WAVES; ++v) s += s_part[parity][v];
+            parity ^= 1;
+        }
+        return s;
+    };
+    auto dot = [&](const cf32x4(&g)[NCH], const cf32x4(&w)[NCH]) -> float {
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            s0 += g[c].x * w[c].x + g[c].y * w[c].y;
+            s1 += g[c].z * w[c].z + g[c].w * w[c].w;
+        }
+        return block_sum(s0 + s1);
+    };
+
+    cf32x4 w[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) w[c] = cf32x4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- initial lists, counters, and w for a warm start
+    for (int t = gl; t < np; t += T) { st_l2(&act[t], int32_t(t)); st_l2(&cnt[t], uint8_t(0)); }
+    // w = sum_t alpha_t y_t g_t over the non-zero alpha, compensated (Kahan) summation in fp32:
+    // used for a warm start and to shed the rounding drift of the incremental updates before
+    // the stopping rule is verified.  Returns the number of rows read.
+    auto recompute_w = [&]() -> int {
+        cf32x4 comp[NCH];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) { w[c] = cf32x4{0.f, 0.f, 0.f, 0.f}; comp[c] = cf32x4{0.f, 0.f, 0.f, 0.f}; }
+        int used = 0;
+        for (int b0 = 0; b0 < np; b0 += 64) {
+            // every wavefront scans the same 64 values and adds the rows of the non-zero ones
+            const int t0 = b0 + (gl & 63);
+            const float av = t0 < np ? ld_l2(&alpha[t0]) : 0.0f;
+            unsigned long long todo = __ballot(av != 0.0f);
+            while (todo) {
+                const int j = __ffsll(todo) - 1;
+                todo &= todo - 1;
+                const float at = __shfl(av, j, 64);
+                cf32x4 g[NCH];
+                load_row(g, rows[b0 + j]);
+                const float f = at * y[b0 + j];
+                ++used;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    const cf32x4 term = f * g[c] - comp[c];
+                    const cf32x4 sum = w[c] + term;
+                    comp[c] = (sum - w[c]) - term;
+                    w[c] = sum;
+                }
+            }
+        }
+        return used;
+    };
+    __threadfence();
+    __syncthreads();
+    recompute_w();
+    __threadfence();
+    __syncthreads();
+
+    int n_act = np, n_rem = 0, head = 0, since = 0, epochs = 0, converged = 0, fresh = 1;   // the start w is computed from alpha
+    int64_t steps = 0;
+    float maxviol = 0.f;
+
+    // one step on a removed variable (re-check) or a violation probe; slow path, no prefetch
+    auto single = [&](int t, bool apply, float &viol_out) -> bool {
+        const int64_t row = rows[t];
+        const float yt = y[t];
+        const float at = ld_l2(&alpha[t]);
+        const float q = a.gsq[row];
+        cf32x4 g[NCH];
+        load_row(g, row);
+        const float grad = 1.0f - yt * dot(g, w);
+        viol_out = cd_violation(at, grad, C);
+        if (!apply) return false;
+        float an = q > 0.0f ? at + grad / q : C;
+        an = fminf(fmaxf(an, 0.0f), C);
+        if (an != at) {
+            const float dl = (an - at) * yt;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) w[c] += dl * g[c];
+            if (gl == 0) st_l2(&alpha[t], an);
+            return true;
+        }
+        return false;
+    };
+
+    while (epochs < a.max_epochs && !converged) {
+        int n_nxt = 0;
+        maxviol = 0.f;
+        for (int b0 = 0; b0 < n_act; b0 += BLK) {
+            const int nb = min(BLK, n_act - b0);
+            // gather the metadata of the next nb steps, one step per lane
+            __threadfence();
+            __syncthreads();
+            if (gl < nb) {
+                const int t = ld_l2(&act[b0 + gl]);
+                const int64_t row = rows[t];
+                s_t[gl] = t;
+                s_row[gl] = row;
+                s_y[gl] = y[t];
+                s_alpha[gl] = ld_l2(&alpha[t]);
+                s_cnt[gl] = ld_l2(&cnt[t]);
+                s_q[gl] = a.gsq[row];
+            }
+            __syncthreads();
+            cf32x4 g0[NCH], g1[NCH];
+            load_row(g0, s_row[0]);
+            auto step = [&](int j, const cf32x4(&g)[NCH], cf32x4(&gn)[NCH]) {
+                // the eta share: one step on the head of the removed queue
+                if (a.shrink_k > 0 && a.check_every > 0 && since >= a.check_every && n_rem > 0) {
+                    __threadfence();        // the lists are written by one lane: make its stores visible
+                    __syncthreads();        // to every wavefront of the workgroup before reading them
+                    const int t = ld_l2(&rem[head]);
+                    head = head + 1 == cap ? 0 : head + 1;
+                    --n_rem;
+                    float v;
+                    const bool changed = single(t, true, v);
+                    ++steps;
+                    since = 0;
+                    if (changed) {
+                        if (gl == 0) { st_l2(&cnt[t], uint8_t(0)); st_l2(&nxt[n_nxt], int32_t(t)); }
+                        ++n_nxt;
+                    } else {
+                        int tail = head + n_rem;
+                        if (tail >= cap) tail -= cap;
+                        if (gl == 0) st_l2(&rem[tail], int32_t(t));
+                        ++n_rem;
+                    }
+                }
+                if (j + 1 < nb) load_row(gn, s_row[j + 1]);          // request the next row early
+                const int t = s_t[j];
+                const float yt = s_y[j], at = s_alpha[j], q = s_q[j];
+                const float grad = 1.0f - yt * dot(g, w);            // step 2a
+                maxviol = fmaxf(maxviol, cd_violation(at, grad, C));
+                float an = q > 0.0f ? at + grad / q : C;             // step 2b
+                an = fminf(fmaxf(an, 0.0f), C);
+                ++steps;
+                ++since;
+                if (an != at) {
+                    const float dl = (an - at) * yt;
+#pragma unroll
+                    for (int c = 0; c < NCH; ++c) w[c] += dl * g[c];
+                    if (gl == 0) {
+                        st_l2(&alpha[t], an);
+                        if (s_cnt[j] != 0) st_l2(&cnt[t], uint8_t(0));
+                        st_l2(&nxt[n_nxt], int32_t(t));
+                    }
+                    ++n_nxt;
+                } else {
+                    const int cn = s_cnt[j] + 1;
+                    if (a.shrink_k > 0 && cn >= a.shrink_k) {
+                        int tail = head + n_rem;
+                        if (tail >= cap) tail -= cap;
+                        if (gl == 0) st_l2(&rem[tail], int32_t(t));
+                        ++n_rem;
+                    } else {
+                        if (gl == 0) { st_l2(&cnt[t], uint8_t(cn)); st_l2(&nxt[n_nxt], int32_t(t)); }
+                        ++n_nxt;
+                    }
+                }
+            };
+            for (int j = 0; j < nb; j += 2) {
+                step(j, g0, g1);
+                if (j + 1 < nb) step(j + 1, g1, g0);
+            }
+        }
+        ++epochs;
+        if (maxviol <= a.eps) {
+            // recompute w from alpha, then sweep over the removed variables with w fixed
+            __threadfence();
+            __syncthreads();
+            steps += recompute_w();
+            int back = 0;
+            const int m = n_rem;
+            for (int c = 0; c < m; ++c) {
+                const int t = ld_l2(&rem[head]);
+                head = head + 1 == cap ? 0 : head + 1;
+                --n_rem;
+                float v;
+                single(t, false, v);
+                ++steps;
+                if (v > a.eps) {
+                    if (gl == 0) { st_l2(&cnt[t], uint8_t(0)); st_l2(&nxt[n_nxt], int32_t(t)); }
+                    ++n_nxt;
+                    ++back;
+                } else {
+                    int tail = head + n_rem;
+                    if (tail >= cap) tail -= cap;
+                    if (gl == 0) st_l2(&rem[tail], int32_t(t));
+                    ++n_rem;
+                }
+            }
+            if (back == 0 && fresh) converged = 1;      // this epoch already started from a recomputed w
+            fresh = 1;
+        } else {
+            fresh = 0;
+        }
+        { int32_t *tmp = act; act = nxt; nxt = tmp; }
+        n_act = n_nxt;
+    }
+
+    // ---- results: w, dual objective, status
+    __threadfence();
+    __syncthreads();
+    float ww = 0.f, sa = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        ww += w[c].x * w[c].x + w[c].y * w[c].y + w[c].z * w[c].z + w[c].w * w[c].w;
+        const int col = (c * T + gl) * 4;
+        float *wo = a.w + int64_t(p) * a.ldw + col;
+        if (col < r) wo[0] = w[c].x;
+        if (col + 1 < r) wo[1] = w[c].y;
+        if (col + 2 < r) wo[2] = w[c].z;
+        if (col + 3 < r) wo[3] = w[c].w;
+    }
+    for (int t = gl; t < np; t += T) sa += ld_l2(&alpha[t]);
+    ww = block_sum(ww);
+    sa = block_sum(sa);
+    if (gl == 0) {
+        CdStatus st;
+        st.steps = steps;
+        st.epochs = epochs;
+        st.converged = converged;
+        st.active = n_act;
+        st.max_violation = maxviol;
+        st.dual = sa - 0.5f * ww;
+        st.reserved = 0;
+        a.status[p] = st;
+    }
+}
+
+}  // namespace lpd

@@ -3,10 +3,12 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <vector>
 
 #include "../../include/lpd.h"
+#include "cd_solver.hip.h"
 #include "gemm_nt.hip.h"
 #include "rowops.hip.h"
 
@@ -386,6 +388,71 @@ int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg, const in
     if (ldg < r) return LPD_ERR_LD;
     hipError_t e = launch_margins<true>(G, n_rows, r, ldg, rows, w, m, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+}
+
+int lpd_row_sqnorms(const float *G, int64_t n, int64_t r, int64_t ldg, float *gsq, void *hip_stream)
+{
+    if (n < 0 || r < 0 || n > kMaxDim * 4 || r > kMaxDim) return LPD_ERR_SHAPE;
+    if (n == 0) return LPD_OK;
+    if (!gsq || (r > 0 && !G)) return LPD_ERR_NULL;
+    if (ldg < r) return LPD_ERR_LD;
+    return launch_sqnorm(G, n, r, ldg, gsq, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+}
+
+int lpd_cd_solve_workspace(int64_t n_problems, int64_t total_rows, size_t *bytes)
+{
+    if (!bytes) return LPD_ERR_NULL;
+    if (n_problems < 0 || total_rows < 0 || n_problems > kMaxDim || total_rows > kMaxDim) return LPD_ERR_SHAPE;
+    *bytes = round_up(size_t(3) * size_t(total_rows + n_problems) * 4, kAlign) + round_up(size_t(total_rows), kAlign);
+    return LPD_OK;
+}
+
+int lpd_cd_solve(const float *G, int64_t n, int64_t r, int64_t ldg, const float *gsq, int64_t n_problems,
+                 const int64_t *prob_off, int64_t total_rows, const int64_t *rows, const float *y, const float *C,
+                 float *alpha, float *w, int64_t ldw, lpd_cd_status *status, float eps, int32_t max_epochs,
+                 int32_t shrink_k, float eta, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    static_assert(sizeof(lpd_cd_status) == sizeof(CdStatus), "status record layout");
+    if (n < 0 || r < 0 || n_problems < 0 || total_rows < 0 || n > kMaxDim || n_problems > 0x7fffffff ||
+        total_rows > kMaxDim || r > 16384 || max_epochs < 0 || shrink_k < 0 || shrink_k > 255 ||
+        !(eta >= 0.0f && eta < 1.0f) || !(eps >= 0.0f))
+        return LPD_ERR_SHAPE;
+    if (n_problems == 0) return LPD_OK;
+    if (!prob_off || !C || !status || (r > 0 && !w)) return LPD_ERR_NULL;
+    if (total_rows > 0 && (!rows || !y || !alpha || !gsq || (r > 0 && !G))) return LPD_ERR_NULL;
+    if (ldg < r || ldw < r) return LPD_ERR_LD;
+    size_t need = 0;
+    lpd_cd_solve_workspace(n_problems, total_rows, &need);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < need)
+        return LPD_ERR_WORKSPACE;
+
+    CdArgs a{};
+    a.G = G; a.ldg = ldg; a.r = int(r); a.gsq = gsq;
+    a.prob_off = prob_off; a.rows = rows; a.y = y; a.C = C; a.alpha = alpha;
+    a.w = w; a.ldw = ldw; a.status = reinterpret_cast<CdStatus *>(status);
+    a.lists = static_cast<int32_t *>(workspace);
+    a.cnt = static_cast<uint8_t *>(workspace) + round_up(size_t(3) * size_t(total_rows + n_problems) * 4, kAlign);
+    a.total = total_rows; a.n_problems = n_problems;
+    a.eps = eps; a.max_epochs = max_epochs; a.shrink_k = shrink_k;
+    a.check_every = eta > 0.0f ? int(std::floor((1.0 - double(eta)) / double(eta) + 0.5)) : 0;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const dim3 grid{unsigned(n_problems)};
+    const bool vec = ldg % 4 == 0 && aligned16(G);
+#define LPD_CD_LAUNCH(WV, NC)                                                                       \
+    do {                                                                                            \
+        if (vec) hipLaunchKernelGGL((cd_solve_kernel<WV, NC, true>), grid, dim3(64 * WV), 0, s, a); \
+        else hipLaunchKernelGGL((cd_solve_kernel<WV, NC, false>), grid, dim3(64 * WV), 0, s, a);    \
+    } while (0)
+    if (r <= 256) LPD_CD_LAUNCH(1, 1);
+    else if (r <= 512) LPD_CD_LAUNCH(1, 2);
+    else if (r <= 1024) LPD_CD_LAUNCH(1, 4);
+    else if (r <= 2048) LPD_CD_LAUNCH(1, 8);
+    else if (r <= 4096) LPD_CD_LAUNCH(1, 16);
+    else if (r <= 8192) LPD_CD_LAUNCH(4, 8);
+    else LPD_CD_LAUNCH(4, 16);
+#undef LPD_CD_LAUNCH
+    return hipGetLastError() == hipSuccess ? LPD_OK : LPD_ERR_HIP;
 }
 
 }  // extern "C"

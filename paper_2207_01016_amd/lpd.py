@@ -57,6 +57,10 @@ SIGNATURES = {
                                         _vp]),
     "lpd_margins": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp, _vp]),
     "lpd_margins_rows": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
+    "lpd_row_sqnorms": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp]),
+    "lpd_cd_solve_workspace": (ctypes.c_int, [_i64, _i64, ctypes.POINTER(_sz)]),
+    "lpd_cd_solve": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp,
+                                    ctypes.c_float, ctypes.c_int32, ctypes.c_int32, ctypes.c_float, _vp, _sz, _vp]),
 }
 
 _lib = None
@@ -236,3 +240,77 @@ def lpd_margins_rows(G, rows, w, m=None, r: int | None = None) -> torch.Tensor:
                                 _stream(G.device))
     _check(st, "lpd_margins_rows")
     return m
+
+
+def lpd_row_sqnorms(G, gsq=None, r: int | None = None) -> torch.Tensor:
+    """gsq[i] = ||G[i, :r]||^2, the diagonal of the dual problem."""
+    G = _dev_f32(G, "G", 2)
+    n = G.shape[0]
+    r = G.shape[1] if r is None else int(r)
+    if r > G.shape[1]:
+        raise ValueError("r exceeds the columns of G")
+    if gsq is None:
+        gsq = torch.empty(n, dtype=torch.float32, device=G.device)
+    gsq = _dev_f32(gsq, "gsq", 1)
+    if gsq.shape[0] != n:
+        raise ValueError("gsq must have one entry per row of G")
+    _check(lib().lpd_row_sqnorms(G.data_ptr(), n, r, _ld(G), gsq.data_ptr(), _stream(G.device)), "lpd_row_sqnorms")
+    return gsq
+
+
+def lpd_cd_solve_workspace(n_problems: int, total_rows: int) -> int:
+    b = _sz(0)
+    _check(lib().lpd_cd_solve_workspace(n_problems, total_rows, ctypes.byref(b)), "lpd_cd_solve_workspace")
+    return int(b.value)
+
+
+CD_STATUS_DTYPE = [("steps", "<i8"), ("epochs", "<i4"), ("converged", "<i4"), ("active", "<i4"),
+                   ("max_violation", "<f4"), ("dual", "<f4"), ("reserved", "<i4")]
+
+
+def lpd_cd_solve(G, gsq, prob_off, rows, y, C, alpha, w=None, eps: float = 1e-3, max_epochs: int = 1000,
+                 shrink_k: int = 5, eta: float = 0.05, r: int | None = None, workspace=None):
+    """Batch of dual coordinate-ascent problems on the rows of G (see include/lpd.h).
+
+    prob_off: int64 device tensor of n_problems + 1 offsets; rows / y / alpha: concatenated per-problem lists
+    (alpha is updated in place); C: float32 device tensor, one per problem.
+    Returns (alpha, w [n_problems x r], status as a numpy record array read back after a synchronise)."""
+    G = _dev_f32(G, "G", 2)
+    gsq = _dev_f32(gsq, "gsq", 1)
+    y = _dev_f32(y, "y", 1)
+    C = _dev_f32(C, "C", 1)
+    alpha = _dev_f32(alpha, "alpha", 1)
+    for name, t in (("prob_off", prob_off), ("rows", rows)):
+        if t.dtype != torch.int64 or t.dim() != 1 or not t.is_cuda or (t.numel() > 1 and t.stride(0) != 1):
+            raise TypeError(f"{name}: expected a contiguous 1-D int64 device tensor")
+    n = G.shape[0]
+    r = G.shape[1] if r is None else int(r)
+    P = C.shape[0]
+    total = rows.shape[0]
+    if r > G.shape[1] or prob_off.shape[0] != P + 1 or y.shape[0] != total or alpha.shape[0] != total or \
+            gsq.shape[0] != n:
+        raise ValueError("shape mismatch between G, gsq, prob_off, rows, y, C, alpha")
+    # the kernel trusts offsets and indices: check them here
+    if P > 0:
+        po = prob_off.cpu()
+        if int(po[0]) != 0 or int(po[-1]) != total or bool((po[1:] < po[:-1]).any()):
+            raise ValueError("prob_off must start at 0, be non-decreasing and end at len(rows)")
+    if total > 0 and (int(rows.min()) < 0 or int(rows.max()) >= n):
+        raise IndexError("rows: index outside [0, n)")
+    if w is None:
+        w = torch.empty((P, max(r, 1)), dtype=torch.float32, device=G.device)
+    w = _dev_f32(w, "w", 2)
+    if w.shape[0] != P or w.shape[1] < r:
+        raise ValueError("w must be n_problems x r")
+    need = lpd_cd_solve_workspace(P, total)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=G.device)
+    status = torch.zeros((max(P, 1), 32), dtype=torch.uint8, device=G.device)
+    st = lib().lpd_cd_solve(G.data_ptr(), n, r, _ld(G), gsq.data_ptr(), P, prob_off.data_ptr(), total,
+                            rows.data_ptr(), y.data_ptr(), C.data_ptr(), alpha.data_ptr(), w.data_ptr(), _ld(w),
+                            status.data_ptr(), float(eps), int(max_epochs), int(shrink_k), float(eta),
+                            workspace.data_ptr(), workspace.numel(), _stream(G.device))
+    _check(st, "lpd_cd_solve")
+    import numpy as np
+    rec = np.frombuffer(status.cpu().numpy().tobytes(), dtype=np.dtype(CD_STATUS_DTYPE))[:P]
+    return alpha, w, rec

@@ -73,10 +73,18 @@ struct CdArgs {
     float eps; int max_epochs; int shrink_k; int check_every;   // check_every = S, 0 = no re-checks
 };
 
+// The lists, alpha and the counters are written by one lane and read back later by other lanes of
+// the same workgroup only: workgroup-scope atomics and fences are enough (one CU, one vector L1),
+// and unlike device-scope ones they cost no L2 write-back or invalidate.
 template <typename T>
-__device__ __forceinline__ T ld_l2(const T *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ T ld_wg(const T *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
 template <typename T>
-__device__ __forceinline__ void st_l2(T *p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_wg(T *p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+__device__ __forceinline__ void wg_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __syncthreads();
+}
 
 __device__ __forceinline__ float wave_allsum(float v)
 {
@@ -98,6 +106,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
 {
     constexpr int T = 64 * WAVES;
     constexpr int BLK = 64;                  // steps whose metadata is gathered at once
+    constexpr int D = NCH <= 4 ? 8 : 32 / NCH;   // row buffers in flight (at most 128 registers)
     __shared__ int32_t s_t[BLK];
     __shared__ int64_t s_row[BLK];
     __shared__ float s_y[BLK], s_alpha[BLK], s_q[BLK];
@@ -121,32 +130,41 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
     const float C = a.C[p];
     const int r = a.r;
 
-    // lane -> columns: chunk c covers columns (c*T + gl)*4 .. +3
-    bool live[NCH];
+    // lane -> columns: chunk c covers columns (c*T + gl)*4 .. +3.  Loads are bare loads: nothing
+    // touches a loaded register before the step that consumes it, so they stay in flight.  Chunks
+    // (or chunk tails) past column r are read from a valid address and zeroed when consumed.
+    const bool ragged = r != NCH * T * 4;
+    int nvalid[NCH], coff[NCH];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) live[c] = (c * T + gl) * 4 < r;
+    for (int c = 0; c < NCH; ++c) {
+        const int col = (c * T + gl) * 4;
+        nvalid[c] = min(max(r - col, 0), 4);
+        coff[c] = nvalid[c] > 0 ? col : 0;
+    }
     auto load_row = [&](cf32x4(&g)[NCH], int64_t row) {
-        const float *base = a.G + row * a.ldg + gl * 4;
+        const float *base = a.G + row * a.ldg;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            cf32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (live[c]) {
-                const int col = (c * T + gl) * 4;
-                if (VEC) {
-                    v = *reinterpret_cast<const cf32x4 *>(base + c * T * 4);
-                    if (col + 1 >= r) v.y = 0.f;
-                    if (col + 2 >= r) v.z = 0.f;
-                    if (col + 3 >= r) v.w = 0.f;
-                } else {
-                    const float *e = base + c * T * 4;
-                    v.x = e[0];
-                    if (col + 1 < r) v.y = e[1];
-                    if (col + 2 < r) v.z = e[2];
-                    if (col + 3 < r) v.w = e[3];
-                }
+            if (VEC) {
+                g[c] = *reinterpret_cast<const cf32x4 *>(base + coff[c]);
+            } else {
+                const float *e = base + coff[c];
+                g[c].x = e[0];
+                g[c].y = e[nvalid[c] > 1 ? 1 : 0];
+                g[c].z = e[nvalid[c] > 2 ? 2 : 0];
+                g[c].w = e[nvalid[c] > 3 ? 3 : 0];
             }
-            g[c] = v;
         }
+    };
+    auto valid = [&](const cf32x4(&g)[NCH], int c) -> cf32x4 {
+        cf32x4 v = g[c];
+        if (ragged) {
+            if (nvalid[c] < 1) v.x = 0.f;
+            if (nvalid[c] < 2) v.y = 0.f;
+            if (nvalid[c] < 3) v.z = 0.f;
+            if (nvalid[c] < 4) v.w = 0.f;
+        }
+        return v;
     };
     int parity = 0;
     auto block_sum = [&](float part) -> float {
@@ -165,8 +183,9 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
         float s0 = 0.f, s1 = 0.f;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            s0 += g[c].x * w[c].x + g[c].y * w[c].y;
-            s1 += g[c].z * w[c].z + g[c].w * w[c].w;
+            const cf32x4 v = valid(g, c);
+            s0 += v.x * w[c].x + v.y * w[c].y;
+            s1 += v.z * w[c].z + v.w * w[c].w;
         }
         return block_sum(s0 + s1);
     };
@@ -176,7 +195,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
     for (int c = 0; c < NCH; ++c) w[c] = cf32x4{0.f, 0.f, 0.f, 0.f};
 
     // ---- initial lists, counters, and w for a warm start
-    for (int t = gl; t < np; t += T) { st_l2(&act[t], int32_t(t)); st_l2(&cnt[t], uint8_t(0)); }
+    for (int t = gl; t < np; t += T) { st_wg(&act[t], int32_t(t)); st_wg(&cnt[t], uint8_t(0)); }
     // w = sum_t alpha_t y_t g_t over the non-zero alpha, compensated (Kahan) summation in fp32:
     // used for a warm start and to shed the rounding drift of the incremental updates before
     // the stopping rule is verified.  Returns the number of rows read.
@@ -188,32 +207,42 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
         for (int b0 = 0; b0 < np; b0 += 64) {
             // every wavefront scans the same 64 values and adds the rows of the non-zero ones
             const int t0 = b0 + (gl & 63);
-            const float av = t0 < np ? ld_l2(&alpha[t0]) : 0.0f;
+            const float av = t0 < np ? ld_wg(&alpha[t0]) : 0.0f;
             unsigned long long todo = __ballot(av != 0.0f);
             while (todo) {
-                const int j = __ffsll(todo) - 1;
-                todo &= todo - 1;
-                const float at = __shfl(av, j, 64);
-                cf32x4 g[NCH];
-                load_row(g, rows[b0 + j]);
-                const float f = at * y[b0 + j];
-                ++used;
+                // up to D rows requested together, then added in index order
+                cf32x4 g[D][NCH];
+                float f[D];
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) {
-                    const cf32x4 term = f * g[c] - comp[c];
-                    const cf32x4 sum = w[c] + term;
-                    comp[c] = (sum - w[c]) - term;
-                    w[c] = sum;
+                for (int u = 0; u < D; ++u) {
+                    f[u] = 0.0f;
+                    if (todo) {
+                        const int j = __ffsll(todo) - 1;
+                        todo &= todo - 1;
+                        load_row(g[u], rows[b0 + j]);
+                        f[u] = __shfl(av, j, 64) * y[b0 + j];
+                        ++used;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < D; ++u) {
+                    if (f[u] != 0.0f) {
+#pragma unroll
+                        for (int c = 0; c < NCH; ++c) {
+                            const cf32x4 term = f[u] * valid(g[u], c) - comp[c];
+                            const cf32x4 sum = w[c] + term;
+                            comp[c] = (sum - w[c]) - term;
+                            w[c] = sum;
+                        }
+                    }
                 }
             }
         }
         return used;
     };
-    __threadfence();
-    __syncthreads();
+    wg_sync();
     recompute_w();
-    __threadfence();
-    __syncthreads();
+    wg_sync();
 
     int n_act = np, n_rem = 0, head = 0, since = 0, epochs = 0, converged = 0, fresh = 1;   // the start w is computed from alpha
     int64_t steps = 0;
@@ -223,7 +252,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
     auto single = [&](int t, bool apply, float &viol_out) -> bool {
         const int64_t row = rows[t];
         const float yt = y[t];
-        const float at = ld_l2(&alpha[t]);
+        const float at = ld_wg(&alpha[t]);
         const float q = a.gsq[row];
         cf32x4 g[NCH];
         load_row(g, row);
@@ -235,8 +264,8 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
         if (an != at) {
             const float dl = (an - at) * yt;
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) w[c] += dl * g[c];
-            if (gl == 0) st_l2(&alpha[t], an);
+            for (int c = 0; c < NCH; ++c) w[c] += dl * valid(g, c);
+            if (gl == 0) st_wg(&alpha[t], an);
             return true;
         }
         return false;
@@ -248,27 +277,30 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
         for (int b0 = 0; b0 < n_act; b0 += BLK) {
             const int nb = min(BLK, n_act - b0);
             // gather the metadata of the next nb steps, one step per lane
-            __threadfence();
-            __syncthreads();
+            wg_sync();
             if (gl < nb) {
-                const int t = ld_l2(&act[b0 + gl]);
+                const int t = ld_wg(&act[b0 + gl]);
                 const int64_t row = rows[t];
                 s_t[gl] = t;
                 s_row[gl] = row;
                 s_y[gl] = y[t];
-                s_alpha[gl] = ld_l2(&alpha[t]);
-                s_cnt[gl] = ld_l2(&cnt[t]);
+                s_alpha[gl] = ld_wg(&alpha[t]);
+                s_cnt[gl] = ld_wg(&cnt[t]);
                 s_q[gl] = a.gsq[row];
             }
             __syncthreads();
-            cf32x4 g0[NCH], g1[NCH];
-            load_row(g0, s_row[0]);
+            // ring of D row buffers: the row of step j + D - 1 is requested at step j, so D - 1 row
+            // loads are in flight behind the one being consumed (a step is far shorter than a trip
+            // to memory)
+            cf32x4 gr[D][NCH];
+#pragma unroll
+            for (int u = 0; u < D - 1; ++u)
+                if (u < nb) load_row(gr[u], s_row[u]);
             auto step = [&](int j, const cf32x4(&g)[NCH], cf32x4(&gn)[NCH]) {
                 // the eta share: one step on the head of the removed queue
                 if (a.shrink_k > 0 && a.check_every > 0 && since >= a.check_every && n_rem > 0) {
-                    __threadfence();        // the lists are written by one lane: make its stores visible
-                    __syncthreads();        // to every wavefront of the workgroup before reading them
-                    const int t = ld_l2(&rem[head]);
+                    wg_sync();              // the lists are written by one lane: make its stores visible
+                    const int t = ld_wg(&rem[head]);
                     head = head + 1 == cap ? 0 : head + 1;
                     --n_rem;
                     float v;
@@ -276,16 +308,16 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
                     ++steps;
                     since = 0;
                     if (changed) {
-                        if (gl == 0) { st_l2(&cnt[t], uint8_t(0)); st_l2(&nxt[n_nxt], int32_t(t)); }
+                        if (gl == 0) { st_wg(&cnt[t], uint8_t(0)); st_wg(&nxt[n_nxt], int32_t(t)); }
                         ++n_nxt;
                     } else {
                         int tail = head + n_rem;
                         if (tail >= cap) tail -= cap;
-                        if (gl == 0) st_l2(&rem[tail], int32_t(t));
+                        if (gl == 0) st_wg(&rem[tail], int32_t(t));
                         ++n_rem;
                     }
                 }
-                if (j + 1 < nb) load_row(gn, s_row[j + 1]);          // request the next row early
+                if (j + D - 1 < nb) load_row(gn, s_row[j + D - 1]);  // into the buffer step j-1 released
                 const int t = s_t[j];
                 const float yt = s_y[j], at = s_alpha[j], q = s_q[j];
                 const float grad = 1.0f - yt * dot(g, w);            // step 2a
@@ -294,60 +326,87 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
                 an = fminf(fmaxf(an, 0.0f), C);
                 ++steps;
                 ++since;
-                if (an != at) {
-                    const float dl = (an - at) * yt;
+                // the same instructions whatever the outcome (a zero update of w, the same three
+                // stores), so that loads in flight are never waited for because of a branch
+                const bool changed = an != at;
+                const float dl = (an - at) * yt;
 #pragma unroll
-                    for (int c = 0; c < NCH; ++c) w[c] += dl * g[c];
-                    if (gl == 0) {
-                        st_l2(&alpha[t], an);
-                        if (s_cnt[j] != 0) st_l2(&cnt[t], uint8_t(0));
-                        st_l2(&nxt[n_nxt], int32_t(t));
-                    }
-                    ++n_nxt;
-                } else {
-                    const int cn = s_cnt[j] + 1;
-                    if (a.shrink_k > 0 && cn >= a.shrink_k) {
-                        int tail = head + n_rem;
-                        if (tail >= cap) tail -= cap;
-                        if (gl == 0) st_l2(&rem[tail], int32_t(t));
-                        ++n_rem;
-                    } else {
-                        if (gl == 0) { st_l2(&cnt[t], uint8_t(cn)); st_l2(&nxt[n_nxt], int32_t(t)); }
-                        ++n_nxt;
-                    }
+                for (int c = 0; c < NCH; ++c) w[c] += dl * valid(g, c);
+                const int cn = changed ? 0 : s_cnt[j] + 1;
+                const bool drop = !changed && a.shrink_k > 0 && cn >= a.shrink_k;
+                int tail = head + n_rem;
+                if (tail >= cap) tail -= cap;
+                int32_t *slot = drop ? &rem[tail] : &nxt[n_nxt];
+                if (gl == 0) {
+                    st_wg(&alpha[t], an);
+                    st_wg(&cnt[t], uint8_t(cn));
+                    st_wg(slot, int32_t(t));
                 }
+                n_rem += drop ? 1 : 0;
+                n_nxt += drop ? 0 : 1;
             };
-            for (int j = 0; j < nb; j += 2) {
-                step(j, g0, g1);
-                if (j + 1 < nb) step(j + 1, g1, g0);
+            for (int j0 = 0; j0 < nb; j0 += D) {
+#pragma unroll
+                for (int u = 0; u < D; ++u)
+                    if (j0 + u < nb) step(j0 + u, gr[u], gr[(u + D - 1) % D]);
             }
         }
         ++epochs;
         if (maxviol <= a.eps) {
             // recompute w from alpha, then sweep over the removed variables with w fixed
-            __threadfence();
-            __syncthreads();
+            wg_sync();
             steps += recompute_w();
-            int back = 0;
+            int back = 0, kept = 0;
             const int m = n_rem;
-            for (int c = 0; c < m; ++c) {
-                const int t = ld_l2(&rem[head]);
-                head = head + 1 == cap ? 0 : head + 1;
-                --n_rem;
-                float v;
-                single(t, false, v);
-                ++steps;
-                if (v > a.eps) {
-                    if (gl == 0) { st_l2(&cnt[t], uint8_t(0)); st_l2(&nxt[n_nxt], int32_t(t)); }
-                    ++n_nxt;
-                    ++back;
-                } else {
-                    int tail = head + n_rem;
-                    if (tail >= cap) tail -= cap;
-                    if (gl == 0) st_l2(&rem[tail], int32_t(t));
-                    ++n_rem;
+            const int head0 = head;
+            for (int b0 = 0; b0 < m; b0 += BLK) {
+                const int nb = min(BLK, m - b0);
+                wg_sync();
+                if (gl < nb) {
+                    int at_ = head0 + b0 + gl;
+                    if (at_ >= cap) at_ -= cap;
+                    const int t = ld_wg(&rem[at_]);
+                    s_t[gl] = t;
+                    s_row[gl] = rows[t];
+                    s_y[gl] = y[t];
+                    s_alpha[gl] = ld_wg(&alpha[t]);
+                }
+                __syncthreads();
+                for (int j0 = 0; j0 < nb; j0 += D) {
+                    // D independent rows: loads, partial sums and reductions overlap
+                    cf32x4 g[D][NCH];
+                    float f[D];
+#pragma unroll
+                    for (int u = 0; u < D; ++u)
+                        if (j0 + u < nb) load_row(g[u], s_row[j0 + u]);
+#pragma unroll
+                    for (int u = 0; u < D; ++u) f[u] = j0 + u < nb ? dot(g[u], w) : 0.0f;
+#pragma unroll
+                    for (int u = 0; u < D; ++u) {
+                        if (j0 + u < nb) {
+                            const int t = s_t[j0 + u];
+                            const float grad = 1.0f - s_y[j0 + u] * f[u];
+                            ++steps;
+                            if (cd_violation(s_alpha[j0 + u], grad, C) > a.eps) {
+                                if (gl == 0) { st_wg(&cnt[t], uint8_t(0)); st_wg(&nxt[n_nxt], int32_t(t)); }
+                                ++n_nxt;
+                                ++back;
+                            } else {
+                                // kept entries are rewritten behind the old tail, in order; that region
+                                // only ever overlaps entries of the ring that were already consumed
+                                int tail = head0 + m + kept;
+                                if (tail >= cap) tail -= cap;
+                                if (tail >= cap) tail -= cap;
+                                if (gl == 0) st_wg(&rem[tail], int32_t(t));
+                                ++kept;
+                            }
+                        }
+                    }
                 }
             }
+            head = head0 + m;
+            if (head >= cap) head -= cap;
+            n_rem = kept;
             if (back == 0 && fresh) converged = 1;      // this epoch already started from a recomputed w
             fresh = 1;
         } else {
@@ -358,8 +417,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
     }
 
     // ---- results: w, dual objective, status
-    __threadfence();
-    __syncthreads();
+    wg_sync();
     float ww = 0.f, sa = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
@@ -371,7 +429,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
         if (col + 2 < r) wo[2] = w[c].z;
         if (col + 3 < r) wo[3] = w[c].w;
     }
-    for (int t = gl; t < np; t += T) sa += ld_l2(&alpha[t]);
+    for (int t = gl; t < np; t += T) sa += ld_wg(&alpha[t]);
     ww = block_sum(ww);
     sa = block_sum(sa);
     if (gl == 0) {

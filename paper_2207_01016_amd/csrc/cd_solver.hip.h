@@ -123,9 +123,11 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
     float *alpha = a.alpha + o0;
     uint8_t *cnt = a.cnt + o0;
     const int64_t stride = a.total + a.n_problems;
-    int32_t *act = a.lists + (o0 + p);
-    int32_t *nxt = act + stride;
-    int32_t *rem = nxt + stride;
+    // the three lists of this problem as offsets from one base pointer (the roles of the first two
+    // swap after every epoch; swapping integers keeps all list accesses plain global accesses)
+    int32_t *const lb = a.lists + (o0 + p);
+    int64_t o_act = 0, o_nxt = stride;      // recomputed from the epoch parity, never swapped
+    const int64_t o_rem = 2 * stride;
     const int cap = np + 1;
     const float C = a.C[p];
     const int r = a.r;
@@ -141,7 +143,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
         nvalid[c] = min(max(r - col, 0), 4);
         coff[c] = nvalid[c] > 0 ? col : 0;
     }
-    auto load_row = [&](cf32x4(&g)[NCH], int64_t row) {
+    auto load_row = [&](cf32x4(&g)[NCH], int64_t row) __attribute__((always_inline)) {
         const float *base = a.G + row * a.ldg;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
@@ -156,7 +158,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
             }
         }
     };
-    auto valid = [&](const cf32x4(&g)[NCH], int c) -> cf32x4 {
+    auto valid = [&](const cf32x4(&g)[NCH], int c) __attribute__((always_inline)) -> cf32x4 {
         cf32x4 v = g[c];
         if (ragged) {
             if (nvalid[c] < 1) v.x = 0.f;
@@ -167,7 +169,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
         return v;
     };
     int parity = 0;
-    auto block_sum = [&](float part) -> float {
+    auto block_sum = [&](float part) __attribute__((always_inline)) -> float {
         float s = wave_allsum(part);
         if (WAVES > 1) {
             if ((gl & 63) == 0) s_part[parity][wave] = s;
@@ -179,7 +181,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
         }
         return s;
     };
-    auto dot = [&](const cf32x4(&g)[NCH], const cf32x4(&w)[NCH]) -> float {
+    auto dot = [&](const cf32x4(&g)[NCH], const cf32x4(&w)[NCH]) __attribute__((always_inline)) -> float {
         float s0 = 0.f, s1 = 0.f;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
@@ -195,11 +197,11 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
     for (int c = 0; c < NCH; ++c) w[c] = cf32x4{0.f, 0.f, 0.f, 0.f};
 
     // ---- initial lists, counters, and w for a warm start
-    for (int t = gl; t < np; t += T) { st_wg(&act[t], int32_t(t)); st_wg(&cnt[t], uint8_t(0)); }
+    for (int t = gl; t < np; t += T) { st_wg(&lb[o_act + t], int32_t(t)); st_wg(&cnt[t], uint8_t(0)); }
     // w = sum_t alpha_t y_t g_t over the non-zero alpha, compensated (Kahan) summation in fp32:
     // used for a warm start and to shed the rounding drift of the incremental updates before
     // the stopping rule is verified.  Returns the number of rows read.
-    auto recompute_w = [&]() -> int {
+    auto recompute_w = [&]() __attribute__((always_inline)) -> int {
         cf32x4 comp[NCH];
 #pragma unroll
         for (int c = 0; c < NCH; ++c) { w[c] = cf32x4{0.f, 0.f, 0.f, 0.f}; comp[c] = cf32x4{0.f, 0.f, 0.f, 0.f}; }
@@ -249,7 +251,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
     float maxviol = 0.f;
 
     // one step on a removed variable (re-check) or a violation probe; slow path, no prefetch
-    auto single = [&](int t, bool apply, float &viol_out) -> bool {
+    auto single = [&](int t, bool apply, float &viol_out) __attribute__((always_inline)) -> bool {
         const int64_t row = rows[t];
         const float yt = y[t];
         const float at = ld_wg(&alpha[t]);
@@ -279,7 +281,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
             // gather the metadata of the next nb steps, one step per lane
             wg_sync();
             if (gl < nb) {
-                const int t = ld_wg(&act[b0 + gl]);
+                const int t = ld_wg(&lb[o_act + b0 + gl]);
                 const int64_t row = rows[t];
                 s_t[gl] = t;
                 s_row[gl] = row;
@@ -296,26 +298,27 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
 #pragma unroll
             for (int u = 0; u < D - 1; ++u)
                 if (u < nb) load_row(gr[u], s_row[u]);
-            auto step = [&](int j, const cf32x4(&g)[NCH], cf32x4(&gn)[NCH]) {
+            auto step = [&](int j, const cf32x4(&g)[NCH], cf32x4(&gn)[NCH]) __attribute__((always_inline)) {
                 // the eta share: one step on the head of the removed queue
                 if (a.shrink_k > 0 && a.check_every > 0 && since >= a.check_every && n_rem > 0) {
                     wg_sync();              // the lists are written by one lane: make its stores visible
-                    const int t = ld_wg(&rem[head]);
+                    const int t = ld_wg(&lb[o_rem + head]);
                     head = head + 1 == cap ? 0 : head + 1;
                     --n_rem;
                     float v;
                     const bool changed = single(t, true, v);
                     ++steps;
                     since = 0;
-                    if (changed) {
-                        if (gl == 0) { st_wg(&cnt[t], uint8_t(0)); st_wg(&nxt[n_nxt], int32_t(t)); }
-                        ++n_nxt;
-                    } else {
-                        int tail = head + n_rem;
-                        if (tail >= cap) tail -= cap;
-                        if (gl == 0) st_wg(&rem[tail], int32_t(t));
-                        ++n_rem;
+                    int tail = head + n_rem;
+                    if (tail >= cap) tail -= cap;
+                    const int64_t slot = changed ? o_nxt + n_nxt : o_rem + tail;
+                    if (gl == 0) {
+                        if (changed) st_wg(&cnt[t], uint8_t(0));
+                        st_wg(&lb[slot], int32_t(t));
                     }
+                    const int ch = changed ? 1 : 0;
+                    n_nxt += ch;
+                    n_rem += 1 - ch;
                 }
                 if (j + D - 1 < nb) load_row(gn, s_row[j + D - 1]);  // into the buffer step j-1 released
                 const int t = s_t[j];
@@ -336,14 +339,15 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
                 const bool drop = !changed && a.shrink_k > 0 && cn >= a.shrink_k;
                 int tail = head + n_rem;
                 if (tail >= cap) tail -= cap;
-                int32_t *slot = drop ? &rem[tail] : &nxt[n_nxt];
+                const int64_t slot = drop ? o_rem + tail : o_nxt + n_nxt;
                 if (gl == 0) {
                     st_wg(&alpha[t], an);
                     st_wg(&cnt[t], uint8_t(cn));
-                    st_wg(slot, int32_t(t));
+                    st_wg(&lb[slot], int32_t(t));
                 }
-                n_rem += drop ? 1 : 0;
-                n_nxt += drop ? 0 : 1;
+                const int dr = drop ? 1 : 0;
+                n_rem += dr;
+                n_nxt += 1 - dr;
             };
             for (int j0 = 0; j0 < nb; j0 += D) {
 #pragma unroll
@@ -365,7 +369,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
                 if (gl < nb) {
                     int at_ = head0 + b0 + gl;
                     if (at_ >= cap) at_ -= cap;
-                    const int t = ld_wg(&rem[at_]);
+                    const int t = ld_wg(&lb[o_rem + at_]);
                     s_t[gl] = t;
                     s_row[gl] = rows[t];
                     s_y[gl] = y[t];
@@ -387,19 +391,21 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
                             const int t = s_t[j0 + u];
                             const float grad = 1.0f - s_y[j0 + u] * f[u];
                             ++steps;
-                            if (cd_violation(s_alpha[j0 + u], grad, C) > a.eps) {
-                                if (gl == 0) { st_wg(&cnt[t], uint8_t(0)); st_wg(&nxt[n_nxt], int32_t(t)); }
-                                ++n_nxt;
-                                ++back;
-                            } else {
-                                // kept entries are rewritten behind the old tail, in order; that region
-                                // only ever overlaps entries of the ring that were already consumed
-                                int tail = head0 + m + kept;
-                                if (tail >= cap) tail -= cap;
-                                if (tail >= cap) tail -= cap;
-                                if (gl == 0) st_wg(&rem[tail], int32_t(t));
-                                ++kept;
+                            const bool viol = cd_violation(s_alpha[j0 + u], grad, C) > a.eps;
+                            // kept entries are rewritten behind the old tail, in order; that region
+                            // only ever overlaps entries of the ring that were already consumed
+                            int tail = head0 + m + kept;
+                            if (tail >= cap) tail -= cap;
+                            if (tail >= cap) tail -= cap;
+                            const int64_t slot = viol ? o_nxt + n_nxt : o_rem + tail;
+                            if (gl == 0) {
+                                if (viol) st_wg(&cnt[t], uint8_t(0));
+                                st_wg(&lb[slot], int32_t(t));
                             }
+                            const int vi = viol ? 1 : 0;
+                            n_nxt += vi;
+                            back += vi;
+                            kept += 1 - vi;
                         }
                     }
                 }
@@ -412,7 +418,8 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
         } else {
             fresh = 0;
         }
-        { int32_t *tmp = act; act = nxt; nxt = tmp; }
+        o_act = (epochs & 1) ? stride : 0;
+        o_nxt = stride - o_act;
         n_act = n_nxt;
     }
 

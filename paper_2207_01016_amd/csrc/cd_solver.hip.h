@@ -86,11 +86,25 @@ __device__ __forceinline__ void wg_sync()
     __syncthreads();
 }
 
+// Sum over the 64 lanes, returned as one wave-uniform value.  Data-parallel-primitive moves inside
+// the VALU (no LDS round trips): two quad permutes, half-row and row mirrors leave each row of 16
+// lanes holding its total; row broadcasts carry lane 15 into the next row and lane 31 into the upper
+// two rows, so lane 63 ends with the full sum, which is read into a scalar register.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false);
+    return v + __builtin_bit_cast(float, moved);
+}
 __device__ __forceinline__ float wave_allsum(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v = dpp_add<0xB1, 0xf>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E, 0xf>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x141, 0xf>(v);   // row_half_mirror
+    v = dpp_add<0x140, 0xf>(v);   // row_mirror
+    v = dpp_add<0x142, 0xa>(v);   // row_bcast15 into rows 1 and 3
+    v = dpp_add<0x143, 0xc>(v);   // row_bcast31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 __device__ __forceinline__ float cd_violation(float alpha, float grad, float C)
@@ -288,7 +302,8 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
                 s_y[gl] = y[t];
                 s_alpha[gl] = ld_wg(&alpha[t]);
                 s_cnt[gl] = ld_wg(&cnt[t]);
-                s_q[gl] = a.gsq[row];
+                const float qq = a.gsq[row];
+                s_q[gl] = qq > 0.0f ? 1.0f / qq : 0.0f;     // reciprocal, off the steps' dependent path
             }
             __syncthreads();
             // ring of D row buffers: the row of step j + D - 1 is requested at step j, so D - 1 row
@@ -322,10 +337,10 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
                 }
                 if (j + D - 1 < nb) load_row(gn, s_row[j + D - 1]);  // into the buffer step j-1 released
                 const int t = s_t[j];
-                const float yt = s_y[j], at = s_alpha[j], q = s_q[j];
+                const float yt = s_y[j], at = s_alpha[j], qinv = s_q[j];
                 const float grad = 1.0f - yt * dot(g, w);            // step 2a
                 maxviol = fmaxf(maxviol, cd_violation(at, grad, C));
-                float an = q > 0.0f ? at + grad / q : C;             // step 2b
+                float an = qinv > 0.0f ? at + grad * qinv : C;       // step 2b
                 an = fminf(fmaxf(an, 0.0f), C);
                 ++steps;
                 ++since;

@@ -400,3 +400,41 @@ void orc_cd_solve(const float *G, int64_t r, int64_t ldg,
     stats[5] = sa - 0.5 * ww;
     free(act); free(nxt); free(rem); free(cnt);
 }
+
+/* ------------------------------------------------------------------------
+ * Prediction (Section 3, "Algorithm Overview": the prediction step; Section 2:
+ * f(x) = <w, phi(x)>, no offset).  In the low-rank feature space the features of
+ * a new point x are g(x) = W z(x), z(x)_b = k(x, l_b) -- the same map that
+ * produced the rows of G (Figure 1, 1d) -- and classifier j scores it with
+ * f_j(x) = ws_j . g(x) (Figure 1, 2a).  Written out exactly so: kernel row by
+ * direct differences, then W, then the weight vectors; nothing is folded.
+ * X: n x d, L: B x d, W: r x B (ldw), Ws: c x r (ldws), F: n x c double.
+ * ------------------------------------------------------------------------ */
+void orc_predict(const float *X, int64_t n, int64_t d, int64_t ldx,
+                 const float *L, int64_t B, int64_t ldl, double gamma,
+                 const float *W, int64_t r, int64_t ldw,
+                 const float *Ws, int64_t c, int64_t ldws, double *F)
+{
+#pragma omp parallel
+    {
+        double *z = (double *)malloc((size_t)(B > 0 ? B : 1) * sizeof(double));
+        double *g = (double *)malloc((size_t)(r > 0 ? r : 1) * sizeof(double));
+#pragma omp for schedule(static)
+        for (int64_t i = 0; i < n; ++i) {
+            for (int64_t b = 0; b < B; ++b)
+                z[b] = gauss_kernel(X + i * ldx, L + b * ldl, d, gamma);
+            for (int64_t j = 0; j < r; ++j) {
+                double s = 0.0;
+                for (int64_t b = 0; b < B; ++b) s += (double)W[j * ldw + b] * z[b];
+                g[j] = s;
+            }
+            for (int64_t q = 0; q < c; ++q) {
+                double s = 0.0;
+                for (int64_t j = 0; j < r; ++j) s += (double)Ws[q * ldws + j] * g[j];
+                F[i * c + q] = s;
+            }
+        }
+        free(z);
+        free(g);
+    }
+}

@@ -64,6 +64,9 @@ def _load():
         lib.orc_cd_solve.argtypes = [_f32p, _i64, _i64, ctypes.POINTER(_i64), _f32p, _i64, ctypes.c_double,
                                      ctypes.c_double, _i64, _i64, ctypes.c_double, _f64p, _f64p, _f64p]
         lib.orc_cd_solve.restype = None
+        lib.orc_predict.argtypes = [_f32p, _i64, _i64, _i64, _f32p, _i64, _i64, ctypes.c_double, _f32p, _i64, _i64,
+                                    _f32p, _i64, _i64, _f64p]
+        lib.orc_predict.restype = None
         lib.orc_num_threads.restype = ctypes.c_int
         lib.orc_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -203,3 +206,18 @@ def cd_solve(G, rows, y, C: float, eps: float = 1e-3, max_epochs: int = 1000, sh
                          float(eps), int(max_epochs), int(shrink_k), float(eta), _p64(alpha), _p64(w), _p64(stats))
     return alpha, w, {"epochs": int(stats[0]), "steps": int(stats[1]), "converged": bool(stats[2]),
                       "active": int(stats[3]), "max_violation": float(stats[4]), "dual": float(stats[5])}
+
+
+def predict(X, L, gamma: float, W, Ws, r: int | None = None) -> np.ndarray:
+    """Scores f_j(x_i) = ws_j . (W z(x_i)) of c classifiers (Section 3 prediction step). Ws: c x r. Returns n x c."""
+    X, L, W = _f32(X), _f32(L), _f32(W)
+    Ws = np.atleast_2d(_f32(Ws))
+    n, d = X.shape
+    B = L.shape[0]
+    r = W.shape[0] if r is None else int(r)
+    c = Ws.shape[0]
+    assert W.shape[1] == B and Ws.shape[1] >= r and L.shape[1] == d
+    F = np.empty((n, c), dtype=np.float64)
+    _load().orc_predict(_p32(X), n, d, d, _p32(L), B, d, float(gamma), _p32(W), r, W.shape[1],
+                        _p32(Ws), c, Ws.shape[1], _p64(F))
+    return F

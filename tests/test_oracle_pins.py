@@ -263,3 +263,46 @@ def test_workload_recipes_keep_landmark_kernel_well_conditioned(oracle):
         W, eig, rank, _ = oracle.whiten(X[idx], small.gamma)
         assert rank == 64, name
         assert eig[-1] > 1e-3, (name, eig[-1])
+
+
+# ---------------------------------------------------------------- prediction (Section 3, prediction step)
+
+def test_predict_closed_form_two_landmarks(oracle):
+    rows, Wg, Dg = _read_golden()
+    Lm = np.array([[0.0], [1.0]], dtype=np.float32)
+    X = rows[:, :1].astype(np.float32)
+    F = oracle.predict(X, Lm, math.log(2.0), Wg.astype(np.float32), np.array([[2.0, -3.0]], dtype=np.float32))
+    assert np.allclose(F[:, 0], rows[:, 5], atol=1e-6)          # fp32 W: 1/sqrt(3) is rounded
+
+
+def test_predict_on_training_rows_equals_margins_of_the_factor(oracle):
+    X = _points(20, 90, 6)
+    idx = np.arange(0, 90, 3)
+    gamma = 0.2
+    W, eig, rank, _ = oracle.whiten(X[idx], gamma)
+    W32 = W.astype(np.float32)
+    G = oracle.nystrom_factor(X, X[idx], gamma, W32)
+    Ws = _rng(21).standard_normal((3, rank)).astype(np.float32)
+    F = oracle.predict(X, X[idx], gamma, W32, Ws)
+    for j in range(3):
+        assert np.allclose(F[:, j], oracle.margins_f64(G, Ws[j].astype(np.float64)), atol=1e-12)
+
+
+def test_predict_is_the_kernel_expansion_when_all_points_are_landmarks(oracle):
+    # B = n: the low-rank kernel is exact, so with w = sum_i a_i y_i g_i the score of a NEW point x is the
+    # representer form f(x) = sum_i a_i y_i k(x, x_i) of Section 2, computed here by an independent loop
+    n, d, gamma = 20, 3, 0.3
+    X = _points(22, n, d)
+    Xt = _points(23, 7, d)
+    W, eig, rank, _ = oracle.whiten(X, gamma)
+    assert rank == n
+    G = oracle.apply_whitening(oracle.kernel_block(X, X, gamma), W)
+    coef = _rng(24).standard_normal(n)                      # a_i y_i
+    w = coef @ G
+    F = oracle.predict(Xt, X, gamma, W.astype(np.float32), w.astype(np.float32)[None, :])
+    for t in range(7):
+        ref = 0.0
+        for i in range(n):
+            dist = sum((float(Xt[t, k]) - float(X[i, k])) ** 2 for k in range(d))
+            ref += coef[i] * math.exp(-gamma * dist)
+        assert abs(F[t, 0] - ref) <= 1e-4 * max(1.0, abs(ref))   # W and w were rounded to fp32

@@ -181,6 +181,30 @@ int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg,
                      const float *w, float *m, void *hip_stream);
 
 /*
+ * Prediction (Section 3, "Algorithm Overview": the prediction step; Section 2: f(x) = <w, phi(x)>,
+ * no offset).  A classifier trained on the rows of G has weights ws (r values); a new point x has
+ * features W z(x), z(x)_b = exp(-gamma ||x - l_b||^2), so its score is ws . (W z(x)) = v . z(x) with
+ * v = W^T ws folded once per classifier.
+ *
+ * lpd_fold_weights:  V[j, b] = sum_{k<r} Ws[j, k] * W[k, b]     (c x B)
+ *   W device in r x B (ldw);  Ws device in c x r (ldws), one classifier per row;  V device out c x B (ldv)
+ * lpd_predict:       F[i, j] = sum_b V[j, b] * exp(-gamma ||x_i - l_b||^2)     (n x c),  c <= B
+ *   X device in n x d (ldx);  L device in B x d (ldl);  V device in c x B (ldv);  F device out n x c (ldf)
+ *   workspace: as for lpd_nystrom_factor (lpd_nystrom_factor_workspace(n, d, B)); the kernel block is
+ *   produced panel by panel and consumed at once, by one sweep per classifier for c <= 4, by the MFMA
+ *   product otherwise.
+ * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE (incl. c > B), LPD_ERR_LD, LPD_ERR_WORKSPACE, LPD_ERR_HIP.
+ */
+int lpd_fold_weights(const float *W, int64_t r, int64_t B, int64_t ldw,
+                     const float *Ws, int64_t c, int64_t ldws,
+                     float *V, int64_t ldv, void *hip_stream);
+int lpd_predict(const float *X, int64_t n, int64_t d, int64_t ldx,
+                const float *L, int64_t B, int64_t ldl, float gamma,
+                const float *V, int64_t c, int64_t ldv,
+                float *F, int64_t ldf,
+                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Squared norms of the rows of the factor, gsq[i] = sum_{j<r} G[i,j]^2: the
  * diagonal Q_ii of the dual problem (Section 2, equation (2)) that the
  * coordinate step divides by.  G device in n x r (ldg); gsq device out, n floats.

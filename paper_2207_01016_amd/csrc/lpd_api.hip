@@ -146,25 +146,25 @@ hipError_t launch_sqnorm(const float *X, int64_t n, int64_t d, int64_t ldx, floa
 
 template <int LPR, bool INDEXED, int ROWS>
 hipError_t launch_margins_lpr(const float *G, int64_t n_out, int r, int64_t ldg, const int64_t *rows,
-                              const float *w, float *m, bool vec, hipStream_t s)
+                              const float *w, float *m, int64_t ms, bool vec, hipStream_t s)
 {
     const unsigned grid = row_grid(n_out, 256 / LPR * ROWS);
-    if (vec) hipLaunchKernelGGL((margins_kernel<LPR, true, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m);
-    else hipLaunchKernelGGL((margins_kernel<LPR, false, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m);
+    if (vec) hipLaunchKernelGGL((margins_kernel<LPR, true, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m, ms);
+    else hipLaunchKernelGGL((margins_kernel<LPR, false, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m, ms);
     return hipGetLastError();
 }
 
 template <bool INDEXED>
 hipError_t launch_margins(const float *G, int64_t n_out, int64_t r, int64_t ldg, const int64_t *rows,
-                          const float *w, float *m, hipStream_t s)
+                          const float *w, float *m, hipStream_t s, int64_t ms = 1)
 {
     const bool vec = aligned16(G) && aligned16(w) && ldg % 4 == 0;
     const int ri = int(r);
-    if (r >= 1024) return launch_margins_lpr<64, INDEXED, 2>(G, n_out, ri, ldg, rows, w, m, vec, s);
-    if (r >= 256) return launch_margins_lpr<64, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, vec, s);
-    if (r >= 128) return launch_margins_lpr<32, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, vec, s);
-    if (r >= 64) return launch_margins_lpr<16, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, vec, s);
-    return launch_margins_lpr<8, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, vec, s);
+    if (r >= 1024) return launch_margins_lpr<64, INDEXED, 2>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
+    if (r >= 256) return launch_margins_lpr<64, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
+    if (r >= 128) return launch_margins_lpr<32, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
+    if (r >= 64) return launch_margins_lpr<16, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
+    return launch_margins_lpr<8, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
 }
 
 // ---------------------------------------------------------------- factor schedule
@@ -212,11 +212,14 @@ int check_factor_args(const float *X, int64_t n, int64_t d, int64_t ldx, const f
         if (e__ != hipSuccess) { status = LPD_ERR_HIP; goto done; } \
     } while (0)
 
+// Shared schedule of the factor (out_cols = B: G = Z W^T with zero fill of columns r..B-1) and of
+// prediction (out_cols = r = number of classifiers, W = their folded weight rows: F = Z V^T).
 int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,
-                float gamma, const float *W, int64_t r, int64_t ldw, float *G, int64_t ldg, void *workspace,
-                size_t workspace_bytes, hipStream_t s, lpd_factor_profile *prof)
+                float gamma, const float *W, int64_t r, int64_t ldw, float *G, int64_t ldg, int64_t out_cols,
+                void *workspace, size_t workspace_bytes, hipStream_t s, lpd_factor_profile *prof)
 {
-    int status = check_factor_args(X, n, d, ldx, L, B, ldl, W, r, ldw, G, ldg);
+    int status = check_factor_args(X, n, d, ldx, L, B, ldl, W, r, ldw, G, out_cols == B ? ldg : std::max(ldg, B));
+    if (status == LPD_OK && ldg < out_cols) status = LPD_ERR_LD;
     if (prof) std::memset(prof, 0, sizeof(*prof));
     if (status != LPD_OK || n == 0 || B == 0) return status;
 
@@ -256,9 +259,16 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
         k2.A = Z; k2.lda = c.ldz;
         k2.B = W; k2.ldb = ldw;
         k2.C = G + p0 * ldg; k2.ldc = ldg;
-        k2.M = int(rows); k2.N = int(r); k2.K = int(B); k2.n_store = int(B);
+        k2.M = int(rows); k2.N = int(r); k2.K = int(B); k2.n_store = int(out_cols);
         LPD_HIP(log.begin(2, s));
-        LPD_HIP(launch_gemm(k2, EPI_STORE, s));
+        if (out_cols != B && r <= 4) {
+            // a handful of classifiers: one bandwidth-bound sweep of the panel per classifier instead of
+            // an MFMA tile that would be 97 % padding
+            for (int64_t j = 0; j < r; ++j)
+                LPD_HIP(launch_margins<false>(Z, rows, B, c.ldz, nullptr, W + j * ldw, G + p0 * ldg + j, s, ldg));
+        } else {
+            LPD_HIP(launch_gemm(k2, EPI_STORE, s));
+        }
         LPD_HIP(log.end(s));
     }
 
@@ -325,7 +335,7 @@ int lpd_nystrom_factor(const float *X, int64_t n, int64_t d, int64_t ldx, const 
                        float gamma, const float *W, int64_t r, int64_t ldw, float *G, int64_t ldg,
                        void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    return factor_impl(X, n, d, ldx, L, B, ldl, gamma, W, r, ldw, G, ldg, workspace, workspace_bytes,
+    return factor_impl(X, n, d, ldx, L, B, ldl, gamma, W, r, ldw, G, ldg, B, workspace, workspace_bytes,
                        static_cast<hipStream_t>(hip_stream), nullptr);
 }
 
@@ -335,7 +345,7 @@ int lpd_nystrom_factor_profiled(const float *X, int64_t n, int64_t d, int64_t ld
                                 lpd_factor_profile *profile)
 {
     if (!profile) return LPD_ERR_NULL;
-    return factor_impl(X, n, d, ldx, L, B, ldl, gamma, W, r, ldw, G, ldg, workspace, workspace_bytes,
+    return factor_impl(X, n, d, ldx, L, B, ldl, gamma, W, r, ldw, G, ldg, B, workspace, workspace_bytes,
                        static_cast<hipStream_t>(hip_stream), profile);
 }
 
@@ -388,6 +398,30 @@ int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg, const in
     if (ldg < r) return LPD_ERR_LD;
     hipError_t e = launch_margins<true>(G, n_rows, r, ldg, rows, w, m, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+}
+
+int lpd_fold_weights(const float *W, int64_t r, int64_t B, int64_t ldw, const float *Ws, int64_t c, int64_t ldws,
+                     float *V, int64_t ldv, void *hip_stream)
+{
+    if (r < 0 || B < 0 || c < 0 || r > kMaxDim || B > kMaxDim || c > 65535 * 8) return LPD_ERR_SHAPE;
+    if (c == 0 || B == 0) return LPD_OK;
+    if (!V || (r > 0 && (!W || !Ws))) return LPD_ERR_NULL;
+    if (ldv < B || (r > 0 && (ldw < B || ldws < r))) return LPD_ERR_LD;
+    constexpr int CPT = 8;
+    const dim3 grid(unsigned((B + 255) / 256), unsigned((c + CPT - 1) / CPT));
+    hipLaunchKernelGGL((fold_weights_kernel<CPT>), grid, dim3(256), 0, static_cast<hipStream_t>(hip_stream), W,
+                       int(r), int(B), ldw, Ws, int(c), ldws, V, ldv);
+    return hipGetLastError() == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+}
+
+int lpd_predict(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,
+                float gamma, const float *V, int64_t c, int64_t ldv, float *F, int64_t ldf, void *workspace,
+                size_t workspace_bytes, void *hip_stream)
+{
+    if (c < 0 || c > B) return LPD_ERR_SHAPE;
+    if (c == 0) return LPD_OK;
+    return factor_impl(X, n, d, ldx, L, B, ldl, gamma, V, c, ldv, F, ldf, c == B ? B : c, workspace, workspace_bytes,
+                       static_cast<hipStream_t>(hip_stream), nullptr);
 }
 
 int lpd_row_sqnorms(const float *G, int64_t n, int64_t r, int64_t ldg, float *gsq, void *hip_stream)

@@ -30,7 +30,8 @@ __device__ __forceinline__ float group_sum(float v)
 template <int LPR, bool VEC, bool INDEXED, int ROWS>
 __global__ __launch_bounds__(256) void margins_kernel(const float *__restrict__ G, int64_t n_out, int r,
                                                       int64_t ldg, const int64_t *__restrict__ rows,
-                                                      const float *__restrict__ w, float *__restrict__ m)
+                                                      const float *__restrict__ w, float *__restrict__ m,
+                                                      int64_t m_stride)
 {
     constexpr int GROUPS = 256 / LPR;             // lane groups per workgroup
     const int sub = threadIdx.x % LPR;
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256) void margins_kernel(const float *__restrict__ 
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
             const float tot = group_sum<LPR>((s[q][0] + s[q][1]) + (s[q][2] + s[q][3]));
-            if (sub == 0 && t0 + q < n_out) m[t0 + q] = tot;
+            if (sub == 0 && t0 + q < n_out) m[(t0 + q) * m_stride] = tot;
         }
     }
 }
@@ -115,6 +116,32 @@ __global__ __launch_bounds__(256) void sqnorm_kernel(const float *__restrict__ X
         const float s = group_sum<LPR>(s0 + s1);
         if (sub == 0) out[i] = s;
     }
+}
+
+// V[j, b] = sum_k Ws[j, k] * W[k, b]: classifier weights folded through the whitening map, so that a
+// score becomes one inner product with the kernel row, f_j(x) = V_j . z(x) (Section 3, prediction step).
+// One thread per column b of W, CPT classifiers per pass held in registers; W is streamed once per
+// pass with coalesced rows, the CPT weights of row k are broadcast loads.
+template <int CPT>
+__global__ __launch_bounds__(256) void fold_weights_kernel(const float *__restrict__ W, int r, int B, int64_t ldw,
+                                                           const float *__restrict__ Ws, int c, int64_t ldws,
+                                                           float *__restrict__ V, int64_t ldv)
+{
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    const int j0 = blockIdx.y * CPT;
+    if (b >= B) return;
+    float acc[CPT];
+#pragma unroll
+    for (int q = 0; q < CPT; ++q) acc[q] = 0.f;
+    for (int k = 0; k < r; ++k) {
+        const float wkb = W[int64_t(k) * ldw + b];
+#pragma unroll
+        for (int q = 0; q < CPT; ++q)
+            if (j0 + q < c) acc[q] += Ws[int64_t(j0 + q) * ldws + k] * wkb;
+    }
+#pragma unroll
+    for (int q = 0; q < CPT; ++q)
+        if (j0 + q < c) V[int64_t(j0 + q) * ldv + b] = acc[q];
 }
 
 }  // namespace lpd

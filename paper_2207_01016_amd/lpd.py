@@ -57,6 +57,9 @@ SIGNATURES = {
                                         _vp]),
     "lpd_margins": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp, _vp]),
     "lpd_margins_rows": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
+    "lpd_fold_weights": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, _vp, _i64, _vp]),
+    "lpd_predict": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _i64, _vp, _i64,
+                                   _vp, _sz, _vp]),
     "lpd_row_sqnorms": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp]),
     "lpd_cd_solve_workspace": (ctypes.c_int, [_i64, _i64, ctypes.POINTER(_sz)]),
     "lpd_cd_solve": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp,
@@ -314,3 +317,45 @@ def lpd_cd_solve(G, gsq, prob_off, rows, y, C, alpha, w=None, eps: float = 1e-3,
     import numpy as np
     rec = np.frombuffer(status.cpu().numpy().tobytes(), dtype=np.dtype(CD_STATUS_DTYPE))[:P]
     return alpha, w, rec
+
+
+def lpd_fold_weights(W, Ws, V=None, r: int | None = None) -> torch.Tensor:
+    """V = Ws[:, :r] W[:r]: classifier weights folded through the whitening map (c x B)."""
+    W = _dev_f32(W, "W", 2)
+    Ws = _dev_f32(Ws, "Ws", 2)
+    r = W.shape[0] if r is None else int(r)
+    B = W.shape[1]
+    c = Ws.shape[0]
+    if r > W.shape[0] or r > Ws.shape[1]:
+        raise ValueError("r exceeds W or Ws")
+    if V is None:
+        V = torch.empty((c, B), dtype=torch.float32, device=W.device)
+    V = _dev_f32(V, "V", 2)
+    if V.shape != (c, B):
+        raise ValueError("V must be c x B")
+    _check(lib().lpd_fold_weights(W.data_ptr(), r, B, _ld(W), Ws.data_ptr(), c, _ld(Ws), V.data_ptr(), _ld(V),
+                                  _stream(W.device)), "lpd_fold_weights")
+    return V
+
+
+def lpd_predict(X, L, gamma: float, V, F=None, workspace=None) -> torch.Tensor:
+    """Scores F[i, j] = V[j] . K(x_i, L) of c folded classifiers (n x c)."""
+    X = _dev_f32(X, "X", 2)
+    L = _dev_f32(L, "L", 2)
+    V = _dev_f32(V, "V", 2)
+    n, d = X.shape
+    B = L.shape[0]
+    c = V.shape[0]
+    if L.shape[1] != d or V.shape[1] != B:
+        raise ValueError("shape mismatch: X n x d, L B x d, V c x B")
+    if F is None:
+        F = torch.empty((n, c), dtype=torch.float32, device=X.device)
+    F = _dev_f32(F, "F", 2)
+    if F.shape != (n, c):
+        raise ValueError("F must be n x c")
+    if workspace is None:
+        workspace = alloc_workspace(n, d, B, X.device)
+    st = lib().lpd_predict(X.data_ptr(), n, d, _ld(X), L.data_ptr(), B, _ld(L), float(gamma), V.data_ptr(), c, _ld(V),
+                           F.data_ptr(), _ld(F), workspace.data_ptr(), workspace.numel(), _stream(X.device))
+    _check(st, "lpd_predict")
+    return F

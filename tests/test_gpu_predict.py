@@ -1,0 +1,100 @@
+"""GPU parity for prediction (lpd_fold_weights + lpd_predict) against the CPU oracle.
+
+The oracle scores a point as ws . (W z(x)) -- features first, then the classifier, nothing folded;
+the GPU folds v = W^T ws once and takes v . z(x).  Tolerance: relative Frobenius error <= 1e-4, as
+for the factor (the scores are sums of the same products).
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+def relfro(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available()
+    return torch.device("cuda:0")
+
+
+@pytest.fixture(scope="module")
+def lpd():
+    from paper_2207_01016_amd import lpd as mod
+    mod.lib()
+    return mod
+
+
+@pytest.mark.parametrize("r,B,c", [(50, 70, 1), (70, 70, 9), (128, 128, 16), (300, 333, 40)])
+def test_fold_weights(lpd, dev, r, B, c):
+    g = torch.Generator().manual_seed(r + B + c)
+    W = torch.randn((B, B), generator=g).to(dev)
+    Ws = torch.randn((c, r + 3), generator=g).to(dev)
+    V = lpd.lpd_fold_weights(W, Ws[:, :r], r=r)
+    torch.cuda.synchronize()
+    ref = Ws[:, :r].double().cpu().numpy() @ W[:r].double().cpu().numpy()
+    assert relfro(V.cpu().numpy(), ref) <= 1e-5
+
+
+@pytest.mark.parametrize("name,n,B,n_test,c", [
+    ("tiny", 1500, 128, 777, 1),
+    ("small", 6000, 512, 2500, 3),       # sweep path (c <= 4), several panels
+    ("digit", 3000, 300, 1111, 10),      # MFMA path, nothing a multiple of a tile
+    ("cnn", 2500, 260, 900, 45),
+    ("highrank", 4000, 640, 2000, 130),
+])
+def test_predict_matches_oracle(lpd, oracle, dev, name, n, B, n_test, c):
+    from paper_2207_01016_amd import workloads
+    wl = workloads.WORKLOADS[name].with_shape(n=n + n_test, B=B)
+    X_all = workloads.make_X(wl, dev)
+    X, Xt = X_all[:n], X_all[n:].contiguous()
+    idx = workloads.landmark_indices(wl.with_rows(n))
+    L = X[idx.to(dev)].contiguous()
+    W, eig, rank = lpd.lpd_whiten_host(L.cpu(), wl.gamma)
+    g = torch.Generator().manual_seed(c)
+    Ws = torch.randn((c, rank), generator=g) / rank ** 0.5
+    V = lpd.lpd_fold_weights(W.to(dev), Ws.to(dev), r=rank)
+    _, mn = lpd.lpd_nystrom_factor_workspace(n_test, wl.d, B)
+    ws = lpd.alloc_workspace(n_test, wl.d, B, dev, mn * 3)           # several panels, ragged last one
+    F = torch.full((n_test, c), float("nan"), dtype=torch.float32, device=dev)
+    lpd.lpd_predict(Xt, L, wl.gamma, V, F, ws)
+    torch.cuda.synchronize()
+    ref = oracle.predict(Xt.cpu().numpy(), L.cpu().numpy(), wl.gamma, W.numpy(), Ws.numpy(), r=rank)
+    Fh = F.cpu().numpy()
+    assert np.all(np.isfinite(Fh))
+    assert relfro(Fh, ref) <= 1e-4
+
+
+def test_predict_on_training_rows_equals_margins_of_the_factor(lpd, dev):
+    from paper_2207_01016_amd import workloads
+    wl = workloads.WORKLOADS["small"].with_shape(n=3000, B=256)
+    X = workloads.make_X(wl, dev)
+    L = X[workloads.landmark_indices(wl).to(dev)].contiguous()
+    W, eig, rank = lpd.lpd_whiten_host(L.cpu(), wl.gamma)
+    Wd = W.to(dev)
+    G = torch.empty((wl.n, wl.B), dtype=torch.float32, device=dev)
+    lpd.lpd_nystrom_factor(X, L, wl.gamma, Wd, G, lpd.alloc_workspace(wl.n, wl.d, wl.B, dev), r=rank)
+    w = workloads.make_w(wl).to(dev)
+    m = lpd.lpd_margins(G, w, r=rank)
+    V = lpd.lpd_fold_weights(Wd, w[None, :].contiguous(), r=rank)
+    F = lpd.lpd_predict(X, L, wl.gamma, V)
+    torch.cuda.synchronize()
+    assert float((F[:, 0].double() - m.double()).norm() / m.double().norm()) <= 1e-4
+
+
+def test_predict_strided_output_and_zero_classifiers(lpd, dev):
+    g = torch.Generator().manual_seed(3)
+    X = torch.randn((500, 12), generator=g).to(dev)
+    L = X[:40].contiguous()
+    V = torch.randn((2, 40), generator=g).to(dev)
+    Fbig = torch.zeros((500, 5), dtype=torch.float32, device=dev)
+    lpd.lpd_predict(X, L, 0.1, V, Fbig[:, :2])
+    torch.cuda.synchronize()
+    assert torch.all(Fbig[:, 2:] == 0) and bool(Fbig[:, :2].abs().sum() > 0)
+    ref = torch.exp(-0.1 * torch.cdist(X.double(), L.double()) ** 2) @ V.double().T
+    assert float((Fbig[:, :2].double() - ref).norm() / ref.norm()) <= 1e-5

@@ -45,8 +45,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", default="auto", choices=["auto", "128x128", "256x128", "256x256"])
     ap.add_argument("--workspace-mult", type=float, default=1.0)
-    ap.add_argument("--path", default="factor", choices=["factor", "solver"],
-                    help="factor: Nystrom factor + margin sweep (default); solver: batched dual coordinate ascent on G")
+    ap.add_argument("--path", default="factor", choices=["factor", "solver", "predict"],
+                    help="factor: Nystrom factor + margin sweep (default); solver: batched dual coordinate ascent "
+                         "on G; predict: scores of new points")
+    ap.add_argument("--classifiers", type=int, default=10, help="predict: number of classifiers scored at once")
     ap.add_argument("--random-w", action="store_true",
                     help="skip the host eigendecomposition and use a random W (tuning only; marks the line invalid)")
     return ap.parse_args()
@@ -184,6 +186,85 @@ def bench_solver(args):
     print(json.dumps(out))
 
 
+def bench_predict(args):
+    """Prediction: scores of c classifiers for the first rows of the workload taken as new points."""
+    import numpy as np
+    import torch
+    from paper_2207_01016_amd import lpd, workloads
+    dev = torch.device("cuda:0")
+    wl = workloads.WORKLOADS[args.workload]
+    n_test = min(wl.n, 262144)
+    X = workloads.make_X(wl.with_rows(max(n_test, wl.B)), dev)
+    idx = workloads.landmark_indices(wl.with_rows(max(n_test, wl.B)))
+    L = X[idx.to(dev)].contiguous()
+    Xt = X[:n_test]
+    t0 = time.perf_counter()
+    if args.random_w:
+        W_host = torch.randn((wl.B, wl.B), generator=torch.Generator().manual_seed(1)) / wl.B ** 0.5
+        rank = wl.B
+    else:
+        W_host, eig, rank = lpd.lpd_whiten_host(L.cpu(), wl.gamma)
+    t_whiten = time.perf_counter() - t0
+    c = args.classifiers
+    Ws = (torch.randn((c, rank), generator=torch.Generator().manual_seed(2)) / rank ** 0.5)
+    W = W_host.to(dev)
+    V = lpd.lpd_fold_weights(W, Ws.to(dev), r=rank)
+    F = torch.empty((n_test, c), dtype=torch.float32, device=dev)
+    ws = lpd.alloc_workspace(n_test, wl.d, wl.B, dev)
+    evs = []
+
+    def step(collect):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        lpd.lpd_predict(Xt, L, wl.gamma, V, F, ws)
+        e1.record()
+        if collect:
+            evs.append((e0, e1))
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
+    flop = 2.0 * n_test * wl.B * (wl.d + (c if c > 4 else 0))
+    tflops = flop / (ms * 1e-3) / 1e12
+    out = {
+        "metric": "prediction_rows_per_s", "value": n_test * len(evs) / elapsed, "unit": "rows/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed * 1e3 / len(evs),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic" + (" (random W: tuning run)" if args.random_w else ""),
+        "config": {"workload": wl.name + " (first rows as new points)", "n_test": n_test, "d": wl.d, "B": wl.B,
+                   "rank": rank, "classifiers": c, "gamma": wl.gamma},
+        "whiten_host_s": None if args.random_w else t_whiten,
+        "roofline": {"kernel": "lpd_predict: gemm_nt_kernel<EPI_GAUSS> panels + consumer", "bound": "mfma",
+                     "achieved": tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / FP32_MFMA_PEAK_TFLOPS, "flop_per_launch": flop, "avg_launch_ms": ms,
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import lpd_oracle as orc
+        Xs = Xt[: 1 << 14].cpu().numpy()
+        Lh, Wh, Wsh = L.cpu().numpy(), W_host[:rank].numpy(), Ws.numpy()
+        probe = 32
+        t0 = time.perf_counter()
+        orc.predict(Xs[:probe], Lh, wl.gamma, Wh, Wsh, r=rank)
+        per_row = (time.perf_counter() - t0) / probe
+        m = int(max(probe, min(Xs.shape[0], args.cpu_seconds / max(per_row, 1e-9))))
+        t0 = time.perf_counter()
+        orc.predict(Xs[:m], Lh, wl.gamma, Wh, Wsh, r=rank)
+        t_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": m / t_cpu, "unit": "rows/s", "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"first {m} of the {n_test} new points, all {wl.B} landmarks, "
+                                         f"{c} classifiers, double precision, {t_cpu:.1f} s",
+                               "gpu_over_cpu": out["value"] / (m / t_cpu)}
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -200,6 +281,9 @@ def main():
     lpd.lib()
     if args.path == "solver":
         bench_solver(args)
+        return
+    if args.path == "predict":
+        bench_predict(args)
         return
     dev = torch.device("cuda:0")
     wl = workloads.WORKLOADS[args.workload]

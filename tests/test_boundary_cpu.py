@@ -85,6 +85,35 @@ def test_margins_and_kernel_block_argument_errors(L):
     assert L.lpd_set_option(1, 9) == -2 and L.lpd_set_option(77, 0) == -2
 
 
+def test_solver_and_predict_argument_errors(L):
+    buf = (ctypes.c_float * 4096)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    nb = ctypes.c_size_t(0)
+    assert L.lpd_cd_solve_workspace(3, 100, ctypes.byref(nb)) == 0 and nb.value >= 3 * 103 * 4 + 100
+    assert L.lpd_cd_solve_workspace(-1, 100, ctypes.byref(nb)) == -2
+    cd = L.lpd_cd_solve
+    #       G  n   r  ldg gsq P  off tot rows y  C  alpha w  ldw st eps  ep  k  eta  ws    bytes stream
+    assert cd(p, 10, 8, 8, p, 0, p, 0, p, p, p, p, p, 8, p, 1e-3, 10, 5, 0.05, None, 0, None) == 0     # no problems
+    assert cd(p, 10, 8, 8, p, 1, p, 10, p, p, p, p, p, 8, p, 1e-3, 10, 5, 0.05, None, 0, None) == -4   # no workspace
+    assert cd(p, 10, 8, 7, p, 1, p, 10, p, p, p, p, p, 8, p, 1e-3, 10, 5, 0.05, p, 4096, None) == -3   # ldg < r
+    assert cd(p, 10, 8, 8, p, 1, p, 10, p, p, p, p, p, 7, p, 1e-3, 10, 5, 0.05, p, 4096, None) == -3   # ldw < r
+    assert cd(p, 10, 8, 8, p, 1, None, 10, p, p, p, p, p, 8, p, 1e-3, 10, 5, 0.05, p, 4096, None) == -1
+    assert cd(p, 10, 8, 8, p, 1, p, 10, p, p, p, p, p, 8, p, 1e-3, 10, 300, 0.05, p, 4096, None) == -2  # k > 255
+    assert cd(p, 10, 8, 8, p, 1, p, 10, p, p, p, p, p, 8, p, 1e-3, 10, 5, 1.0, p, 4096, None) == -2     # eta >= 1
+    assert cd(p, 10, 20000, 20000, p, 1, p, 10, p, p, p, p, p, 20000, p, 1e-3, 10, 5, 0.05, p, 4096, None) == -2
+    assert L.lpd_row_sqnorms(p, 0, 8, 8, p, None) == 0
+    assert L.lpd_row_sqnorms(p, 4, 8, 7, p, None) == -3
+    assert L.lpd_row_sqnorms(p, 4, 8, 8, None, None) == -1
+    assert L.lpd_fold_weights(p, 4, 8, 8, p, 0, 4, p, 8, None) == 0
+    assert L.lpd_fold_weights(p, 4, 8, 7, p, 2, 4, p, 8, None) == -3
+    assert L.lpd_fold_weights(p, 4, 8, 8, p, 2, 4, None, 8, None) == -1
+    pr = L.lpd_predict
+    assert pr(p, 4, 4, 4, p, 8, 4, 0.5, p, 0, 8, p, 1, None, 0, None) == 0           # no classifiers
+    assert pr(p, 4, 4, 4, p, 8, 4, 0.5, p, 9, 8, p, 9, None, 0, None) == -2          # c > B
+    assert pr(p, 4, 4, 4, p, 8, 4, 0.5, p, 2, 8, p, 1, p, 4096, None) == -3          # ldf < c
+    assert pr(p, 4, 4, 4, p, 8, 4, 0.5, p, 2, 8, p, 2, None, 0, None) == -4
+
+
 def test_binding_rejects_host_tensors():
     from paper_2207_01016_amd import lpd
     with pytest.raises(ValueError):

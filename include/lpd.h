@@ -181,6 +181,17 @@ int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg,
                      const float *w, float *m, void *hip_stream);
 
 /*
+ * Step 2a for several weight vectors that share G (the classifiers of a C grid, of the folds, of the
+ * class pairs; Section 3):  M[i, q] = sum_{j<r} G[i,j] * Ws[q,j],  q < k.
+ * Up to 8 vectors are served by one bandwidth-bound pass over G, more by the MFMA product G Ws^T.
+ *   G device in n x r (ldg);  Ws device in k x r (ldws), one vector per row;  M device out n x k (ldm)
+ * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE, LPD_ERR_LD, LPD_ERR_HIP.
+ */
+int lpd_margins_multi(const float *G, int64_t n, int64_t r, int64_t ldg,
+                      const float *Ws, int64_t k, int64_t ldws,
+                      float *M, int64_t ldm, void *hip_stream);
+
+/*
  * Prediction (Section 3, "Algorithm Overview": the prediction step; Section 2: f(x) = <w, phi(x)>,
  * no offset).  A classifier trained on the rows of G has weights ws (r values); a new point x has
  * features W z(x), z(x)_b = exp(-gamma ||x - l_b||^2), so its score is ws . (W z(x)) = v . z(x) with
@@ -191,7 +202,7 @@ int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg,
  * lpd_predict:       F[i, j] = sum_b V[j, b] * exp(-gamma ||x_i - l_b||^2)     (n x c),  c <= B
  *   X device in n x d (ldx);  L device in B x d (ldl);  V device in c x B (ldv);  F device out n x c (ldf)
  *   workspace: as for lpd_nystrom_factor (lpd_nystrom_factor_workspace(n, d, B)); the kernel block is
- *   produced panel by panel and consumed at once, by one sweep per classifier for c <= 4, by the MFMA
+ *   produced panel by panel and consumed at once, by one multi-vector sweep for c <= 8, by the MFMA
  *   product otherwise.
  * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE (incl. c > B), LPD_ERR_LD, LPD_ERR_WORKSPACE, LPD_ERR_HIP.
  */

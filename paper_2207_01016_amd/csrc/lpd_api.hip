@@ -167,6 +167,24 @@ hipError_t launch_margins(const float *G, int64_t n_out, int64_t r, int64_t ldg,
     return launch_margins_lpr<8, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
 }
 
+// Up to 8 weight vectors in one pass over the rows (margins_multi_kernel).
+hipError_t launch_margins_multi(const float *G, int64_t n, int64_t r, int64_t ldg, const float *Ws, int64_t k,
+                                int64_t ldws, float *M, int64_t ldm, hipStream_t s)
+{
+    const bool vec = aligned16(G) && aligned16(Ws) && ldg % 4 == 0 && ldws % 4 == 0;
+    const unsigned grid = row_grid(n, 4);
+#define LPD_MM(KK)                                                                                               \
+    case KK:                                                                                                     \
+        if (vec) hipLaunchKernelGGL((margins_multi_kernel<KK, true>), dim3(grid), dim3(256), 0, s, G, n, int(r), ldg, Ws, ldws, M, ldm); \
+        else hipLaunchKernelGGL((margins_multi_kernel<KK, false>), dim3(grid), dim3(256), 0, s, G, n, int(r), ldg, Ws, ldws, M, ldm);    \
+        break
+    switch (int(k)) {
+        LPD_MM(1); LPD_MM(2); LPD_MM(3); LPD_MM(4); LPD_MM(5); LPD_MM(6); LPD_MM(7); LPD_MM(8);
+    }
+#undef LPD_MM
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- factor schedule
 
 struct EventLog {
@@ -261,11 +279,10 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
         k2.C = G + p0 * ldg; k2.ldc = ldg;
         k2.M = int(rows); k2.N = int(r); k2.K = int(B); k2.n_store = int(out_cols);
         LPD_HIP(log.begin(2, s));
-        if (out_cols != B && r <= 4) {
-            // a handful of classifiers: one bandwidth-bound sweep of the panel per classifier instead of
-            // an MFMA tile that would be 97 % padding
-            for (int64_t j = 0; j < r; ++j)
-                LPD_HIP(launch_margins<false>(Z, rows, B, c.ldz, nullptr, W + j * ldw, G + p0 * ldg + j, s, ldg));
+        if (out_cols != B && r <= 8) {
+            // a handful of classifiers: one bandwidth-bound pass over the panel serves them all,
+            // instead of an MFMA tile that would be 94 % padding or more
+            LPD_HIP(launch_margins_multi(Z, rows, B, c.ldz, W, r, ldw, G + p0 * ldg, ldg, s));
         } else {
             LPD_HIP(launch_gemm(k2, EPI_STORE, s));
         }
@@ -398,6 +415,26 @@ int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg, const in
     if (ldg < r) return LPD_ERR_LD;
     hipError_t e = launch_margins<true>(G, n_rows, r, ldg, rows, w, m, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+}
+
+int lpd_margins_multi(const float *G, int64_t n, int64_t r, int64_t ldg, const float *Ws, int64_t k, int64_t ldws,
+                      float *M, int64_t ldm, void *hip_stream)
+{
+    if (n < 0 || r < 0 || k < 0 || n > kMaxDim || r > kMaxDim || k > kMaxDim) return LPD_ERR_SHAPE;
+    if (n == 0 || k == 0) return LPD_OK;
+    if (!M || (r > 0 && (!G || !Ws))) return LPD_ERR_NULL;
+    if (ldg < r || ldws < r || ldm < k) return LPD_ERR_LD;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (k > 8) {
+        // many weight vectors: the MFMA product M = G Ws^T
+        GemmArgs a{};
+        a.A = G; a.lda = ldg;
+        a.B = Ws; a.ldb = ldws;
+        a.C = M; a.ldc = ldm;
+        a.M = int(n); a.N = int(k); a.K = int(r); a.n_store = int(k);
+        return launch_gemm(a, EPI_STORE, s) == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+    }
+    return launch_margins_multi(G, n, r, ldg, Ws, k, ldws, M, ldm, s) == hipSuccess ? LPD_OK : LPD_ERR_HIP;
 }
 
 int lpd_fold_weights(const float *W, int64_t r, int64_t B, int64_t ldw, const float *Ws, int64_t c, int64_t ldws,

@@ -57,6 +57,7 @@ SIGNATURES = {
                                         _vp]),
     "lpd_margins": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp, _vp]),
     "lpd_margins_rows": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
+    "lpd_margins_multi": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, _vp, _i64, _vp]),
     "lpd_fold_weights": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, _vp, _i64, _vp]),
     "lpd_predict": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _i64, _vp, _i64,
                                    _vp, _sz, _vp]),
@@ -359,3 +360,22 @@ def lpd_predict(X, L, gamma: float, V, F=None, workspace=None) -> torch.Tensor:
                            F.data_ptr(), _ld(F), workspace.data_ptr(), workspace.numel(), _stream(X.device))
     _check(st, "lpd_predict")
     return F
+
+
+def lpd_margins_multi(G, Ws, M=None, r: int | None = None) -> torch.Tensor:
+    """Step 2a for k weight vectors at once: M = G[:, :r] Ws[:, :r]^T (n x k)."""
+    G = _dev_f32(G, "G", 2)
+    Ws = _dev_f32(Ws, "Ws", 2)
+    n = G.shape[0]
+    k = Ws.shape[0]
+    r = Ws.shape[1] if r is None else int(r)
+    if r > Ws.shape[1] or r > G.shape[1]:
+        raise ValueError("r exceeds Ws or the columns of G")
+    if M is None:
+        M = torch.empty((n, k), dtype=torch.float32, device=G.device)
+    M = _dev_f32(M, "M", 2)
+    if M.shape != (n, k):
+        raise ValueError("M must be n x k")
+    _check(lib().lpd_margins_multi(G.data_ptr(), n, r, _ld(G), Ws.data_ptr(), k, _ld(Ws), M.data_ptr(), _ld(M),
+                                   _stream(G.device)), "lpd_margins_multi")
+    return M

@@ -107,6 +107,9 @@ def test_solver_and_predict_argument_errors(L):
     assert L.lpd_fold_weights(p, 4, 8, 8, p, 0, 4, p, 8, None) == 0
     assert L.lpd_fold_weights(p, 4, 8, 7, p, 2, 4, p, 8, None) == -3
     assert L.lpd_fold_weights(p, 4, 8, 8, p, 2, 4, None, 8, None) == -1
+    assert L.lpd_margins_multi(p, 4, 8, 8, p, 0, 8, p, 1, None) == 0
+    assert L.lpd_margins_multi(p, 4, 8, 8, p, 3, 8, p, 2, None) == -3                # ldm < k
+    assert L.lpd_margins_multi(p, 4, 8, 8, None, 3, 8, p, 3, None) == -1
     pr = L.lpd_predict
     assert pr(p, 4, 4, 4, p, 8, 4, 0.5, p, 0, 8, p, 1, None, 0, None) == 0           # no classifiers
     assert pr(p, 4, 4, 4, p, 8, 4, 0.5, p, 9, 8, p, 9, None, 0, None) == -2          # c > B

@@ -279,3 +279,22 @@ def test_margins_on_factor_output_tiny(lpd, wls, oracle, dev):
     chained = oracle.margins_f64(oracle.nystrom_factor(X.cpu().numpy(), L.cpu().numpy(), wl.gamma, W.numpy()),
                                  w.cpu().numpy().astype(np.float64))
     print("chained rel error (oracle G -> oracle m vs GPU G -> GPU m):", relfro(m.cpu().numpy(), chained))
+
+
+@pytest.mark.parametrize("n,r,ld,k", [(700, 300, 300, 1), (1000, 1024, 1024, 3), (513, 1001, 1004, 8),
+                                       (301, 517, 517, 5), (2000, 640, 640, 9), (900, 260, 264, 150)])
+def test_margins_multi_match_oracle(lpd, oracle, dev, n, r, ld, k):
+    g = torch.Generator().manual_seed(n + r + k)
+    Gfull = torch.randn((n, ld), generator=g).to(dev)
+    Ws = (torch.randn((k, ld), generator=g) / r ** 0.5).to(dev)
+    M = torch.full((n, k), float("nan"), dtype=torch.float32, device=dev)
+    lpd.lpd_margins_multi(Gfull, Ws, M, r=r)
+    torch.cuda.synchronize()
+    Gh, Wh = Gfull.cpu().numpy(), Ws.cpu().numpy()
+    for q in range(k):
+        ref = oracle.margins(Gh, Wh[q], r=r)
+        assert relfro(M[:, q].cpu().numpy(), ref) <= TOL_M, q
+    if k <= 8:
+        # the single-vector sweep of the same row gives the same bits only up to summation order: compare loosely
+        m0 = lpd.lpd_margins(Gfull, Ws[0].contiguous(), r=r)
+        assert float((m0.double() - M[:, 0].double()).norm() / m0.double().norm()) <= 1e-6

@@ -45,10 +45,11 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", default="auto", choices=["auto", "128x128", "256x128", "256x256"])
     ap.add_argument("--workspace-mult", type=float, default=1.0)
-    ap.add_argument("--path", default="factor", choices=["factor", "solver", "predict"],
+    ap.add_argument("--path", default="factor", choices=["factor", "solver", "predict", "stream"],
                     help="factor: Nystrom factor + margin sweep (default); solver: batched dual coordinate ascent "
-                         "on G; predict: scores of new points")
+                         "on G; predict: scores of new points; stream: the factor copied to pinned host memory as it is made")
     ap.add_argument("--classifiers", type=int, default=10, help="predict: number of classifiers scored at once")
+    ap.add_argument("--chunk-rows", type=int, default=0, help="stream: rows per chunk (0 = the library's suggestion)")
     ap.add_argument("--random-w", action="store_true",
                     help="skip the host eigendecomposition and use a random W (tuning only; marks the line invalid)")
     return ap.parse_args()
@@ -265,6 +266,56 @@ def bench_predict(args):
     print(json.dumps(out))
 
 
+def bench_stream(args):
+    """Step 1d streamed to pinned host memory: device compute overlapped with the copy of G over PCIe."""
+    import torch
+    from paper_2207_01016_amd import lpd, workloads
+    dev = torch.device("cuda:0")
+    wl = workloads.WORKLOADS[args.workload]
+    X = workloads.make_X(wl, dev)
+    idx = workloads.landmark_indices(wl)
+    L = X[idx.to(dev)].contiguous()
+    t0 = time.perf_counter()
+    if args.random_w:
+        W_host = torch.randn((wl.B, wl.B), generator=torch.Generator().manual_seed(1)) / wl.B ** 0.5
+        rank = wl.B
+    else:
+        W_host, eig, rank = lpd.lpd_whiten_host(L.cpu(), wl.gamma)
+    t_whiten = time.perf_counter() - t0
+    W = W_host.to(dev)
+    chunk_rows, nbytes = lpd.lpd_nystrom_factor_to_host_workspace(wl.n, wl.d, wl.B, args.chunk_rows)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    t0 = time.perf_counter()
+    G_host = torch.empty((wl.n, wl.B), dtype=torch.float32, pin_memory=True)
+    t_pin = time.perf_counter() - t0
+    for _ in range(args.warmup):
+        lpd.lpd_nystrom_factor_to_host(X, L, wl.gamma, W, G_host, chunk_rows, ws, r=rank)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        lpd.lpd_nystrom_factor_to_host(X, L, wl.gamma, W, G_host, chunk_rows, ws, r=rank)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = elapsed * 1e3 / args.steps
+    flop = 2.0 * wl.n * wl.B * (wl.d + rank)
+    tflops = flop / (ms * 1e-3) / 1e12
+    out = {
+        "metric": "stage1_factor_rows_per_s_to_host", "value": wl.n * args.steps / elapsed, "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic" + (" (random W: tuning run)" if args.random_w else ""),
+        "config": {"workload": wl.name, "n": wl.n, "d": wl.d, "B": wl.B, "rank": rank, "gamma": wl.gamma,
+                   "chunk_rows": chunk_rows, "workspace_bytes": nbytes, "G_host": "pinned, n x B float32"},
+        "whiten_host_s": None if args.random_w else t_whiten, "pin_alloc_s": t_pin,
+        "pcie_GBps": wl.n * wl.B * 4 / (ms * 1e-3) / 1e9,
+        "roofline": {"kernel": "lpd_nystrom_factor_to_host: both GEMMs per chunk, copy of G overlapped",
+                     "bound": "mfma", "achieved": tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / FP32_MFMA_PEAK_TFLOPS, "flop_per_launch": flop, "avg_launch_ms": ms,
+                     "traffic": None},
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -284,6 +335,9 @@ def main():
         return
     if args.path == "predict":
         bench_predict(args)
+        return
+    if args.path == "stream":
+        bench_stream(args)
         return
     dev = torch.device("cuda:0")
     wl = workloads.WORKLOADS[args.workload]

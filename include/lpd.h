@@ -148,6 +148,38 @@ int lpd_nystrom_factor_profiled(const float *X, int64_t n, int64_t d, int64_t ld
                                 lpd_factor_profile *profile);
 
 /*
+ * Streaming form of step 1d for a factor that fits host memory but not device
+ * memory (Section 3, "Algorithm Overview": every stage must be able to work in
+ * chunks).  X, L and W stay on the device; G is produced chunk_rows rows at a
+ * time into one of two device chunk buffers and copied to G_host on a second
+ * stream of default priority while the next chunk is computed, so the copy
+ * over PCIe hides behind the MFMA work whenever it is the shorter of the two.
+ * Rows of G_host equal what lpd_nystrom_factor writes for the same row of X.
+ *
+ *   X, L, W     device in, as for lpd_nystrom_factor
+ *   G_host      HOST out, n x B, ldg.  Page-locked memory (hipHostMalloc, a
+ *               pinned torch tensor) is needed for the copies to overlap;
+ *               pageable memory still gives the right result, serially.
+ *   chunk_rows  rows per chunk, > 0 (the workspace query suggests a value)
+ *   workspace   device, 256-byte aligned, at least the size the query returns
+ *               for this chunk_rows: two chunk buffers and the factor scratch.
+ * The call BLOCKS until G_host is complete.  It creates and destroys one stream
+ * and four events; it allocates no device memory.
+ * The query takes *chunk_rows in and out: a value <= 0 is replaced by the
+ * suggested one (one kernel-block panel, at most n: short chunks keep the last,
+ * exposed copy short); *bytes is the workspace size for the value it returns.
+ * Errors: as lpd_nystrom_factor.
+ */
+int lpd_nystrom_factor_to_host_workspace(int64_t n, int64_t d, int64_t B,
+                                         int64_t *chunk_rows, size_t *bytes);
+int lpd_nystrom_factor_to_host(const float *X, int64_t n, int64_t d, int64_t ldx,
+                               const float *L, int64_t B, int64_t ldl,
+                               float gamma,
+                               const float *W, int64_t r, int64_t ldw,
+                               float *G_host, int64_t ldg, int64_t chunk_rows,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * The kernel block alone (Figure 1 steps 1a / 1d, Section 4 kernel):
  * Z[i,b] = exp(-gamma ||x_i - l_b||^2), written in full to device memory.
  * With X = L this is the landmark kernel matrix K_LL of step 1a.

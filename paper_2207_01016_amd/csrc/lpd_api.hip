@@ -57,6 +57,17 @@ Carve carve(int64_t n, int64_t B)
     return c;
 }
 
+// Workspace of the streaming factor: two device chunk buffers (chunk_rows x B, dense) followed by the
+// factor scratch of one chunk.
+struct StreamCarve { size_t buf_bytes, bytes; };
+StreamCarve stream_carve(int64_t chunk_rows, int64_t B)
+{
+    StreamCarve sc;
+    sc.buf_bytes = round_up(size_t(chunk_rows) * size_t(B) * 4, kAlign);
+    sc.bytes = 2 * sc.buf_bytes + carve(chunk_rows, B).rec_bytes;
+    return sc;
+}
+
 // ---------------------------------------------------------------- GEMM launch
 
 enum TileId { TILE_AUTO = 0, TILE_128x128 = 1, TILE_256x128 = 2, TILE_256x256 = 3 };
@@ -364,6 +375,72 @@ int lpd_nystrom_factor_profiled(const float *X, int64_t n, int64_t d, int64_t ld
     if (!profile) return LPD_ERR_NULL;
     return factor_impl(X, n, d, ldx, L, B, ldl, gamma, W, r, ldw, G, ldg, B, workspace, workspace_bytes,
                        static_cast<hipStream_t>(hip_stream), profile);
+}
+
+int lpd_nystrom_factor_to_host_workspace(int64_t n, int64_t d, int64_t B, int64_t *chunk_rows, size_t *bytes)
+{
+    if (!chunk_rows || !bytes) return LPD_ERR_NULL;
+    if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
+    if (*chunk_rows <= 0) *chunk_rows = std::max<int64_t>(1, std::min<int64_t>(n, carve(n, B).rec_rows));
+    if (*chunk_rows > kMaxDim) return LPD_ERR_SHAPE;
+    const StreamCarve sc = stream_carve(*chunk_rows, B);
+    *bytes = sc.bytes;
+    return LPD_OK;
+}
+
+int lpd_nystrom_factor_to_host(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B,
+                               int64_t ldl, float gamma, const float *W, int64_t r, int64_t ldw, float *G_host,
+                               int64_t ldg, int64_t chunk_rows, void *workspace, size_t workspace_bytes,
+                               void *hip_stream)
+{
+    int status = check_factor_args(X, n, d, ldx, L, B, ldl, W, r, ldw, G_host, ldg);
+    if (status != LPD_OK) return status;
+    if (chunk_rows <= 0 || chunk_rows > kMaxDim) return LPD_ERR_SHAPE;
+    if (n == 0 || B == 0) return LPD_OK;
+    chunk_rows = std::min(chunk_rows, n);
+    const StreamCarve sc = stream_carve(chunk_rows, B);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < sc.bytes)
+        return LPD_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace);
+    float *buf[2] = {reinterpret_cast<float *>(ws), reinterpret_cast<float *>(ws + sc.buf_bytes)};
+    void *fws = ws + 2 * sc.buf_bytes;
+    const size_t fws_bytes = workspace_bytes - 2 * sc.buf_bytes;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipStream_t cs = nullptr;
+    hipEvent_t computed[2] = {nullptr, nullptr}, copied[2] = {nullptr, nullptr};
+    LPD_HIP(hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
+    for (int b = 0; b < 2; ++b) {
+        LPD_HIP(hipEventCreateWithFlags(&computed[b], hipEventDisableTiming));
+        LPD_HIP(hipEventCreateWithFlags(&copied[b], hipEventDisableTiming));
+    }
+    {
+        int64_t chunk = 0;
+        for (int64_t c0 = 0; c0 < n; c0 += chunk_rows, ++chunk) {
+            const int64_t rows = std::min(chunk_rows, n - c0);
+            const int b = int(chunk & 1);
+            // the buffer is free again once the copy of the chunk before last has drained
+            if (chunk >= 2) LPD_HIP(hipStreamWaitEvent(s, copied[b], 0));
+            status = factor_impl(X + c0 * ldx, rows, d, ldx, L, B, ldl, gamma, W, r, ldw, buf[b], B, B, fws,
+                                 fws_bytes, s, nullptr);
+            if (status != LPD_OK) break;
+            LPD_HIP(hipEventRecord(computed[b], s));
+            LPD_HIP(hipStreamWaitEvent(cs, computed[b], 0));
+            LPD_HIP(hipMemcpy2DAsync(G_host + c0 * ldg, size_t(ldg) * 4, buf[b], size_t(B) * 4, size_t(B) * 4,
+                                     size_t(rows), hipMemcpyDeviceToHost, cs));
+            LPD_HIP(hipEventRecord(copied[b], cs));
+        }
+    }
+done:
+    // drain both streams before the events and the buffers they guard go away, on errors too
+    if (cs && hipStreamSynchronize(cs) != hipSuccess && status == LPD_OK) status = LPD_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess && status == LPD_OK) status = LPD_ERR_HIP;
+    for (int b = 0; b < 2; ++b) {
+        if (computed[b]) (void)hipEventDestroy(computed[b]);
+        if (copied[b]) (void)hipEventDestroy(copied[b]);
+    }
+    if (cs) (void)hipStreamDestroy(cs);
+    return status;
 }
 
 int lpd_kernel_block(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,

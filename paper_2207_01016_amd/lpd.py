@@ -53,6 +53,10 @@ SIGNATURES = {
     "lpd_nystrom_factor_workspace": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
     "lpd_nystrom_factor": (ctypes.c_int, _FACTOR_ARGS),
     "lpd_nystrom_factor_profiled": (ctypes.c_int, _FACTOR_ARGS + [ctypes.POINTER(FactorProfile)]),
+    "lpd_nystrom_factor_to_host_workspace": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_i64),
+                                                            ctypes.POINTER(_sz)]),
+    "lpd_nystrom_factor_to_host": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64,
+                                                  _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
     "lpd_kernel_block": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _vp, _sz,
                                         _vp]),
     "lpd_margins": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp, _vp]),
@@ -187,6 +191,45 @@ def lpd_nystrom_factor_profiled(X, L, gamma: float, W, G, workspace, r: int | No
     prof = FactorProfile()
     _check(lib().lpd_nystrom_factor_profiled(*args, ctypes.byref(prof)), "lpd_nystrom_factor_profiled")
     return prof
+
+
+def lpd_nystrom_factor_to_host_workspace(n: int, d: int, B: int, chunk_rows: int = 0):
+    """(chunk_rows, bytes): the chunk size in use (the suggested one for chunk_rows <= 0) and its scratch size."""
+    cr, nb = _i64(int(chunk_rows)), _sz(0)
+    _check(lib().lpd_nystrom_factor_to_host_workspace(n, d, B, ctypes.byref(cr), ctypes.byref(nb)),
+           "lpd_nystrom_factor_to_host_workspace")
+    return int(cr.value), int(nb.value)
+
+
+def lpd_nystrom_factor_to_host(X, L, gamma: float, W, G_host=None, chunk_rows: int = 0, workspace=None,
+                               r: int | None = None) -> torch.Tensor:
+    """Step 1d streamed to host memory: G_host (pinned float32 CPU tensor, n x B) is filled chunk by chunk
+    while the device computes the next chunk. Blocks until G_host is complete."""
+    X = _dev_f32(X, "X", 2)
+    L = _dev_f32(L, "L", 2)
+    W = _dev_f32(W, "W", 2)
+    n, d = X.shape
+    B = L.shape[0]
+    if L.shape[1] != d or W.shape[1] != B:
+        raise ValueError("shape mismatch: X n x d, L B x d, W r x B")
+    r = W.shape[0] if r is None else int(r)
+    if r > W.shape[0]:
+        raise ValueError("r exceeds the rows of W")
+    if G_host is None:
+        G_host = torch.empty((n, B), dtype=torch.float32, pin_memory=True)
+    if G_host.is_cuda or G_host.dtype != torch.float32 or G_host.dim() != 2 or G_host.shape != (n, B) \
+            or (G_host.numel() and G_host.stride(1) != 1):
+        raise TypeError("G_host: expected a float32 CPU tensor n x B with unit column stride")
+    chunk_rows, nbytes = lpd_nystrom_factor_to_host_workspace(n, d, B, chunk_rows)
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=X.device)
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda:
+        raise TypeError("workspace: expected a uint8 device tensor")
+    _check(lib().lpd_nystrom_factor_to_host(X.data_ptr(), n, d, _ld(X), L.data_ptr(), B, _ld(L), float(gamma),
+                                            W.data_ptr(), r, _ld(W), G_host.data_ptr(), _ld(G_host), chunk_rows,
+                                            workspace.data_ptr(), workspace.numel(), _stream(X.device)),
+           "lpd_nystrom_factor_to_host")
+    return G_host
 
 
 def lpd_kernel_block(X, L, gamma: float, Z, workspace) -> torch.Tensor:

@@ -68,6 +68,33 @@ def test_factor_argument_errors(L):
     assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, p, 16, None) == -4           # too small
 
 
+def test_streaming_factor_query_and_argument_errors(L):
+    cr, nb = ctypes.c_int64(0), ctypes.c_size_t(0)
+    q = L.lpd_nystrom_factor_to_host_workspace
+    assert q(1_000_000, 784, 4096, ctypes.byref(cr), ctypes.byref(nb)) == 0
+    assert 0 < cr.value <= 1_000_000 and nb.value % 256 == 0
+    assert nb.value >= 2 * cr.value * 4096 * 4                       # two chunk buffers plus scratch
+    cr2, nb2 = ctypes.c_int64(1000), ctypes.c_size_t(0)
+    assert q(1_000_000, 784, 4096, ctypes.byref(cr2), ctypes.byref(nb2)) == 0
+    assert cr2.value == 1000 and nb2.value < nb.value                # a given chunk size is kept
+    cr3 = ctypes.c_int64(0)
+    assert q(10, 4, 8, ctypes.byref(cr3), ctypes.byref(nb2)) == 0 and cr3.value == 10   # never above n
+    assert q(10, 4, 8, None, ctypes.byref(nb2)) == -1
+    assert q(-1, 4, 8, ctypes.byref(cr3), ctypes.byref(nb2)) == -2
+
+    buf = (ctypes.c_float * 4096)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    f = L.lpd_nystrom_factor_to_host
+    #        X  n  d  ldx L  B  ldl gamma W  r  ldw G  ldg chunk ws bytes stream
+    assert f(p, 0, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, None, 0, None) == 0       # n = 0: nothing to do
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, 0, None, 0, None) == -2      # chunk_rows must be > 0
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 9, 8, p, 8, 4, None, 0, None) == -2      # r > B
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, 8, None, 8, 4, None, 0, None) == -1
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 7, 4, None, 0, None) == -3      # ldg < B
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, None, 0, None) == -4      # no workspace
+    assert f(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, p, 256, None) == -4       # too small
+
+
 def test_margins_and_kernel_block_argument_errors(L):
     buf = (ctypes.c_float * 1024)()
     p = ctypes.cast(buf, ctypes.c_void_p)

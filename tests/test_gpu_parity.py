@@ -210,6 +210,30 @@ def test_factor_profiled_matches_plain(lpd, wls, dev):
     assert prof.ms_whiten > 0 and prof.ms_kernel_block > 0
 
 
+@pytest.mark.parametrize("chunk_rows,pinned,pad", [
+    (3000, True, 0),       # 7 chunks, ragged last one, both buffers reused several times
+    (512, True, 4),        # many small chunks into a padded host matrix
+    (0, True, 0),          # the suggested chunk size (one chunk here)
+    (7000, False, 0),      # pageable host memory: same result, copies just do not overlap
+])
+def test_streaming_factor_matches_device_factor_and_oracle(lpd, wls, oracle, dev, chunk_rows, pinned, pad):
+    wl = wls.WORKLOADS["small"].with_shape(n=20000, B=512)
+    X, idx, L, W, eig, rank = _prepare(lpd, wls, wl, dev)
+    G_dev = _factor(lpd, X, L, wl.gamma, W, rank).cpu()
+    host = torch.full((wl.n, wl.B + pad), float("nan"), dtype=torch.float32, pin_memory=pinned)
+    G_host = lpd.lpd_nystrom_factor_to_host(X, L, wl.gamma, W.to(dev), host[:, :wl.B], chunk_rows=chunk_rows, r=rank)
+    assert G_host.data_ptr() == host.data_ptr()
+    # a row of G depends on its own row of X only, and the arithmetic per row is the same in
+    # both schedules, so the streamed factor equals the resident one
+    assert relfro(G_host.numpy(), G_dev.numpy()) <= 1e-6
+    if pad:
+        assert torch.isnan(host[:, wl.B:]).all()                     # padding columns untouched
+    rows = wls.sample_rows(wl, 300, include=idx[:32])
+    ref = oracle.nystrom_factor(X[rows.to(dev)].cpu().numpy(), L.cpu().numpy(), wl.gamma, W.numpy(), r=rank)
+    assert relfro(G_host[rows].numpy()[:, :rank], ref) <= TOL_G
+    assert not G_host[:, rank:].any()
+
+
 def test_factor_zero_sizes(lpd, dev):
     ws = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
     X = torch.zeros((0, 8), device=dev)

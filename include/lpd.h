@@ -100,6 +100,33 @@ int lpd_whiten_host(const float *L_host, int64_t B, int64_t d, int64_t ldl,
                     float *W_host, int64_t ldw, double *eig_host, int64_t *rank);
 
 /*
+ * Figure 1 steps 1a-1c with the O(B^3) work on the device: the same result as
+ * lpd_whiten_host (same definition, same ordering, clipping and sign rule),
+ * computed in double precision by HIP kernels: kernel matrix of the landmarks,
+ * Householder reduction to tridiagonal form, accumulation of the reflectors,
+ * application of the QL plane rotations, scaling to W.  Only the scalar QL
+ * iteration on the tridiagonal matrix (O(B^2)) runs on the host, overlapped
+ * with the device.  Eigenvectors of a repeated eigenvalue may differ from the
+ * host routine's by a rotation within their eigenspace.
+ *
+ *   L          device in   B x d floats, ldl
+ *   W          device out  B x B floats, ldw; rows >= *rank are zero
+ *   eig_host   host out    B doubles, descending; may be NULL
+ *   rank       host out
+ *   workspace  device, 256-byte aligned, at least lpd_whiten_workspace(B) bytes
+ *              (two B x B double matrices and some vectors)
+ * The call BLOCKS until W is complete.  It allocates page-locked host staging
+ * (a few MB) and events for its duration, no device memory.  B <= 46340.
+ * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE, LPD_ERR_LD, LPD_ERR_WORKSPACE,
+ * LPD_ERR_HIP, LPD_ERR_NUMERIC (QL did not converge, or no positive eigenvalue).
+ */
+int lpd_whiten_workspace(int64_t B, size_t *bytes);
+int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl,
+               double gamma, double clip_ratio,
+               float *W, int64_t ldw, double *eig_host, int64_t *rank,
+               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Device scratch for lpd_nystrom_factor / lpd_kernel_block: squared row norms
  * of X and L plus one row panel of the kernel block Z.  `*bytes` receives the
  * recommended size for this shape; any 256-byte aligned buffer of at least

@@ -1,0 +1,641 @@
+// Stage-1 preparation on the device (Figure 1 steps 1a-1c, Section 3): landmark kernel matrix,
+// symmetric eigendecomposition and the whitening factor W = Lambda^{-1/2} U^T, in double precision,
+// for gfx950.  All O(B^3) work runs in the kernels below; the host keeps only the serial scalar part,
+// the implicit-shift QL iteration on the tridiagonal matrix (O(B^2)), and overlaps it with the device.
+//
+//   1a  kll_kernel        K[a,b] = exp(-gamma ||l_a - l_b||^2) from direct differences
+//   1b  hh_kernel / trail_kernel / w_kernel, once per column: Householder reduction to tridiagonal
+//       form.  The rank-2 update of the trailing matrix by reflector j-1 and the matrix-vector
+//       product with reflector j share ONE pass over the trailing matrix (read, update, write, dot),
+//       so a step moves 16 bytes per trailing element and the reduction is bound by HBM bandwidth.
+//       panel_gram_kernel / panel_t_kernel / panel_apply_kernel: Q^T accumulated row-wise from the
+//       reflectors, 32 at a time in compact form I - V T^T V^T.
+//       rot_kernel: the QL plane rotations, 16 sweeps per pass.  A thread owns one column of the
+//       eigenvector matrix and runs the sweeps as a register pipeline: rows enter in descending
+//       order, stage s holds one row, rotates it against the next and hands it on two steps later,
+//       so the 16 rotations of a step are independent and a pass reads and writes each row once.
+//   1c  finish_kernel     W[j,:] = sign_j * u_j / sqrt(lambda_j) in eigenvalue order, rows >= r zero.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "../../include/lpd.h"
+#include "whiten_internal.h"
+
+namespace {
+
+constexpr int NB = 32;        // reflectors per compact panel
+constexpr int KSW = 16;       // QL sweeps per rotation pass
+constexpr size_t kAlign = 256;
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Sum over a workgroup of up to 1024 threads; every thread gets the result. `red` holds 16 doubles.
+__device__ __forceinline__ double block_sum(double v, double *red)
+{
+    v = wave_sum(v);
+    const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[wave] = v;
+    __syncthreads();
+    double t = 0.0;
+    for (int k = 0; k < nw; ++k) t += red[k];
+    return t;
+}
+
+// ---------------------------------------------------------------- step 1a
+
+__global__ __launch_bounds__(256) void kll_kernel(const float *__restrict__ L, int n, int d, int64_t ldl, double gamma,
+                                                  double *__restrict__ A)
+{
+    __shared__ float la[16][33], lb[16][33];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int a0 = blockIdx.y * 16, b0 = blockIdx.x * 16;
+    double s = 0.0;
+    for (int k0 = 0; k0 < d; k0 += 32) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < 16 * 32; e += 256) {
+            const int r = e >> 5, k = e & 31;
+            la[r][k] = (a0 + r < n && k0 + k < d) ? L[int64_t(a0 + r) * ldl + k0 + k] : 0.f;
+            lb[r][k] = (b0 + r < n && k0 + k < d) ? L[int64_t(b0 + r) * ldl + k0 + k] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int k = 0; k < 32; ++k) {
+            const double df = double(la[ty][k]) - double(lb[tx][k]);
+            s += df * df;
+        }
+    }
+    const int a = a0 + ty, b = b0 + tx;
+    if (a < n && b < n) A[int64_t(a) * n + b] = a == b ? 1.0 : exp(-gamma * s);
+}
+
+// ---------------------------------------------------------------- step 1b, tridiagonalisation
+
+// Step j, part 1 (one workgroup).  Row j of the trailing matrix, brought up to date with the pending
+// reflector pair (vp, wp), gives the diagonal entry dg[j] and the Householder vector v_j over columns
+// j+1.. (v_j[j+1] = 1), which is written to vc and, for the later accumulation of Q, over row j of A.
+__global__ __launch_bounds__(1024) void hh_kernel(double *__restrict__ A, int n, int j, int pending,
+                                                  const double *__restrict__ vp, const double *__restrict__ wp,
+                                                  double *__restrict__ vc, double *__restrict__ dg,
+                                                  double *__restrict__ e, double *__restrict__ tau)
+{
+    __shared__ double red[16];
+    double *row = A + int64_t(j) * n;
+    const double vpj = pending ? vp[j] : 0.0, wpj = pending ? wp[j] : 0.0;
+    double ss = 0.0;
+    for (int c = j + threadIdx.x; c < n; c += blockDim.x) {
+        double x = row[c];
+        if (pending) x -= vpj * wp[c] + wpj * vp[c];
+        vc[c] = x;
+        if (c >= j + 2) ss += x * x;
+    }
+    ss = block_sum(ss, red);        // also orders the writes of vc before the reads below
+    const double diag = vc[j], alpha = vc[j + 1];
+    double beta = alpha, t = 0.0, scale = 0.0;
+    if (ss > 0.0) {
+        beta = -copysign(sqrt(alpha * alpha + ss), alpha);
+        t = (beta - alpha) / beta;
+        scale = 1.0 / (alpha - beta);
+    }
+    __syncthreads();
+    for (int c = j + 1 + threadIdx.x; c < n; c += blockDim.x) {
+        const double v = c == j + 1 ? 1.0 : vc[c] * scale;
+        vc[c] = v;
+        row[c] = v;
+    }
+    if (threadIdx.x == 0) {
+        dg[j] = diag;
+        e[j] = beta;
+        tau[j] = t;
+    }
+}
+
+// Step j, part 2: one pass over the trailing matrix A[j+1.., j+1..].  Each row is first updated with the
+// pending pair, A -= vp wp^T + wp vp^T, written back, and its inner product with v_j is left in y.
+// One wavefront per row at a time, rows dealt out grid-stride.
+__global__ __launch_bounds__(256) void trail_kernel(double *__restrict__ A, int n, int j, int pending,
+                                                    const double *__restrict__ vp, const double *__restrict__ wp,
+                                                    const double *__restrict__ vc, double *__restrict__ y)
+{
+    const int lane = threadIdx.x & 63;
+    const int c0 = j + 1;
+    for (int a = c0 + blockIdx.x * 4 + (threadIdx.x >> 6); a < n; a += gridDim.x * 4) {
+        double *row = A + int64_t(a) * n;
+        double acc0 = 0.0, acc1 = 0.0;
+        if (pending) {
+            const double va = vp[a], wa = wp[a];
+            int c = c0 + lane;
+            for (; c + 64 < n; c += 128) {
+                double x0 = row[c], x1 = row[c + 64];
+                x0 -= va * wp[c] + wa * vp[c];
+                x1 -= va * wp[c + 64] + wa * vp[c + 64];
+                row[c] = x0;
+                row[c + 64] = x1;
+                acc0 += x0 * vc[c];
+                acc1 += x1 * vc[c + 64];
+            }
+            if (c < n) {
+                double x0 = row[c];
+                x0 -= va * wp[c] + wa * vp[c];
+                row[c] = x0;
+                acc0 += x0 * vc[c];
+            }
+        } else {
+            for (int c = c0 + lane; c < n; c += 64) acc0 += row[c] * vc[c];
+        }
+        const double tot = wave_sum(acc0 + acc1);
+        if (lane == 0) y[a] = tot;
+    }
+}
+
+// Step j, part 3 (one workgroup): w_j = tau_j y - (tau_j^2 / 2)(y . v_j) v_j over columns j+1..
+__global__ __launch_bounds__(1024) void w_kernel(int n, int j, const double *__restrict__ tau,
+                                                 const double *__restrict__ vc, const double *__restrict__ y,
+                                                 double *__restrict__ wc)
+{
+    __shared__ double red[16];
+    const double t = tau[j];
+    double dot = 0.0;
+    for (int c = j + 1 + threadIdx.x; c < n; c += blockDim.x) dot += y[c] * vc[c];
+    dot = block_sum(dot, red);
+    const double alpha = 0.5 * t * t * dot;
+    for (int c = j + 1 + threadIdx.x; c < n; c += blockDim.x) wc[c] = t * y[c] - alpha * vc[c];
+}
+
+// The last pending pair applied to the 2x2 corner; n >= 2.
+__global__ void tri_tail_kernel(const double *__restrict__ A, int n, int pending, const double *__restrict__ vp,
+                                const double *__restrict__ wp, double *__restrict__ dg, double *__restrict__ e)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int a = n - 2, b = n - 1;
+    double daa = A[int64_t(a) * n + a], dab = A[int64_t(a) * n + b], dbb = A[int64_t(b) * n + b];
+    if (pending) {
+        daa -= 2.0 * vp[a] * wp[a];
+        dab -= vp[a] * wp[b] + wp[a] * vp[b];
+        dbb -= 2.0 * vp[b] * wp[b];
+    }
+    dg[a] = daa;
+    e[a] = dab;
+    dg[b] = dbb;
+    e[b] = 0.0;
+}
+
+// ---------------------------------------------------------------- step 1b, accumulation of Q^T
+
+__global__ __launch_bounds__(256) void identity_kernel(double *__restrict__ Zt, int n)
+{
+    const int64_t total = int64_t(n) * n;
+    for (int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x; idx < total; idx += int64_t(gridDim.x) * 256)
+        Zt[idx] = (idx / n == idx % n) ? 1.0 : 0.0;
+}
+
+// Reflector t of the panel at k0 is row k0+t of A over columns k0+t+1..; anything left of that is zero.
+__device__ __forceinline__ double panel_v(const double *__restrict__ A, int n, int k0, int nb, int t, int c)
+{
+    return (t < nb && c < n && c >= k0 + t + 1) ? A[int64_t(k0 + t) * n + c] : 0.0;
+}
+
+// Partial Gram matrices of the panel's reflectors, one per chunk of 128 columns: P[chunk][t][i].
+__global__ __launch_bounds__(256) void panel_gram_kernel(const double *__restrict__ A, int n, int k0, int nb,
+                                                         double *__restrict__ P)
+{
+    __shared__ double vs[NB][129];
+    const int cbase = k0 + 1 + blockIdx.x * 128;
+    for (int e = threadIdx.x; e < NB * 128; e += 256) {
+        const int t = e >> 7, c = e & 127;
+        vs[t][c] = panel_v(A, n, k0, nb, t, cbase + c);
+    }
+    __syncthreads();
+    const int t = threadIdx.x >> 3, i0 = (threadIdx.x & 7) * 4;
+    double g[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int c = 0; c < 128; ++c) {
+        const double vt = vs[t][c];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) g[q] += vt * vs[i0 + q][c];
+    }
+    double *out = P + int64_t(blockIdx.x) * NB * NB + t * NB + i0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) out[q] = g[q];
+}
+
+// T of the compact form H_k0 ... H_{k0+nb-1} = I - V T V^T (upper triangular), from the summed Gram matrix.
+__global__ __launch_bounds__(64) void panel_t_kernel(const double *__restrict__ P, int nchunks, int k0, int nb,
+                                                     const double *__restrict__ tau, double *__restrict__ T)
+{
+    __shared__ double gm[NB][NB + 1], ts[NB][NB + 1];
+    for (int e = threadIdx.x; e < NB * NB; e += 64) {
+        double s = 0.0;
+        for (int ch = 0; ch < nchunks; ++ch) s += P[int64_t(ch) * NB * NB + e];
+        gm[e / NB][e % NB] = s;
+        ts[e / NB][e % NB] = 0.0;
+    }
+    __syncthreads();
+    for (int i = 0; i < nb; ++i) {
+        const double ti = tau[k0 + i];
+        const int a = threadIdx.x;
+        if (a < i) {
+            double s = 0.0;
+            for (int t = a; t < i; ++t) s += ts[a][t] * gm[t][i];
+            ts[a][i] = -ti * s;
+        } else if (a == i) {
+            ts[i][i] = ti;
+        }
+        __syncthreads();
+    }
+    for (int e = threadIdx.x; e < NB * NB; e += 64) T[e] = ts[e / NB][e % NB];
+}
+
+// Rows r0.. of Zt times the panel: row <- row (I - V T^T V^T), 16 rows per workgroup.
+__global__ __launch_bounds__(256) void panel_apply_kernel(double *__restrict__ Zt, int n, const double *__restrict__ A,
+                                                          int k0, int nb, const double *__restrict__ T, int r0)
+{
+    constexpr int RB = 16, CC = 64;
+    __shared__ double zs[RB][CC + 1], vs[NB][CC + 1], ys[RB][NB + 1], y2[RB][NB + 1], ts[NB][NB + 1];
+    const int rbase = r0 + blockIdx.x * RB;
+    const int cfirst = k0 + 1;
+    for (int e = threadIdx.x; e < NB * NB; e += 256) ts[e / NB][e % NB] = T[e];
+
+    // Y[rr][t] = sum_c Zt[rbase+rr][c] v_t[c]; thread (rr, tq) owns t = tq and tq + 16
+    const int rr = threadIdx.x >> 4, tq = threadIdx.x & 15;
+    double ya = 0.0, yb = 0.0;
+    for (int cb = cfirst; cb < n; cb += CC) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < RB * CC; e += 256) {
+            const int r = e / CC, c = e % CC;
+            zs[r][c] = (rbase + r < n && cb + c < n) ? Zt[int64_t(rbase + r) * n + cb + c] : 0.0;
+        }
+        for (int e = threadIdx.x; e < NB * CC; e += 256) {
+            const int t = e / CC, c = e % CC;
+            vs[t][c] = panel_v(A, n, k0, nb, t, cb + c);
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int c = 0; c < CC; ++c) {
+            const double z = zs[rr][c];
+            ya += z * vs[tq][c];
+            yb += z * vs[tq + 16][c];
+        }
+    }
+    ys[rr][tq] = ya;
+    ys[rr][tq + 16] = yb;
+    __syncthreads();
+    // Y2[rr][t] = sum_{u >= t} Y[rr][u] T[t][u]
+    for (int e = threadIdx.x; e < RB * NB; e += 256) {
+        const int r = e / NB, t = e % NB;
+        double s = 0.0;
+        for (int u = t; u < NB; ++u) s += ys[r][u] * ts[t][u];
+        y2[r][t] = s;
+    }
+    // Zt[r][c] -= sum_t Y2[r][t] v_t[c]
+    for (int cb = cfirst; cb < n; cb += CC) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < NB * CC; e += 256) {
+            const int t = e / CC, c = e % CC;
+            vs[t][c] = panel_v(A, n, k0, nb, t, cb + c);
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < RB * CC; e += 256) {
+            const int r = e / CC, c = e % CC;
+            if (rbase + r < n && cb + c < n) {
+                double s = 0.0;
+#pragma unroll 8
+                for (int t = 0; t < NB; ++t) s += y2[r][t] * vs[t][c];
+                Zt[int64_t(rbase + r) * n + cb + c] -= s;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- step 1b, QL rotations
+
+struct RotBatch {
+    int imin, imax;            // lowest and highest rotation index of the batch
+    int lo[KSW], hi[KSW];      // sweep s rotates i = hi[s] down to lo[s]; lo > hi: idle stage
+    long long off[KSW];        // its (c, s) pairs start at cs[off[s]], highest index first
+};
+
+__global__ __launch_bounds__(64) void rot_kernel(double *__restrict__ Zt, int n, RotBatch rb,
+                                                 const double *__restrict__ cs)
+{
+    const int q = blockIdx.x * 64 + threadIdx.x;
+    const bool live = q < n;
+    const int qq = live ? q : n - 1;
+    double up[KSW], pipe[KSW];
+#pragma unroll
+    for (int s = 0; s < KSW; ++s) { up[s] = 0.0; pipe[s] = 0.0; }
+    const int top = rb.imax + 1;                       // highest row touched
+    const int t_last = (top - rb.imin) + 2 * KSW - 1;
+    // stage s receives row rho = top - t + 2 s at time t and mixes it with the row rho + 1 it holds
+    double nxt = Zt[int64_t(top) * n + qq];
+    for (int t = 0; t <= t_last; ++t) {
+        const double fresh = nxt;
+        const int rn = top - (t + 1);
+        nxt = rn >= rb.imin ? Zt[int64_t(rn) * n + qq] : 0.0;
+#pragma unroll
+        for (int s = KSW - 1; s >= 0; --s) {
+            const int rho = top - t + 2 * s;
+            const double in = s == 0 ? fresh : pipe[s];
+            double c = 1.0, sn = 0.0;
+            if (rho >= rb.lo[s] && rho <= rb.hi[s]) {
+                const long long o = rb.off[s] + 2ll * (rb.hi[s] - rho);
+                c = cs[o];
+                sn = cs[o + 1];
+            }
+            const double f = up[s];
+            const double out = sn * in + c * f;        // row rho + 1, done with sweep s
+            up[s] = c * in - sn * f;                   // row rho, kept for the next step
+            if (s == KSW - 1) {
+                const int ro = rho + 1;
+                if (live && ro >= rb.imin && ro <= top) Zt[int64_t(ro) * n + q] = out;
+            } else {
+                pipe[s + 1] = out;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- step 1c
+
+// Row j of W from eigenvector row ord[j] of Zt: scaled by 1/sqrt(lambda), sign chosen so that the entry
+// of largest magnitude (the first of them) is positive; rows from r on are zero.
+__global__ __launch_bounds__(256) void finish_kernel(const double *__restrict__ Zt, int n, const int *__restrict__ ord,
+                                                     const double *__restrict__ lam, int r, float *__restrict__ W,
+                                                     int64_t ldw)
+{
+    __shared__ double bestv[256];
+    __shared__ int besti[256];
+    const int j = blockIdx.x;
+    float *wr = W + int64_t(j) * ldw;
+    if (j >= r) {
+        for (int k = threadIdx.x; k < n; k += 256) wr[k] = 0.f;
+        return;
+    }
+    const double *u = Zt + int64_t(ord[j]) * n;
+    double bv = -1.0;
+    int bi = n;
+    for (int k = threadIdx.x; k < n; k += 256) {
+        const double a = fabs(u[k]);
+        if (a > bv) { bv = a; bi = k; }
+    }
+    bestv[threadIdx.x] = bv;
+    besti[threadIdx.x] = bi;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (threadIdx.x < off) {
+            const double ov = bestv[threadIdx.x + off];
+            const int oi = besti[threadIdx.x + off];
+            if (ov > bestv[threadIdx.x] || (ov == bestv[threadIdx.x] && oi < besti[threadIdx.x])) {
+                bestv[threadIdx.x] = ov;
+                besti[threadIdx.x] = oi;
+            }
+        }
+        __syncthreads();
+    }
+    const double sgn = u[besti[0]] < 0.0 ? -1.0 : 1.0;
+    const double scale = sgn / sqrt(lam[j]);
+    for (int k = threadIdx.x; k < n; k += 256) wr[k] = float(scale * u[k]);
+}
+
+// ---------------------------------------------------------------- host side
+
+struct DevCarve {
+    size_t off_A, off_Zt, off_vec, off_P, off_T, off_cs, off_ord, off_lam, bytes;
+    size_t cs_doubles;     // capacity of ONE of the two rotation buffers
+};
+
+DevCarve dev_carve(int64_t n)
+{
+    DevCarve c;
+    const size_t nn = round_up(size_t(n) * size_t(n) * 8, kAlign);
+    const size_t vec = round_up(size_t(n) * 8, kAlign);
+    size_t o = 0;
+    c.off_A = o; o += nn;
+    c.off_Zt = o; o += nn;
+    c.off_vec = o; o += 8 * vec;                   // v, w (two of each), y, dg, e, tau
+    const size_t nchunks = size_t(n) / 128 + 2;
+    c.off_P = o; o += round_up(nchunks * NB * NB * 8, kAlign);
+    c.off_T = o; o += round_up(size_t(NB) * NB * 8, kAlign);
+    c.cs_doubles = size_t(KSW) * 2 * size_t(std::max<int64_t>(n, 1));
+    c.off_cs = o; o += 2 * round_up(c.cs_doubles * 8, kAlign);
+    c.off_ord = o; o += round_up(size_t(n) * 4, kAlign);
+    c.off_lam = o; o += vec;
+    c.bytes = o;
+    return c;
+}
+
+bool verbose()
+{
+    const char *v = std::getenv("LPD_VERBOSE");
+    return v && v[0] == '1';
+}
+
+#define LPD_HIP(call)                                             \
+    do {                                                          \
+        if ((call) != hipSuccess) { status = LPD_ERR_HIP; goto done; } \
+    } while (0)
+
+}  // namespace
+
+extern "C" int lpd_whiten_workspace(int64_t B, size_t *bytes)
+{
+    if (!bytes) return LPD_ERR_NULL;
+    if (B < 0 || B > 46340) return LPD_ERR_SHAPE;     // B * B must fit 32-bit row arithmetic
+    *bytes = dev_carve(B).bytes;
+    return LPD_OK;
+}
+
+extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, double gamma, double clip_ratio, float *W,
+                          int64_t ldw, double *eig_host, int64_t *rank, void *workspace, size_t workspace_bytes,
+                          void *hip_stream)
+{
+    if (B < 0 || d < 0 || B > 46340 || d > (int64_t(1) << 24)) return LPD_ERR_SHAPE;
+    if (!rank) return LPD_ERR_NULL;
+    *rank = 0;
+    if (B == 0) return LPD_OK;
+    if (!W || (d > 0 && !L)) return LPD_ERR_NULL;
+    if (ldw < B || (d > 0 && ldl < d)) return LPD_ERR_LD;
+    const int n = int(B);
+    const DevCarve cv = dev_carve(n);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < cv.bytes)
+        return LPD_ERR_WORKSPACE;
+
+    int status = LPD_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(workspace);
+    double *A = reinterpret_cast<double *>(ws + cv.off_A);
+    double *Zt = reinterpret_cast<double *>(ws + cv.off_Zt);
+    const size_t vec = round_up(size_t(n) * 8, kAlign);
+    auto vecp = [&](int k) { return reinterpret_cast<double *>(ws + cv.off_vec + size_t(k) * vec); };
+    double *vbuf[2] = {vecp(0), vecp(1)}, *wbuf[2] = {vecp(2), vecp(3)};
+    double *y = vecp(4), *dg_d = vecp(5), *e_d = vecp(6), *tau_d = vecp(7);
+    double *P = reinterpret_cast<double *>(ws + cv.off_P);
+    double *T = reinterpret_cast<double *>(ws + cv.off_T);
+    double *cs_d[2] = {reinterpret_cast<double *>(ws + cv.off_cs),
+                       reinterpret_cast<double *>(ws + cv.off_cs + round_up(cv.cs_doubles * 8, kAlign))};
+    int *ord_d = reinterpret_cast<int *>(ws + cv.off_ord);
+    double *lam_d = reinterpret_cast<double *>(ws + cv.off_lam);
+
+    const bool talk = verbose();
+    auto say = [&](const char *what) {
+        if (talk) { std::fprintf(stderr, "[lpd_whiten B=%d] %s\n", n, what); std::fflush(stderr); }
+    };
+
+    // page-locked staging: rotation batches (two in flight), the tridiagonal matrix, order and eigenvalues
+    double *cs_h[2] = {nullptr, nullptr};
+    double *dge_h = nullptr;
+    hipEvent_t cs_free[2] = {nullptr, nullptr}, tri_done = nullptr;
+    std::vector<double> dg(size_t(n), 0.0), e(size_t(n), 0.0);
+    std::vector<int64_t> ord;
+    bool ql_ok = true;
+    int hip_fail = 0;
+    int64_t r = 0;
+
+    LPD_HIP(hipHostMalloc(reinterpret_cast<void **>(&cs_h[0]), cv.cs_doubles * 8, hipHostMallocDefault));
+    LPD_HIP(hipHostMalloc(reinterpret_cast<void **>(&cs_h[1]), cv.cs_doubles * 8, hipHostMallocDefault));
+    LPD_HIP(hipHostMalloc(reinterpret_cast<void **>(&dge_h), size_t(n) * 8 * 3, hipHostMallocDefault));
+    LPD_HIP(hipEventCreateWithFlags(&cs_free[0], hipEventDisableTiming));
+    LPD_HIP(hipEventCreateWithFlags(&cs_free[1], hipEventDisableTiming));
+    LPD_HIP(hipEventCreateWithFlags(&tri_done, hipEventDisableTiming));
+
+    say("landmark kernel matrix");
+    {
+        const dim3 grid((n + 15) / 16, (n + 15) / 16);
+        hipLaunchKernelGGL(kll_kernel, grid, dim3(256), 0, s, L, n, int(d), ldl, gamma, A);
+        LPD_HIP(hipGetLastError());
+    }
+
+    say("tridiagonalisation");
+    {
+        int pending = 0;
+        for (int j = 0; j + 2 < n; ++j) {
+            double *vc = vbuf[j & 1], *wc = wbuf[j & 1];
+            const double *vp = vbuf[(j & 1) ^ 1], *wp = wbuf[(j & 1) ^ 1];
+            hipLaunchKernelGGL(hh_kernel, dim3(1), dim3(1024), 0, s, A, n, j, pending, vp, wp, vc, dg_d, e_d, tau_d);
+            const int rows = n - j - 1;
+            const int grid = std::min(2048, (rows + 3) / 4);
+            hipLaunchKernelGGL(trail_kernel, dim3(grid), dim3(256), 0, s, A, n, j, pending, vp, wp, vc, y);
+            hipLaunchKernelGGL(w_kernel, dim3(1), dim3(1024), 0, s, n, j, tau_d, vc, y, wc);
+            pending = 1;
+            if ((j & 1023) == 1023) LPD_HIP(hipGetLastError());
+        }
+        if (n >= 2) {
+            const int jl = n - 3;        // last reflector, if any
+            const double *vp = vbuf[jl & 1], *wp = wbuf[jl & 1];
+            hipLaunchKernelGGL(tri_tail_kernel, dim3(1), dim3(64), 0, s, A, n, n >= 3 ? 1 : 0, n >= 3 ? vp : A,
+                               n >= 3 ? wp : A, dg_d, e_d);
+        } else {
+            LPD_HIP(hipMemcpyAsync(dg_d, A, 8, hipMemcpyDeviceToDevice, s));
+        }
+        LPD_HIP(hipGetLastError());
+        LPD_HIP(hipMemcpyAsync(dge_h, dg_d, size_t(n) * 8, hipMemcpyDeviceToHost, s));
+        LPD_HIP(hipMemcpyAsync(dge_h + n, e_d, size_t(n) * 8, hipMemcpyDeviceToHost, s));
+        LPD_HIP(hipEventRecord(tri_done, s));
+    }
+
+    // Q^T into Zt while the host starts on the tridiagonal matrix
+    {
+        hipLaunchKernelGGL(identity_kernel, dim3(2048), dim3(256), 0, s, Zt, n);
+        const int nref = n - 2;
+        const int npanel = nref > 0 ? (nref + NB - 1) / NB : 0;
+        for (int pi = npanel - 1; pi >= 0; --pi) {
+            const int k0 = pi * NB;
+            const int nb = std::min(NB, nref - k0);
+            const int nchunks = (n - (k0 + 1) + 127) / 128;
+            hipLaunchKernelGGL(panel_gram_kernel, dim3(nchunks), dim3(256), 0, s, A, n, k0, nb, P);
+            hipLaunchKernelGGL(panel_t_kernel, dim3(1), dim3(64), 0, s, P, nchunks, k0, nb, tau_d, T);
+            // rows up to k0 are still unit vectors with nothing in the columns this panel touches
+            const int r0 = k0 + 1;
+            const int nblk = (n - r0 + 15) / 16;
+            hipLaunchKernelGGL(panel_apply_kernel, dim3(nblk), dim3(256), 0, s, Zt, n, A, k0, nb, T, r0);
+        }
+        LPD_HIP(hipGetLastError());
+    }
+
+    LPD_HIP(hipEventSynchronize(tri_done));     // dg, e on the host; the panel kernels queued behind them keep running
+    std::memcpy(dg.data(), dge_h, size_t(n) * 8);
+    std::memcpy(e.data(), dge_h + n, size_t(n) * 8);
+    if (n == 1) e[0] = 0.0;
+
+    say("QL iteration (host) with rotation passes (device)");
+    {
+        int64_t nbatch = 0;
+        auto apply = [&](const std::vector<lpd_host::Sweep> &sw, const std::vector<double> &cs) {
+            if (hip_fail || sw.empty()) return;
+            const int b = int(nbatch & 1);
+            ++nbatch;
+            RotBatch rb;
+            rb.imin = n;
+            rb.imax = 0;
+            for (int k = 0; k < KSW; ++k) { rb.lo[k] = 1; rb.hi[k] = 0; rb.off[k] = 0; }
+            for (size_t k = 0; k < sw.size() && k < size_t(KSW); ++k) {
+                rb.lo[k] = int(sw[k].lo);
+                rb.hi[k] = int(sw[k].hi);
+                rb.off[k] = (long long)sw[k].off;
+                rb.imin = std::min(rb.imin, rb.lo[k]);
+                rb.imax = std::max(rb.imax, rb.hi[k]);
+            }
+            if (cs.size() > cv.cs_doubles || sw.size() > size_t(KSW) || rb.imax + 1 >= n || rb.imin < 0) {
+                hip_fail = 2;
+                return;
+            }
+            // the staging buffer is free once the copy queued from it two batches ago has run
+            if (hipEventSynchronize(cs_free[b]) != hipSuccess) { hip_fail = 1; return; }
+            std::memcpy(cs_h[b], cs.data(), cs.size() * 8);
+            if (hipMemcpyAsync(cs_d[b], cs_h[b], cs.size() * 8, hipMemcpyHostToDevice, s) != hipSuccess ||
+                hipEventRecord(cs_free[b], s) != hipSuccess) { hip_fail = 1; return; }
+            hipLaunchKernelGGL(rot_kernel, dim3((n + 63) / 64), dim3(64), 0, s, Zt, n, rb, cs_d[b]);
+            if (hipGetLastError() != hipSuccess) hip_fail = 1;
+        };
+        int last_decile = -1;
+        auto prog = [&](int64_t l) {
+            const int dec = int(l * 10 / n);
+            if (talk && dec != last_decile) {
+                last_decile = dec;
+                std::fprintf(stderr, "[lpd_whiten B=%d] QL iteration %d%%\n", n, dec * 10);
+                std::fflush(stderr);
+            }
+        };
+        ql_ok = lpd_host::tridiag_ql(dg.data(), e.data(), n, KSW, apply, prog);
+    }
+    if (hip_fail) { status = hip_fail == 1 ? LPD_ERR_HIP : LPD_ERR_NUMERIC; goto done; }
+    if (!ql_ok) { status = LPD_ERR_NUMERIC; goto done; }
+
+    say("ordering and scaling");
+    r = lpd_host::order_and_clip(dg.data(), n, clip_ratio, ord, eig_host);
+    if (r < 0) { status = LPD_ERR_NUMERIC; goto done; }
+    {
+        // order (int32) and sorted eigenvalues through the page-locked block, after all rotation copies
+        LPD_HIP(hipStreamSynchronize(s));
+        int *ord_h = reinterpret_cast<int *>(dge_h);
+        double *lam_h = dge_h + n;
+        for (int j = 0; j < n; ++j) { ord_h[j] = int(ord[size_t(j)]); lam_h[j] = dg[size_t(ord[size_t(j)])]; }
+        LPD_HIP(hipMemcpyAsync(ord_d, ord_h, size_t(n) * 4, hipMemcpyHostToDevice, s));
+        LPD_HIP(hipMemcpyAsync(lam_d, lam_h, size_t(n) * 8, hipMemcpyHostToDevice, s));
+        hipLaunchKernelGGL(finish_kernel, dim3(n), dim3(256), 0, s, Zt, n, ord_d, lam_d, int(r), W, ldw);
+        LPD_HIP(hipGetLastError());
+    }
+    *rank = r;
+done:
+    if (hipStreamSynchronize(s) != hipSuccess && status == LPD_OK) status = LPD_ERR_HIP;
+    for (int b = 0; b < 2; ++b) {
+        if (cs_free[b]) (void)hipEventDestroy(cs_free[b]);
+        if (cs_h[b]) (void)hipHostFree(cs_h[b]);
+    }
+    if (tri_done) (void)hipEventDestroy(tri_done);
+    if (dge_h) (void)hipHostFree(dge_h);
+    return status;
+}

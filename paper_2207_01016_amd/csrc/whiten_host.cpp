@@ -20,6 +20,7 @@
 #include <vector>
 
 #include "../../include/lpd.h"
+#include "whiten_internal.h"
 
 namespace {
 
@@ -187,7 +188,7 @@ void tridiagonalise(double *A, int64_t n, double *dg, double *e, double *tau)
 // ---- step 1b, part 2: eigen-decomposition of the tridiagonal matrix.
 // Zt (n x n) must hold the identity on entry; on exit row i of Zt is the
 // eigenvector (in the tridiagonal basis) of eigenvalue dg[i].
-struct Sweep { int64_t lo, hi; size_t off; };   // rotations for i = hi down to lo; c,s pairs at off
+using lpd_host::Sweep;
 
 void apply_rotations(double *Zt, int64_t n, const std::vector<Sweep> &sw, const std::vector<double> &cs)
 {
@@ -216,72 +217,6 @@ void apply_rotations(double *Zt, int64_t n, const std::vector<Sweep> &sw, const 
             }
         }
     }
-}
-
-// Implicit-shift QL iteration; returns false if an eigenvalue needs more than 60 sweeps.
-bool tridiag_ql(double *dg, double *e, int64_t n, double *Zt)
-{
-    constexpr int BATCH = 32;
-    std::vector<Sweep> sw;
-    std::vector<double> cs;
-    cs.reserve(size_t(BATCH) * 2 * n);
-    const double eps = 2.220446049250313e-16;
-    for (int64_t l = 0; l < n; ++l) {
-        progress("QL iteration", l, n);
-        int iter = 0;
-        while (true) {
-            int64_t m = l;
-            for (; m < n - 1; ++m) {
-                const double dd = std::fabs(dg[m]) + std::fabs(dg[m + 1]);
-                if (std::fabs(e[m]) <= eps * dd) break;
-            }
-            if (m == l) break;
-            if (++iter > 60) return false;
-            // Wilkinson-type shift from the leading 2x2 block of the active window
-            double g = (dg[l + 1] - dg[l]) / (2.0 * e[l]);
-            double r = std::hypot(g, 1.0);
-            g = dg[m] - dg[l] + e[l] / (g + std::copysign(r, g));
-            double s = 1.0, c = 1.0, p = 0.0;
-            Sweep rec{m, m - 1, cs.size()};
-            int64_t i = m - 1;
-            bool underflow = false;
-            for (; i >= l; --i) {
-                const double f = s * e[i];
-                const double b = c * e[i];
-                r = std::hypot(f, g);
-                e[i + 1] = r;
-                if (r == 0.0) {
-                    dg[i + 1] -= p;
-                    e[m] = 0.0;
-                    underflow = true;
-                    break;
-                }
-                s = f / r;
-                c = g / r;
-                g = dg[i + 1] - p;
-                r = (dg[i] - g) * s + 2.0 * c * b;
-                p = s * r;
-                dg[i + 1] = g + p;
-                g = c * r - b;
-                cs.push_back(c);
-                cs.push_back(s);
-                rec.lo = i;
-            }
-            if (rec.lo <= rec.hi) sw.push_back(rec);
-            if (!underflow) {
-                dg[l] -= p;
-                e[l] = g;
-                e[m] = 0.0;
-            }
-            if (int(sw.size()) >= BATCH) {
-                apply_rotations(Zt, n, sw, cs);
-                sw.clear();
-                cs.clear();
-            }
-        }
-    }
-    apply_rotations(Zt, n, sw, cs);
-    return true;
 }
 
 // ---- step 1b, part 3: rows of Zt become eigenvectors of the original matrix:
@@ -357,6 +292,91 @@ void back_transform(const double *A, const double *tau, int64_t n, double *Zt)
 
 }  // namespace
 
+namespace lpd_host {
+
+// Implicit-shift QL iteration; returns false if an eigenvalue needs more than 60 sweeps.
+bool tridiag_ql(double *dg, double *e, int64_t n, int batch, const ApplyRotations &apply,
+                const std::function<void(int64_t)> &progress)
+{
+    std::vector<Sweep> sw;
+    std::vector<double> cs;
+    cs.reserve(size_t(batch) * 2 * n);
+    const double eps = 2.220446049250313e-16;
+    for (int64_t l = 0; l < n; ++l) {
+        if (progress) progress(l);
+        int iter = 0;
+        while (true) {
+            int64_t m = l;
+            for (; m < n - 1; ++m) {
+                const double dd = std::fabs(dg[m]) + std::fabs(dg[m + 1]);
+                if (std::fabs(e[m]) <= eps * dd) break;
+            }
+            if (m == l) break;
+            if (++iter > 60) return false;
+            // Wilkinson-type shift from the leading 2x2 block of the active window
+            double g = (dg[l + 1] - dg[l]) / (2.0 * e[l]);
+            double r = std::hypot(g, 1.0);
+            g = dg[m] - dg[l] + e[l] / (g + std::copysign(r, g));
+            double s = 1.0, c = 1.0, p = 0.0;
+            Sweep rec{m, m - 1, cs.size()};
+            int64_t i = m - 1;
+            bool underflow = false;
+            for (; i >= l; --i) {
+                const double f = s * e[i];
+                const double b = c * e[i];
+                r = std::hypot(f, g);
+                e[i + 1] = r;
+                if (r == 0.0) {
+                    dg[i + 1] -= p;
+                    e[m] = 0.0;
+                    underflow = true;
+                    break;
+                }
+                s = f / r;
+                c = g / r;
+                g = dg[i + 1] - p;
+                r = (dg[i] - g) * s + 2.0 * c * b;
+                p = s * r;
+                dg[i + 1] = g + p;
+                g = c * r - b;
+                cs.push_back(c);
+                cs.push_back(s);
+                rec.lo = i;
+            }
+            if (rec.lo <= rec.hi) sw.push_back(rec);
+            if (!underflow) {
+                dg[l] -= p;
+                e[l] = g;
+                e[m] = 0.0;
+            }
+            if (int(sw.size()) >= batch) {
+                apply(sw, cs);
+                sw.clear();
+                cs.clear();
+            }
+        }
+    }
+    if (!sw.empty()) apply(sw, cs);
+    return true;
+}
+
+int64_t order_and_clip(const double *dg, int64_t n, double clip_ratio, std::vector<int64_t> &ord, double *eig_sorted)
+{
+    ord.resize(size_t(n));
+    std::iota(ord.begin(), ord.end(), int64_t(0));
+    std::stable_sort(ord.begin(), ord.end(), [&](int64_t a, int64_t b) { return dg[a] > dg[b]; });
+    if (eig_sorted)
+        for (int64_t j = 0; j < n; ++j) eig_sorted[j] = dg[ord[j]];
+    if (n == 0) return 0;
+    const double top = dg[ord[0]];
+    if (!(top > 0.0)) return -1;
+    int64_t r = 0;
+    while (r < n && dg[ord[r]] >= clip_ratio * top && dg[ord[r]] > 0.0) ++r;
+    return r;
+}
+
+}  // namespace lpd_host
+
 extern "C" int lpd_whiten_host(const float *L_host, int64_t B, int64_t d, int64_t ldl, double gamma,
                                double clip_ratio, float *W_host, int64_t ldw, double *eig_host, int64_t *rank)
 {
@@ -380,21 +400,19 @@ extern "C" int lpd_whiten_host(const float *L_host, int64_t B, int64_t d, int64_
     tridiagonalise(A.data(), n, dg.data(), e.data(), tau.data());
     for (int64_t i = 0; i < n; ++i) Zt[i * n + i] = 1.0;
     say("QL iteration");
-    if (!tridiag_ql(dg.data(), e.data(), n, Zt.data())) return LPD_ERR_NUMERIC;
+    {
+        double *zt = Zt.data();
+        auto apply = [&](const std::vector<Sweep> &sw, const std::vector<double> &cs) { apply_rotations(zt, n, sw, cs); };
+        auto prog = [&](int64_t l) { progress("QL iteration", l, n); };
+        if (!lpd_host::tridiag_ql(dg.data(), e.data(), n, 32, apply, prog)) return LPD_ERR_NUMERIC;
+    }
     say("back-transformation");
     back_transform(A.data(), tau.data(), n, Zt.data());
     say("ordering and scaling");
 
-    std::vector<int64_t> ord(n);
-    std::iota(ord.begin(), ord.end(), int64_t(0));
-    std::stable_sort(ord.begin(), ord.end(), [&](int64_t a, int64_t b) { return dg[a] > dg[b]; });
-    const double top = dg[ord[0]];
-    if (eig_host)
-        for (int64_t j = 0; j < n; ++j) eig_host[j] = dg[ord[j]];
-    if (!(top > 0.0)) return LPD_ERR_NUMERIC;
-
-    int64_t r = 0;
-    while (r < n && dg[ord[r]] >= clip_ratio * top && dg[ord[r]] > 0.0) ++r;
+    std::vector<int64_t> ord;
+    const int64_t r = lpd_host::order_and_clip(dg.data(), n, clip_ratio, ord, eig_host);
+    if (r < 0) return LPD_ERR_NUMERIC;
 #pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < n; ++j) {
         float *wr = W_host + j * ldw;

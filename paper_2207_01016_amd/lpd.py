@@ -50,6 +50,9 @@ SIGNATURES = {
     "lpd_set_option": (ctypes.c_int, [ctypes.c_int, _i64]),
     "lpd_whiten_host": (ctypes.c_int, [_vp, _i64, _i64, _i64, ctypes.c_double, ctypes.c_double, _vp, _i64, _vp,
                                        ctypes.POINTER(_i64)]),
+    "lpd_whiten_workspace": (ctypes.c_int, [_i64, ctypes.POINTER(_sz)]),
+    "lpd_whiten": (ctypes.c_int, [_vp, _i64, _i64, _i64, ctypes.c_double, ctypes.c_double, _vp, _i64, _vp,
+                                  ctypes.POINTER(_i64), _vp, _sz, _vp]),
     "lpd_nystrom_factor_workspace": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
     "lpd_nystrom_factor": (ctypes.c_int, _FACTOR_ARGS),
     "lpd_nystrom_factor_profiled": (ctypes.c_int, _FACTOR_ARGS + [ctypes.POINTER(FactorProfile)]),
@@ -142,6 +145,33 @@ def lpd_whiten_host(L: torch.Tensor, gamma: float, clip_ratio: float = 1e-10):
     st = lib().lpd_whiten_host(L.data_ptr(), B, d, max(d, 1), float(gamma), float(clip_ratio), W.data_ptr(),
                                max(B, 1), eig.data_ptr(), ctypes.byref(rank))
     _check(st, "lpd_whiten_host")
+    return W, eig, int(rank.value)
+
+
+def lpd_whiten_workspace(B: int) -> int:
+    """Bytes of device scratch lpd_whiten needs for B landmarks."""
+    nb = _sz(0)
+    _check(lib().lpd_whiten_workspace(B, ctypes.byref(nb)), "lpd_whiten_workspace")
+    return int(nb.value)
+
+
+def lpd_whiten(L: torch.Tensor, gamma: float, clip_ratio: float = 1e-10, workspace=None):
+    """Steps 1a-1c with the cubic work on the device. L: B x d float32 device tensor.
+    Returns (W B x B float32 on L's device, eig float64 CPU tensor, rank). Blocks until W is complete."""
+    L = _dev_f32(L, "L", 2)
+    B, d = L.shape
+    W = torch.empty((B, B), dtype=torch.float32, device=L.device)
+    eig = torch.empty(B, dtype=torch.float64)
+    rank = _i64(0)
+    nbytes = lpd_whiten_workspace(B)
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=L.device)
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda:
+        raise TypeError("workspace: expected a uint8 device tensor")
+    st = lib().lpd_whiten(L.data_ptr(), B, d, _ld(L), float(gamma), float(clip_ratio), W.data_ptr(), max(B, 1),
+                          eig.data_ptr(), ctypes.byref(rank), workspace.data_ptr(), workspace.numel(),
+                          _stream(L.device))
+    _check(st, "lpd_whiten")
     return W, eig, int(rank.value)
 
 

@@ -212,3 +212,25 @@ def test_whiten_host_errors(L):
     assert L.lpd_whiten_host(p, 4, 2, 2, 0.5, 1e-10, None, 4, None, ctypes.byref(r)) == -1
     assert L.lpd_whiten_host(p, 4, 2, 2, 0.5, 1e-10, p, 4, None, None) == -1
     assert L.lpd_whiten_host(p, -4, 2, 2, 0.5, 1e-10, p, 4, None, ctypes.byref(r)) == -2
+
+
+def test_whiten_device_query_and_argument_errors(L):
+    nb = ctypes.c_size_t(0)
+    assert L.lpd_whiten_workspace(4096, ctypes.byref(nb)) == 0
+    assert nb.value >= 2 * 4096 * 4096 * 8 and nb.value % 256 == 0
+    assert L.lpd_whiten_workspace(4096, None) == -1
+    assert L.lpd_whiten_workspace(-1, ctypes.byref(nb)) == -2
+    assert L.lpd_whiten_workspace(50_000, ctypes.byref(nb)) == -2          # above the supported B
+    r = ctypes.c_int64(7)
+    buf = (ctypes.c_float * 64)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    f = L.lpd_whiten
+    #        L  B  d  ldl gamma clip  W  ldw eig   rank             ws    bytes stream
+    assert f(p, 0, 2, 2, 0.5, 1e-10, p, 1, None, ctypes.byref(r), None, 0, None) == 0 and r.value == 0
+    assert f(p, 4, 2, 1, 0.5, 1e-10, p, 4, None, ctypes.byref(r), None, 0, None) == -3
+    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 3, None, ctypes.byref(r), None, 0, None) == -3
+    assert f(p, 4, 2, 2, 0.5, 1e-10, None, 4, None, ctypes.byref(r), None, 0, None) == -1
+    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 4, None, None, None, 0, None) == -1
+    assert f(p, -4, 2, 2, 0.5, 1e-10, p, 4, None, ctypes.byref(r), None, 0, None) == -2
+    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 4, None, ctypes.byref(r), None, 0, None) == -4   # no workspace
+    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 4, None, ctypes.byref(r), p, 256, None) == -4    # too small

@@ -45,14 +45,30 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", default="auto", choices=["auto", "128x128", "256x128", "256x256"])
     ap.add_argument("--workspace-mult", type=float, default=1.0)
-    ap.add_argument("--path", default="factor", choices=["factor", "solver", "predict", "stream"],
+    ap.add_argument("--path", default="factor", choices=["factor", "solver", "predict", "stream", "whiten"],
                     help="factor: Nystrom factor + margin sweep (default); solver: batched dual coordinate ascent "
-                         "on G; predict: scores of new points; stream: the factor copied to pinned host memory as it is made")
+                         "on G; predict: scores of new points; stream: the factor copied to pinned host memory as it is made; whiten: the one-off preparation "
+                         "(steps 1a-1c) on the device")
     ap.add_argument("--classifiers", type=int, default=10, help="predict: number of classifiers scored at once")
+    ap.add_argument("--whiten", default="device", choices=["device", "host"],
+                    help="steps 1a-1c (one-off preparation, outside the timed region): lpd_whiten on the GPU, or the "
+                         "host routine")
     ap.add_argument("--chunk-rows", type=int, default=0, help="stream: rows per chunk (0 = the library's suggestion)")
     ap.add_argument("--random-w", action="store_true",
                     help="skip the host eigendecomposition and use a random W (tuning only; marks the line invalid)")
     return ap.parse_args()
+
+
+def whiten(args, lpd, L, gamma):
+    """W on the host (float32 CPU tensor) and the rank, by the routine --whiten names."""
+    import torch
+    if args.whiten == "host":
+        W, eig, rank = lpd.lpd_whiten_host(L.cpu(), gamma)
+        return W, rank
+    W, eig, rank = lpd.lpd_whiten(L, gamma)
+    W = W.cpu()
+    torch.cuda.empty_cache()        # the eigensolver scratch (2 B^2 doubles) goes back to the pool
+    return W, rank
 
 
 def cpu_baseline(orc, wl, Xs, L, W, w, target_s):
@@ -108,7 +124,7 @@ def bench_solver(args):
     X = workloads.make_X(wl, dev)
     idx = workloads.landmark_indices(wl)
     L = X[idx.to(dev)].contiguous()
-    W_host, eig, rank = lpd.lpd_whiten_host(L.cpu(), wl.gamma)
+    W_host, rank = whiten(args, lpd, L, wl.gamma)
     G = torch.empty((wl.n, wl.B), dtype=torch.float32, device=dev)
     lpd.lpd_nystrom_factor(X, L, wl.gamma, W_host.to(dev), G, lpd.alloc_workspace(wl.n, wl.d, wl.B, dev), r=rank)
     gsq = lpd.lpd_row_sqnorms(G, r=rank)
@@ -204,7 +220,7 @@ def bench_predict(args):
         W_host = torch.randn((wl.B, wl.B), generator=torch.Generator().manual_seed(1)) / wl.B ** 0.5
         rank = wl.B
     else:
-        W_host, eig, rank = lpd.lpd_whiten_host(L.cpu(), wl.gamma)
+        W_host, rank = whiten(args, lpd, L, wl.gamma)
     t_whiten = time.perf_counter() - t0
     c = args.classifiers
     Ws = (torch.randn((c, rank), generator=torch.Generator().manual_seed(2)) / rank ** 0.5)
@@ -241,7 +257,7 @@ def bench_predict(args):
         "data": "synthetic" + (" (random W: tuning run)" if args.random_w else ""),
         "config": {"workload": wl.name + " (first rows as new points)", "n_test": n_test, "d": wl.d, "B": wl.B,
                    "rank": rank, "classifiers": c, "gamma": wl.gamma},
-        "whiten_host_s": None if args.random_w else t_whiten,
+        "whiten_s": None if args.random_w else t_whiten,
         "roofline": {"kernel": "lpd_predict: gemm_nt_kernel<EPI_GAUSS> panels + consumer", "bound": "mfma",
                      "achieved": tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / FP32_MFMA_PEAK_TFLOPS, "flop_per_launch": flop, "avg_launch_ms": ms,
@@ -280,7 +296,7 @@ def bench_stream(args):
         W_host = torch.randn((wl.B, wl.B), generator=torch.Generator().manual_seed(1)) / wl.B ** 0.5
         rank = wl.B
     else:
-        W_host, eig, rank = lpd.lpd_whiten_host(L.cpu(), wl.gamma)
+        W_host, rank = whiten(args, lpd, L, wl.gamma)
     t_whiten = time.perf_counter() - t0
     W = W_host.to(dev)
     chunk_rows, nbytes = lpd.lpd_nystrom_factor_to_host_workspace(wl.n, wl.d, wl.B, args.chunk_rows)
@@ -306,13 +322,59 @@ def bench_stream(args):
         "data": "synthetic" + (" (random W: tuning run)" if args.random_w else ""),
         "config": {"workload": wl.name, "n": wl.n, "d": wl.d, "B": wl.B, "rank": rank, "gamma": wl.gamma,
                    "chunk_rows": chunk_rows, "workspace_bytes": nbytes, "G_host": "pinned, n x B float32"},
-        "whiten_host_s": None if args.random_w else t_whiten, "pin_alloc_s": t_pin,
+        "whiten_s": None if args.random_w else t_whiten, "pin_alloc_s": t_pin,
         "pcie_GBps": wl.n * wl.B * 4 / (ms * 1e-3) / 1e9,
         "roofline": {"kernel": "lpd_nystrom_factor_to_host: both GEMMs per chunk, copy of G overlapped",
                      "bound": "mfma", "achieved": tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / FP32_MFMA_PEAK_TFLOPS, "flop_per_launch": flop, "avg_launch_ms": ms,
                      "traffic": None},
     }
+    print(json.dumps(out))
+
+
+def bench_whiten(args):
+    """Steps 1a-1c on the device for the workload's landmarks: seconds per preparation, phase by phase."""
+    import torch
+    from paper_2207_01016_amd import lpd, workloads
+    dev = torch.device("cuda:0")
+    wl = workloads.WORKLOADS[args.workload]
+    n_rows = max(4 * wl.B, 65536)                 # landmarks are drawn from the first rows of the recipe
+    wl_s = wl.with_rows(min(wl.n, n_rows))
+    X = workloads.make_X(wl_s, dev)
+    L = X[workloads.landmark_indices(wl_s).to(dev)].contiguous()
+    del X
+    B = wl.B
+    ws = torch.empty(lpd.lpd_whiten_workspace(B), dtype=torch.uint8, device=dev)
+    for _ in range(args.warmup):
+        lpd.lpd_whiten(L, wl.gamma, workspace=ws)
+    phases, totals = {}, []
+    for _ in range(args.steps):
+        ph = {}
+        t0 = time.perf_counter()
+        W, eig, rank = lpd.lpd_whiten(L, wl.gamma, workspace=ws, phases=ph)
+        totals.append(time.perf_counter() - t0)
+        for k, v in ph.items():
+            phases[k] = phases.get(k, 0.0) + v / args.steps
+    sec = sum(totals) / len(totals)
+    # trailing-matrix pass of column j: m^2 doubles read and written once, m = B - j - 1
+    bytes_trail = 16.0 * sum(float(m) * m for m in range(2, B))
+    gbps = bytes_trail / max(phases["tridiagonalisation"], 1e-9) / 1e9
+    out = {
+        "metric": "stage1_preparation_seconds", "value": sec, "unit": "s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": wl.name + " (landmarks only)", "B": B, "d": wl.d, "gamma": wl.gamma, "rank": rank,
+                   "workspace_bytes": ws.numel()},
+        "phases_s": phases,
+        "roofline": {"kernel": "trail_kernel (rank-2 update + next matrix-vector product, one pass per column); "
+                               "time = the whole tridiagonalisation phase, its small kernels included",
+                     "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": gbps / HBM_PEAK_GBPS, "bytes_per_call": bytes_trail, "traffic": None},
+    }
+    if not args.no_cpu_baseline and B <= 4096:
+        t0 = time.perf_counter()
+        lpd.lpd_whiten_host(L.cpu(), wl.gamma)
+        out["host_routine_s"] = time.perf_counter() - t0
     print(json.dumps(out))
 
 
@@ -339,6 +401,9 @@ def main():
     if args.path == "stream":
         bench_stream(args)
         return
+    if args.path == "whiten":
+        bench_whiten(args)
+        return
     dev = torch.device("cuda:0")
     wl = workloads.WORKLOADS[args.workload]
 
@@ -353,7 +418,7 @@ def main():
         W_host = torch.randn((wl.B, wl.B), generator=g) / wl.B ** 0.5
         rank = wl.B
     else:
-        W_host, eig, rank = lpd.lpd_whiten_host(L_host, wl.gamma)
+        W_host, rank = whiten(args, lpd, L, wl.gamma)
     t_whiten = time.perf_counter() - t0
     W = W_host.to(dev)
     w = workloads.make_w(wl).to(dev)
@@ -418,7 +483,7 @@ def main():
                    "tflops": factor_tflops, "frac_of_fp32_mfma_peak": factor_tflops / FP32_MFMA_PEAK_TFLOPS,
                    "ms_kernel_block": ms_kb / steps, "ms_whiten": ms_whiten / steps, "ms_norms": ms_norms / steps},
         "sweep": {"ms_per_step": ms_sweep / steps, "gbps": sweep_gbps, "frac_of_hbm_peak": sweep_gbps / HBM_PEAK_GBPS},
-        "whiten_host_s": None if args.random_w else t_whiten,
+        "whiten_s": None if args.random_w else t_whiten, "whiten_routine": None if args.random_w else args.whiten,
         "roofline": {"kernel": "gemm_nt_kernel<EPI_STORE> (whitening product Z W^T)", "bound": "mfma",
                      "achieved": whiten_tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": whiten_tflops / FP32_MFMA_PEAK_TFLOPS,

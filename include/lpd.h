@@ -115,6 +115,10 @@ int lpd_whiten_host(const float *L_host, int64_t B, int64_t d, int64_t ldl,
  *   rank       host out
  *   workspace  device, 256-byte aligned, at least lpd_whiten_workspace(B) bytes
  *              (two B x B double matrices and some vectors)
+ *   phase_seconds  host out, may be NULL: 5 doubles, wall time of the kernel
+ *              matrix, the tridiagonalisation, the reflector accumulation, the
+ *              QL iteration with its rotation passes, and the final scaling.
+ *              Asking for them drains the stream between phases.
  * The call BLOCKS until W is complete.  It allocates page-locked host staging
  * (a few MB) and events for its duration, no device memory.  B <= 46340.
  * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE, LPD_ERR_LD, LPD_ERR_WORKSPACE,
@@ -124,7 +128,8 @@ int lpd_whiten_workspace(int64_t B, size_t *bytes);
 int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl,
                double gamma, double clip_ratio,
                float *W, int64_t ldw, double *eig_host, int64_t *rank,
-               void *workspace, size_t workspace_bytes, void *hip_stream);
+               void *workspace, size_t workspace_bytes, void *hip_stream,
+               double *phase_seconds);
 
 /*
  * Device scratch for lpd_nystrom_factor / lpd_kernel_block: squared row norms

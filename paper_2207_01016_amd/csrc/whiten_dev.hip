@@ -19,6 +19,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -322,49 +323,94 @@ __global__ __launch_bounds__(256) void panel_apply_kernel(double *__restrict__ Z
 
 // ---------------------------------------------------------------- step 1b, QL rotations
 
-struct RotBatch {
-    int imin, imax;            // lowest and highest rotation index of the batch
-    int lo[KSW], hi[KSW];      // sweep s rotates i = hi[s] down to lo[s]; lo > hi: idle stage
-    long long off[KSW];        // its (c, s) pairs start at cs[off[s]], highest index first
-};
+// A batch as the host hands it over: header of 3 * KSW 64-bit integers (lo, hi, off per sweep; sweep s
+// rotates i = hi[s] down to lo[s], lo > hi marks an idle stage; its (c, s) pairs start at pairs[off[s]],
+// highest index first), then the pairs.
+constexpr int ROT_HDR = 3 * KSW;   // in 8-byte words
+constexpr int CH = 8;              // time steps per chunk of the rotation pass
 
-__global__ __launch_bounds__(64) void rot_kernel(double *__restrict__ Zt, int n, RotBatch rb,
-                                                 const double *__restrict__ cs)
+// Time-major coefficient table for one pass: tab[t][s] = (c, s) of the rotation stage s applies at
+// time t (index rho = top - t + 2 s), the identity where sweep s has none there.
+__global__ __launch_bounds__(256) void rot_table_kernel(const long long *__restrict__ hdr,
+                                                        const double *__restrict__ pairs, int top, int nsteps,
+                                                        double *__restrict__ tab)
 {
-    const int q = blockIdx.x * 64 + threadIdx.x;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= nsteps * KSW) return;
+    const int t = idx / KSW, s = idx % KSW;
+    const long long lo = hdr[s], hi = hdr[KSW + s], off = hdr[2 * KSW + s];
+    const long long rho = (long long)top - t + 2 * s;
+    double c = 1.0, sn = 0.0;
+    if (rho >= lo && rho <= hi) {
+        c = pairs[off + 2 * (hi - rho)];
+        sn = pairs[off + 2 * (hi - rho) + 1];
+    }
+    tab[2 * idx] = c;
+    tab[2 * idx + 1] = sn;
+}
+
+// One pass of up to KSW sweeps over rows imin..top of Zt.  A wavefront owns 64 columns; stage s of the
+// register pipeline receives row rho = top - t + 2 s at time t, mixes it with the row rho + 1 it holds,
+// and passes that one on.  Rows and coefficients of the next chunk of CH steps are fetched while the
+// current chunk is computed; the coefficients go through LDS so that every lane reads them by broadcast.
+__global__ __launch_bounds__(64) void rot_kernel(double *__restrict__ Zt, int n, int imin, int top, int nchunks,
+                                                 const double *__restrict__ tab)
+{
+    __shared__ double coef[2][CH * KSW * 2];
+    const int lane = threadIdx.x;
+    const int q = blockIdx.x * 64 + lane;
     const bool live = q < n;
     const int qq = live ? q : n - 1;
-    double up[KSW], pipe[KSW];
+    double up[KSW], pipe[KSW], cur[CH], nxt[CH], cf[4];
 #pragma unroll
     for (int s = 0; s < KSW; ++s) { up[s] = 0.0; pipe[s] = 0.0; }
-    const int top = rb.imax + 1;                       // highest row touched
-    const int t_last = (top - rb.imin) + 2 * KSW - 1;
-    // stage s receives row rho = top - t + 2 s at time t and mixes it with the row rho + 1 it holds
-    double nxt = Zt[int64_t(top) * n + qq];
-    for (int t = 0; t <= t_last; ++t) {
-        const double fresh = nxt;
-        const int rn = top - (t + 1);
-        nxt = rn >= rb.imin ? Zt[int64_t(rn) * n + qq] : 0.0;
 #pragma unroll
-        for (int s = KSW - 1; s >= 0; --s) {
-            const int rho = top - t + 2 * s;
-            const double in = s == 0 ? fresh : pipe[s];
-            double c = 1.0, sn = 0.0;
-            if (rho >= rb.lo[s] && rho <= rb.hi[s]) {
-                const long long o = rb.off[s] + 2ll * (rb.hi[s] - rho);
-                c = cs[o];
-                sn = cs[o + 1];
+    for (int u = 0; u < CH; ++u) {
+        const int rho = top - u;
+        cur[u] = rho >= imin ? Zt[int64_t(rho) * n + qq] : 0.0;
+        nxt[u] = 0.0;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) coef[0][lane * 4 + k] = tab[lane * 4 + k];
+    __syncthreads();
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const bool more = ch + 1 < nchunks;
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                const int rho = top - ((ch + 1) * CH + u);
+                nxt[u] = rho >= imin ? Zt[int64_t(rho) * n + qq] : 0.0;
             }
-            const double f = up[s];
-            const double out = sn * in + c * f;        // row rho + 1, done with sweep s
-            up[s] = c * in - sn * f;                   // row rho, kept for the next step
-            if (s == KSW - 1) {
-                const int ro = rho + 1;
-                if (live && ro >= rb.imin && ro <= top) Zt[int64_t(ro) * n + q] = out;
-            } else {
-                pipe[s + 1] = out;
+            const double *src = tab + int64_t(ch + 1) * (CH * KSW * 2) + lane * 4;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) cf[k] = src[k];
+        }
+        const double *cb = coef[ch & 1];
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int t = ch * CH + u;
+#pragma unroll
+            for (int s = KSW - 1; s >= 0; --s) {
+                const double c = cb[(u * KSW + s) * 2], sn = cb[(u * KSW + s) * 2 + 1];
+                const double in = s == 0 ? cur[u] : pipe[s];
+                const double f = up[s];
+                const double out = sn * in + c * f;        // row rho + 1, done with sweep s
+                up[s] = c * in - sn * f;                   // row rho, kept for the next step
+                if (s == KSW - 1) {
+                    const int ro = top - t + 2 * (KSW - 1) + 1;
+                    if (live && ro >= imin && ro <= top) Zt[int64_t(ro) * n + q] = out;
+                } else {
+                    pipe[s + 1] = out;
+                }
             }
         }
+        if (more) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) coef[(ch + 1) & 1][lane * 4 + k] = cf[k];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < CH; ++u) cur[u] = nxt[u];
     }
 }
 
@@ -413,8 +459,8 @@ __global__ __launch_bounds__(256) void finish_kernel(const double *__restrict__ 
 // ---------------------------------------------------------------- host side
 
 struct DevCarve {
-    size_t off_A, off_Zt, off_vec, off_P, off_T, off_cs, off_ord, off_lam, bytes;
-    size_t cs_doubles;     // capacity of ONE of the two rotation buffers
+    size_t off_A, off_Zt, off_vec, off_P, off_T, off_cs, off_tab, off_ord, off_lam, bytes;
+    size_t cs_doubles;     // capacity of ONE of the two rotation buffers, header included
 };
 
 DevCarve dev_carve(int64_t n)
@@ -429,8 +475,9 @@ DevCarve dev_carve(int64_t n)
     const size_t nchunks = size_t(n) / 128 + 2;
     c.off_P = o; o += round_up(nchunks * NB * NB * 8, kAlign);
     c.off_T = o; o += round_up(size_t(NB) * NB * 8, kAlign);
-    c.cs_doubles = size_t(KSW) * 2 * size_t(std::max<int64_t>(n, 1));
+    c.cs_doubles = ROT_HDR + size_t(KSW) * 2 * size_t(std::max<int64_t>(n, 1));
     c.off_cs = o; o += 2 * round_up(c.cs_doubles * 8, kAlign);
+    c.off_tab = o; o += round_up((size_t(n) + 2 * KSW + 2 * CH) * KSW * 2 * 8, kAlign);
     c.off_ord = o; o += round_up(size_t(n) * 4, kAlign);
     c.off_lam = o; o += vec;
     c.bytes = o;
@@ -460,7 +507,7 @@ extern "C" int lpd_whiten_workspace(int64_t B, size_t *bytes)
 
 extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, double gamma, double clip_ratio, float *W,
                           int64_t ldw, double *eig_host, int64_t *rank, void *workspace, size_t workspace_bytes,
-                          void *hip_stream)
+                          void *hip_stream, double *phase_seconds)
 {
     if (B < 0 || d < 0 || B > 46340 || d > (int64_t(1) << 24)) return LPD_ERR_SHAPE;
     if (!rank) return LPD_ERR_NULL;
@@ -486,13 +533,27 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
     double *T = reinterpret_cast<double *>(ws + cv.off_T);
     double *cs_d[2] = {reinterpret_cast<double *>(ws + cv.off_cs),
                        reinterpret_cast<double *>(ws + cv.off_cs + round_up(cv.cs_doubles * 8, kAlign))};
+    double *tab_d = reinterpret_cast<double *>(ws + cv.off_tab);
     int *ord_d = reinterpret_cast<int *>(ws + cv.off_ord);
     double *lam_d = reinterpret_cast<double *>(ws + cv.off_lam);
 
+    // Phase timing (phase_seconds given, or LPD_VERBOSE=1 for lines on stderr): the stream is drained at
+    // each phase boundary, which costs the overlap of the reflector accumulation with the host's QL start.
     const bool talk = verbose();
+    const auto t_start = std::chrono::steady_clock::now();
+    int phase = -1;
+    double t_phase = 0.0;
     auto say = [&](const char *what) {
-        if (talk) { std::fprintf(stderr, "[lpd_whiten B=%d] %s\n", n, what); std::fflush(stderr); }
+        if (!talk && !phase_seconds) return;
+        (void)hipStreamSynchronize(s);
+        const double sec = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count();
+        if (phase_seconds && phase >= 0 && phase < 5) phase_seconds[phase] = sec - t_phase;
+        ++phase;
+        t_phase = sec;
+        if (talk) { std::fprintf(stderr, "[lpd_whiten B=%d] +%.3f s: %s\n", n, sec, what); std::fflush(stderr); }
     };
+    if (phase_seconds)
+        for (int k = 0; k < 5; ++k) phase_seconds[k] = 0.0;
 
     // page-locked staging: rotation batches (two in flight), the tridiagonal matrix, order and eigenvalues
     double *cs_h[2] = {nullptr, nullptr};
@@ -546,6 +607,7 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
         LPD_HIP(hipEventRecord(tri_done, s));
     }
 
+    say("accumulation of the reflectors");
     // Q^T into Zt while the host starts on the tridiagonal matrix
     {
         hipLaunchKernelGGL(identity_kernel, dim3(2048), dim3(256), 0, s, Zt, n);
@@ -577,27 +639,32 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
             if (hip_fail || sw.empty()) return;
             const int b = int(nbatch & 1);
             ++nbatch;
-            RotBatch rb;
-            rb.imin = n;
-            rb.imax = 0;
-            for (int k = 0; k < KSW; ++k) { rb.lo[k] = 1; rb.hi[k] = 0; rb.off[k] = 0; }
+            long long *hdr = reinterpret_cast<long long *>(cs_h[b]);
+            int imin = n, imax = 0;
+            if (hipEventSynchronize(cs_free[b]) != hipSuccess) { hip_fail = 1; return; }   // staging free again
+            for (int k = 0; k < KSW; ++k) { hdr[k] = 1; hdr[KSW + k] = 0; hdr[2 * KSW + k] = 0; }
             for (size_t k = 0; k < sw.size() && k < size_t(KSW); ++k) {
-                rb.lo[k] = int(sw[k].lo);
-                rb.hi[k] = int(sw[k].hi);
-                rb.off[k] = (long long)sw[k].off;
-                rb.imin = std::min(rb.imin, rb.lo[k]);
-                rb.imax = std::max(rb.imax, rb.hi[k]);
+                hdr[k] = sw[k].lo;
+                hdr[KSW + k] = sw[k].hi;
+                hdr[2 * KSW + k] = (long long)sw[k].off;
+                imin = std::min(imin, int(sw[k].lo));
+                imax = std::max(imax, int(sw[k].hi));
             }
-            if (cs.size() > cv.cs_doubles || sw.size() > size_t(KSW) || rb.imax + 1 >= n || rb.imin < 0) {
+            if (ROT_HDR + cs.size() > cv.cs_doubles || sw.size() > size_t(KSW) || imax + 1 >= n || imin < 0 ||
+                imin > imax) {
                 hip_fail = 2;
                 return;
             }
-            // the staging buffer is free once the copy queued from it two batches ago has run
-            if (hipEventSynchronize(cs_free[b]) != hipSuccess) { hip_fail = 1; return; }
-            std::memcpy(cs_h[b], cs.data(), cs.size() * 8);
-            if (hipMemcpyAsync(cs_d[b], cs_h[b], cs.size() * 8, hipMemcpyHostToDevice, s) != hipSuccess ||
+            std::memcpy(cs_h[b] + ROT_HDR, cs.data(), cs.size() * 8);
+            if (hipMemcpyAsync(cs_d[b], cs_h[b], (ROT_HDR + cs.size()) * 8, hipMemcpyHostToDevice, s) != hipSuccess ||
                 hipEventRecord(cs_free[b], s) != hipSuccess) { hip_fail = 1; return; }
-            hipLaunchKernelGGL(rot_kernel, dim3((n + 63) / 64), dim3(64), 0, s, Zt, n, rb, cs_d[b]);
+            const int top = imax + 1;
+            const int nsteps = (top - imin) + 2 * KSW;              // t = 0 .. t_last
+            const int nchunks = (nsteps + CH - 1) / CH;
+            hipLaunchKernelGGL(rot_table_kernel, dim3((nchunks * CH * KSW + 255) / 256), dim3(256), 0, s,
+                               reinterpret_cast<const long long *>(cs_d[b]), cs_d[b] + ROT_HDR, top, nchunks * CH,
+                               tab_d);
+            hipLaunchKernelGGL(rot_kernel, dim3((n + 63) / 64), dim3(64), 0, s, Zt, n, imin, top, nchunks, tab_d);
             if (hipGetLastError() != hipSuccess) hip_fail = 1;
         };
         int last_decile = -1;
@@ -629,6 +696,7 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
         LPD_HIP(hipGetLastError());
     }
     *rank = r;
+    say("done");
 done:
     if (hipStreamSynchronize(s) != hipSuccess && status == LPD_OK) status = LPD_ERR_HIP;
     for (int b = 0; b < 2; ++b) {

@@ -52,7 +52,7 @@ SIGNATURES = {
                                        ctypes.POINTER(_i64)]),
     "lpd_whiten_workspace": (ctypes.c_int, [_i64, ctypes.POINTER(_sz)]),
     "lpd_whiten": (ctypes.c_int, [_vp, _i64, _i64, _i64, ctypes.c_double, ctypes.c_double, _vp, _i64, _vp,
-                                  ctypes.POINTER(_i64), _vp, _sz, _vp]),
+                                  ctypes.POINTER(_i64), _vp, _sz, _vp, ctypes.POINTER(ctypes.c_double)]),
     "lpd_nystrom_factor_workspace": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
     "lpd_nystrom_factor": (ctypes.c_int, _FACTOR_ARGS),
     "lpd_nystrom_factor_profiled": (ctypes.c_int, _FACTOR_ARGS + [ctypes.POINTER(FactorProfile)]),
@@ -155,9 +155,13 @@ def lpd_whiten_workspace(B: int) -> int:
     return int(nb.value)
 
 
-def lpd_whiten(L: torch.Tensor, gamma: float, clip_ratio: float = 1e-10, workspace=None):
+WHITEN_PHASES = ("kernel_matrix", "tridiagonalisation", "accumulation", "ql_rotations", "scaling")
+
+
+def lpd_whiten(L: torch.Tensor, gamma: float, clip_ratio: float = 1e-10, workspace=None, phases: dict | None = None):
     """Steps 1a-1c with the cubic work on the device. L: B x d float32 device tensor.
-    Returns (W B x B float32 on L's device, eig float64 CPU tensor, rank). Blocks until W is complete."""
+    Returns (W B x B float32 on L's device, eig float64 CPU tensor, rank). Blocks until W is complete.
+    `phases`, if given, receives the wall seconds of each phase (this drains the stream between phases)."""
     L = _dev_f32(L, "L", 2)
     B, d = L.shape
     W = torch.empty((B, B), dtype=torch.float32, device=L.device)
@@ -168,10 +172,13 @@ def lpd_whiten(L: torch.Tensor, gamma: float, clip_ratio: float = 1e-10, workspa
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=L.device)
     if workspace.dtype != torch.uint8 or not workspace.is_cuda:
         raise TypeError("workspace: expected a uint8 device tensor")
+    ph = (ctypes.c_double * 5)() if phases is not None else None
     st = lib().lpd_whiten(L.data_ptr(), B, d, _ld(L), float(gamma), float(clip_ratio), W.data_ptr(), max(B, 1),
                           eig.data_ptr(), ctypes.byref(rank), workspace.data_ptr(), workspace.numel(),
-                          _stream(L.device))
+                          _stream(L.device), ph)
     _check(st, "lpd_whiten")
+    if phases is not None:
+        phases.update(zip(WHITEN_PHASES, ph))
     return W, eig, int(rank.value)
 
 

@@ -225,12 +225,12 @@ def test_whiten_device_query_and_argument_errors(L):
     buf = (ctypes.c_float * 64)()
     p = ctypes.cast(buf, ctypes.c_void_p)
     f = L.lpd_whiten
-    #        L  B  d  ldl gamma clip  W  ldw eig   rank             ws    bytes stream
-    assert f(p, 0, 2, 2, 0.5, 1e-10, p, 1, None, ctypes.byref(r), None, 0, None) == 0 and r.value == 0
-    assert f(p, 4, 2, 1, 0.5, 1e-10, p, 4, None, ctypes.byref(r), None, 0, None) == -3
-    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 3, None, ctypes.byref(r), None, 0, None) == -3
-    assert f(p, 4, 2, 2, 0.5, 1e-10, None, 4, None, ctypes.byref(r), None, 0, None) == -1
-    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 4, None, None, None, 0, None) == -1
-    assert f(p, -4, 2, 2, 0.5, 1e-10, p, 4, None, ctypes.byref(r), None, 0, None) == -2
-    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 4, None, ctypes.byref(r), None, 0, None) == -4   # no workspace
-    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 4, None, ctypes.byref(r), p, 256, None) == -4    # too small
+    #        L  B  d  ldl gamma clip  W  ldw eig   rank             ws    bytes stream phases
+    assert f(p, 0, 2, 2, 0.5, 1e-10, p, 1, None, ctypes.byref(r), None, 0, None, None) == 0 and r.value == 0
+    assert f(p, 4, 2, 1, 0.5, 1e-10, p, 4, None, ctypes.byref(r), None, 0, None, None) == -3
+    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 3, None, ctypes.byref(r), None, 0, None, None) == -3
+    assert f(p, 4, 2, 2, 0.5, 1e-10, None, 4, None, ctypes.byref(r), None, 0, None, None) == -1
+    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 4, None, None, None, 0, None, None) == -1
+    assert f(p, -4, 2, 2, 0.5, 1e-10, p, 4, None, ctypes.byref(r), None, 0, None, None) == -2
+    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 4, None, ctypes.byref(r), None, 0, None, None) == -4   # no workspace
+    assert f(p, 4, 2, 2, 0.5, 1e-10, p, 4, None, ctypes.byref(r), p, 256, None, None) == -4    # too small

@@ -349,68 +349,89 @@ __global__ __launch_bounds__(256) void rot_table_kernel(const long long *__restr
     tab[2 * idx + 1] = sn;
 }
 
-// One pass of up to KSW sweeps over rows imin..top of Zt.  A wavefront owns 64 columns; stage s of the
-// register pipeline receives row rho = top - t + 2 s at time t, mixes it with the row rho + 1 it holds,
-// and passes that one on.  Rows and coefficients of the next chunk of CH steps are fetched while the
-// current chunk is computed; the coefficients go through LDS so that every lane reads them by broadcast.
-__global__ __launch_bounds__(64) void rot_kernel(double *__restrict__ Zt, int n, int imin, int top, int nchunks,
-                                                 const double *__restrict__ tab)
+// One pass of up to KSW sweeps over rows imin..top of Zt.  A workgroup owns 64 columns (one per lane);
+// the KSW stages of the pipeline are split over its RW wavefronts, SPW consecutive stages each.  Stage s
+// receives row rho = top - t + 2 s at time t, mixes it with the row rho + 1 it holds, and passes that one
+// on.  Wave w runs one time step behind wave w - 1 and takes its rows from it through LDS, a chunk of CH
+// steps per barrier; wave 0 reads rows from memory, the last wave writes them back.  Rows and
+// coefficients of the next chunk are fetched while the current one is computed.
+constexpr int RW = 4;
+constexpr int SPW = KSW / RW;
+
+__global__ __launch_bounds__(64 * RW) void rot_kernel(double *__restrict__ Zt, int n, int imin, int top, int nchunks,
+                                                      const double *__restrict__ tab)
 {
-    __shared__ double coef[2][CH * KSW * 2];
-    const int lane = threadIdx.x;
+    __shared__ double xfer[RW - 1][2][CH][64];
+    __shared__ double coef[RW][2][CH * SPW * 2];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int q = blockIdx.x * 64 + lane;
     const bool live = q < n;
     const int qq = live ? q : n - 1;
-    double up[KSW], pipe[KSW], cur[CH], nxt[CH], cf[4];
+    double up[SPW], pipe[SPW], cur[CH], nxt[CH];
 #pragma unroll
-    for (int s = 0; s < KSW; ++s) { up[s] = 0.0; pipe[s] = 0.0; }
+    for (int s = 0; s < SPW; ++s) { up[s] = 0.0; pipe[s] = 0.0; }
+    // coefficients of this wave for chunk c: table rows c*CH + w + u (u < CH), its SPW stages' pairs
+    const double *ctab = tab + int64_t(w + (lane >> 3)) * (KSW * 2) + w * (SPW * 2) + (lane & 7);
 #pragma unroll
     for (int u = 0; u < CH; ++u) {
         const int rho = top - u;
-        cur[u] = rho >= imin ? Zt[int64_t(rho) * n + qq] : 0.0;
+        cur[u] = (w == 0 && rho >= imin) ? Zt[int64_t(rho) * n + qq] : 0.0;
         nxt[u] = 0.0;
     }
-#pragma unroll
-    for (int k = 0; k < 4; ++k) coef[0][lane * 4 + k] = tab[lane * 4 + k];
+    coef[w][0][lane] = ctab[0];
     __syncthreads();
-    for (int ch = 0; ch < nchunks; ++ch) {
-        const bool more = ch + 1 < nchunks;
-        if (more) {
+    const int nticks = nchunks + RW - 1;
+    for (int tick = 0; tick < nticks; ++tick) {
+        const int ch = tick - w;                       // this wave's chunk in this tick
+        if (ch >= 0 && ch < nchunks) {
+            const bool more = ch + 1 < nchunks;
+            double cfn = 0.0;
+            if (more) {
+                cfn = ctab[int64_t(ch + 1) * (CH * KSW * 2)];
+                if (w == 0) {
+#pragma unroll
+                    for (int u = 0; u < CH; ++u) {
+                        const int rho = top - ((ch + 1) * CH + u);
+                        nxt[u] = rho >= imin ? Zt[int64_t(rho) * n + qq] : 0.0;
+                    }
+                }
+            }
+            if (w > 0) {
+#pragma unroll
+                for (int u = 0; u < CH; ++u) cur[u] = xfer[w - 1][ch & 1][u][lane];
+            }
+            const double *cb = coef[w][ch & 1];
 #pragma unroll
             for (int u = 0; u < CH; ++u) {
-                const int rho = top - ((ch + 1) * CH + u);
-                nxt[u] = rho >= imin ? Zt[int64_t(rho) * n + qq] : 0.0;
+#pragma unroll
+                for (int s = SPW - 1; s >= 0; --s) {
+                    const double c = cb[(u * SPW + s) * 2], sn = cb[(u * SPW + s) * 2 + 1];
+                    const double in = s == 0 ? cur[u] : pipe[s];
+                    const double f = up[s];
+                    const double out = sn * in + c * f;        // row rho + 1, done with this sweep
+                    up[s] = c * in - sn * f;                   // row rho, kept for the next step
+                    if (s == SPW - 1) {
+                        if (w == RW - 1) {
+                            const int t = ch * CH + u + w;     // time of this step in the whole pipeline
+                            const int ro = top - t + 2 * (KSW - 1) + 1;
+                            if (live && ro >= imin && ro <= top) Zt[int64_t(ro) * n + q] = out;
+                        } else {
+                            xfer[w][ch & 1][u][lane] = out;
+                        }
+                    } else {
+                        pipe[s + 1] = out;
+                    }
+                }
             }
-            const double *src = tab + int64_t(ch + 1) * (CH * KSW * 2) + lane * 4;
+            if (more) {
+                coef[w][(ch + 1) & 1][lane] = cfn;
+                if (w == 0) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) cf[k] = src[k];
-        }
-        const double *cb = coef[ch & 1];
-#pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const int t = ch * CH + u;
-#pragma unroll
-            for (int s = KSW - 1; s >= 0; --s) {
-                const double c = cb[(u * KSW + s) * 2], sn = cb[(u * KSW + s) * 2 + 1];
-                const double in = s == 0 ? cur[u] : pipe[s];
-                const double f = up[s];
-                const double out = sn * in + c * f;        // row rho + 1, done with sweep s
-                up[s] = c * in - sn * f;                   // row rho, kept for the next step
-                if (s == KSW - 1) {
-                    const int ro = top - t + 2 * (KSW - 1) + 1;
-                    if (live && ro >= imin && ro <= top) Zt[int64_t(ro) * n + q] = out;
-                } else {
-                    pipe[s + 1] = out;
+                    for (int u = 0; u < CH; ++u) cur[u] = nxt[u];
                 }
             }
         }
-        if (more) {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) coef[(ch + 1) & 1][lane * 4 + k] = cf[k];
-        }
         __syncthreads();
-#pragma unroll
-        for (int u = 0; u < CH; ++u) cur[u] = nxt[u];
     }
 }
 
@@ -661,10 +682,11 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
             const int top = imax + 1;
             const int nsteps = (top - imin) + 2 * KSW;              // t = 0 .. t_last
             const int nchunks = (nsteps + CH - 1) / CH;
-            hipLaunchKernelGGL(rot_table_kernel, dim3((nchunks * CH * KSW + 255) / 256), dim3(256), 0, s,
-                               reinterpret_cast<const long long *>(cs_d[b]), cs_d[b] + ROT_HDR, top, nchunks * CH,
+            const int tab_steps = (nchunks + 1) * CH;               // the later waves read RW - 1 steps further
+            hipLaunchKernelGGL(rot_table_kernel, dim3((tab_steps * KSW + 255) / 256), dim3(256), 0, s,
+                               reinterpret_cast<const long long *>(cs_d[b]), cs_d[b] + ROT_HDR, top, tab_steps, tab_d);
+            hipLaunchKernelGGL(rot_kernel, dim3((n + 63) / 64), dim3(64 * RW), 0, s, Zt, n, imin, top, nchunks,
                                tab_d);
-            hipLaunchKernelGGL(rot_kernel, dim3((n + 63) / 64), dim3(64), 0, s, Zt, n, imin, top, nchunks, tab_d);
             if (hipGetLastError() != hipSuccess) hip_fail = 1;
         };
         int last_decile = -1;

@@ -324,7 +324,9 @@ bool tridiag_ql(double *dg, double *e, int64_t n, int batch, const ApplyRotation
             for (; i >= l; --i) {
                 const double f = s * e[i];
                 const double b = c * e[i];
-                r = std::hypot(f, g);
+                // sqrt of the plain sum of squares unless it could overflow or lose bits to underflow
+                const double rr = f * f + g * g;
+                r = (rr > 1e-280 && rr < 1e280) ? std::sqrt(rr) : std::hypot(f, g);
                 e[i + 1] = r;
                 if (r == 0.0) {
                     dg[i + 1] -= p;

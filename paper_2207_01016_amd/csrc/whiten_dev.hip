@@ -163,6 +163,55 @@ __global__ __launch_bounds__(256) void trail_kernel(double *__restrict__ A, int 
     }
 }
 
+// The same pass for even n, where every row starts on a 16-byte boundary: two rows per wavefront share
+// the loads of the three vectors, and every lane moves 16 bytes per access.  The pass starts at the even
+// column at or below j+1; an element left of j+1 is carried through unchanged and adds nothing to y.
+typedef double d2 __attribute__((ext_vector_type(2)));
+
+__global__ __launch_bounds__(256) void trail2_kernel(double *__restrict__ A, int n, int j, int pending,
+                                                     const double *__restrict__ vp, const double *__restrict__ wp,
+                                                     const double *__restrict__ vc, double *__restrict__ y)
+{
+    const int lane = threadIdx.x & 63;
+    const int c0 = j + 1;
+    const int cal = c0 & ~1;
+    const int npair = (n - c0 + 1) / 2;        // row pairs of the trailing matrix, the last one may be half
+    for (int pr = blockIdx.x * 4 + (threadIdx.x >> 6); pr < npair; pr += gridDim.x * 4) {
+        const int a0 = c0 + 2 * pr;
+        const bool two = a0 + 1 < n;
+        const int a1 = two ? a0 + 1 : a0;
+        double *r0 = A + int64_t(a0) * n, *r1 = A + int64_t(a1) * n;
+        const double va0 = pending ? vp[a0] : 0.0, wa0 = pending ? wp[a0] : 0.0;
+        const double va1 = pending ? vp[a1] : 0.0, wa1 = pending ? wp[a1] : 0.0;
+        double acc0 = 0.0, acc1 = 0.0;
+        for (int c = cal + 2 * lane; c < n; c += 128) {
+            d2 x0 = *reinterpret_cast<const d2 *>(r0 + c);
+            d2 x1 = *reinterpret_cast<const d2 *>(r1 + c);
+            d2 v = *reinterpret_cast<const d2 *>(vc + c);
+            if (pending) {
+                const d2 pv = *reinterpret_cast<const d2 *>(vp + c);
+                const d2 pw = *reinterpret_cast<const d2 *>(wp + c);
+                d2 u0 = x0 - (va0 * pw + wa0 * pv);
+                d2 u1 = x1 - (va1 * pw + wa1 * pv);
+                if (c < c0) { u0.x = x0.x; u1.x = x1.x; }
+                x0 = u0;
+                x1 = u1;
+                *reinterpret_cast<d2 *>(r0 + c) = x0;
+                if (two) *reinterpret_cast<d2 *>(r1 + c) = x1;
+            }
+            if (c < c0) v.x = 0.0;
+            acc0 += x0.x * v.x + x0.y * v.y;
+            acc1 += x1.x * v.x + x1.y * v.y;
+        }
+        acc0 = wave_sum(acc0);
+        acc1 = wave_sum(acc1);
+        if (lane == 0) {
+            y[a0] = acc0;
+            if (two) y[a1] = acc1;
+        }
+    }
+}
+
 // Step j, part 3 (one workgroup): w_j = tau_j y - (tau_j^2 / 2)(y . v_j) v_j over columns j+1..
 __global__ __launch_bounds__(1024) void w_kernel(int n, int j, const double *__restrict__ tau,
                                                  const double *__restrict__ vc, const double *__restrict__ y,
@@ -608,8 +657,13 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
             const double *vp = vbuf[(j & 1) ^ 1], *wp = wbuf[(j & 1) ^ 1];
             hipLaunchKernelGGL(hh_kernel, dim3(1), dim3(1024), 0, s, A, n, j, pending, vp, wp, vc, dg_d, e_d, tau_d);
             const int rows = n - j - 1;
-            const int grid = std::min(2048, (rows + 3) / 4);
-            hipLaunchKernelGGL(trail_kernel, dim3(grid), dim3(256), 0, s, A, n, j, pending, vp, wp, vc, y);
+            if (n % 2 == 0) {
+                const int grid = std::min(2048, ((rows + 1) / 2 + 3) / 4);
+                hipLaunchKernelGGL(trail2_kernel, dim3(grid), dim3(256), 0, s, A, n, j, pending, vp, wp, vc, y);
+            } else {
+                const int grid = std::min(2048, (rows + 3) / 4);
+                hipLaunchKernelGGL(trail_kernel, dim3(grid), dim3(256), 0, s, A, n, j, pending, vp, wp, vc, y);
+            }
             hipLaunchKernelGGL(w_kernel, dim3(1), dim3(1024), 0, s, n, j, tau_d, vc, y, wc);
             pending = 1;
             if ((j & 1023) == 1023) LPD_HIP(hipGetLastError());

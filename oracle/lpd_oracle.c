@@ -62,6 +62,38 @@ void orc_kernel_block(const float *X, int64_t n, int64_t d, int64_t ldx,
             Z[i * B + b] = gauss_kernel(X + i * ldx, L + b * ldl, d, gamma);
 }
 
+/* The kernel block for sparse inputs (Section 4, "we implemented all kernel
+ * operations based on efficient sparse matrix products"): row i of X is given
+ * in compressed-row form, entries row_ptr[i] .. row_ptr[i+1]-1 of (col_idx,
+ * values), every other coordinate zero; column indices of a row are distinct,
+ * in any order.  The kernel value is that of the vector so described:
+ * the row is written out in full and the definition applied. */
+void orc_kernel_block_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values,
+                          int64_t n, int64_t d,
+                          const float *L, int64_t B, int64_t ldl,
+                          double gamma, double *Z)
+{
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)(d > 0 ? d : 1) * sizeof(double));
+#pragma omp for schedule(static)
+        for (int64_t i = 0; i < n; ++i) {
+            for (int64_t k = 0; k < d; ++k) x[k] = 0.0;
+            for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) x[col_idx[e]] = (double)values[e];
+            for (int64_t b = 0; b < B; ++b) {
+                const float *l = L + b * ldl;
+                double s = 0.0;
+                for (int64_t k = 0; k < d; ++k) {
+                    const double df = x[k] - (double)l[k];
+                    s += df * df;
+                }
+                Z[i * B + b] = exp(-gamma * s);
+            }
+        }
+        free(x);
+    }
+}
+
 /* Figure 1, step 1b: K = U D U^T by the cyclic two-sided Jacobi method.
  * A (B x B, symmetric, overwritten), V receives eigenvectors as COLUMNS,
  * ev the eigenvalues (unsorted).  Returns the number of sweeps, or -1 if the

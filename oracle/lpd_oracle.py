@@ -48,6 +48,9 @@ def _load():
         lib = ctypes.CDLL(build())
         lib.orc_kernel_block.argtypes = [_f32p, _i64, _i64, _i64, _f32p, _i64, _i64, ctypes.c_double, _f64p]
         lib.orc_kernel_block.restype = None
+        lib.orc_kernel_block_csr.argtypes = [ctypes.c_void_p, ctypes.c_void_p, _f32p, _i64, _i64, _f32p, _i64, _i64,
+                                             ctypes.c_double, _f64p]
+        lib.orc_kernel_block_csr.restype = None
         lib.orc_jacobi_eigh.argtypes = [_f64p, _i64, _f64p, _f64p]
         lib.orc_jacobi_eigh.restype = ctypes.c_int
         lib.orc_whiten_from_eig.argtypes = [_f64p, _f64p, _i64, ctypes.c_double, _f64p, _f64p]
@@ -106,6 +109,25 @@ def kernel_block(X, L, gamma: float) -> np.ndarray:
     assert d == d2
     Z = np.empty((n, B), dtype=np.float64)
     _load().orc_kernel_block(_p32(X), n, d, d, _p32(L), B, d, float(gamma), _p64(Z))
+    return Z
+
+
+def kernel_block_csr(row_ptr, col_idx, values, d: int, L, gamma: float) -> np.ndarray:
+    """Z[i,b] = exp(-gamma ||x_i - l_b||^2) with the rows x_i given in compressed-row form (Section 4, sparse
+    kernel operations): distinct column indices per row, any order, absent coordinates zero."""
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    values = _f32(values)
+    L = _f32(L)
+    n = row_ptr.shape[0] - 1
+    B, d2 = L.shape
+    assert d == d2 and row_ptr[0] == 0 and row_ptr[-1] == col_idx.shape[0] == values.shape[0]
+    assert np.all(np.diff(row_ptr) >= 0)
+    if col_idx.size:
+        assert col_idx.min() >= 0 and col_idx.max() < d
+    Z = np.empty((n, B), dtype=np.float64)
+    _load().orc_kernel_block_csr(row_ptr.ctypes.data_as(ctypes.c_void_p), col_idx.ctypes.data_as(ctypes.c_void_p),
+                                 _p32(values), n, d, _p32(L), B, d, float(gamma), _p64(Z))
     return Z
 
 

@@ -306,3 +306,58 @@ def test_predict_is_the_kernel_expansion_when_all_points_are_landmarks(oracle):
             dist = sum((float(Xt[t, k]) - float(X[i, k])) ** 2 for k in range(d))
             ref += coef[i] * math.exp(-gamma * dist)
         assert abs(F[t, 0] - ref) <= 1e-4 * max(1.0, abs(ref))   # W and w were rounded to fp32
+
+
+# ---------------------------------------------------------------- Section 4, kernel block of sparse rows
+
+def _random_csr(seed, n, d, density, sort=True):
+    """Rows as dicts {column: value}, and the same rows in compressed-row form."""
+    g = _rng(seed)
+    rows, row_ptr, cols, vals = [], [0], [], []
+    for i in range(n):
+        k = int(g.binomial(d, density)) if i % 5 else 0          # every fifth row is empty
+        c = g.choice(d, size=k, replace=False)
+        if sort:
+            c = np.sort(c)
+        v = g.standard_normal(k).astype(np.float32)
+        rows.append({int(a): float(b) for a, b in zip(c, v)})
+        cols.extend(int(a) for a in c)
+        vals.extend(float(b) for b in v)
+        row_ptr.append(len(cols))
+    return rows, np.array(row_ptr, dtype=np.int64), np.array(cols, dtype=np.int32), np.array(vals, dtype=np.float32)
+
+
+def test_csr_kernel_block_against_sparse_inner_products(oracle):
+    """Independent formula: ||x - l||^2 = sum_nz x_k^2 + ||l||^2 - 2 sum_nz x_k l_k, from the dict rows.
+    A dropped entry, an index shifted by one, or a value attached to the wrong row would show here."""
+    d, B, gamma = 23, 9, 0.07
+    rows, rp, ci, va = _random_csr(3, 31, d, 0.3)
+    L = _points(4, B, d)
+    Z = oracle.kernel_block_csr(rp, ci, va, d, L, gamma)
+    for i, row in enumerate(rows):
+        for b in range(B):
+            l = L[b].astype(np.float64)
+            sq = sum(v * v for v in row.values()) + float(l @ l) - 2.0 * sum(v * l[k] for k, v in row.items())
+            assert abs(Z[i, b] - math.exp(-gamma * sq)) <= 1e-12
+
+
+def test_csr_kernel_block_equals_dense_on_the_written_out_matrix(oracle):
+    d, B, gamma = 40, 17, 0.02
+    for sort in (True, False):                         # column order within a row does not matter
+        rows, rp, ci, va = _random_csr(5, 50, d, 0.15, sort=sort)
+        X = np.zeros((50, d), dtype=np.float32)
+        for i, row in enumerate(rows):
+            for k, v in row.items():
+                X[i, k] = v
+        L = _points(6, B, d)
+        assert np.array_equal(oracle.kernel_block_csr(rp, ci, va, d, L, gamma), oracle.kernel_block(X, L, gamma))
+    # an all-empty matrix gives exp(-gamma ||l||^2) in every row
+    Z = oracle.kernel_block_csr(np.zeros(4, dtype=np.int64), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.float32),
+                                d, L, gamma)
+    assert np.allclose(Z, np.exp(-gamma * (L.astype(np.float64) ** 2).sum(axis=1))[None, :], rtol=1e-14)
+    # stored zeros are harmless
+    rp2 = np.array([0, 2], dtype=np.int64)
+    Z0 = oracle.kernel_block_csr(rp2, np.array([3, 7], dtype=np.int32), np.array([0.0, 1.5], dtype=np.float32), d, L, gamma)
+    Z1 = oracle.kernel_block_csr(np.array([0, 1], dtype=np.int64), np.array([7], dtype=np.int32),
+                                 np.array([1.5], dtype=np.float32), d, L, gamma)
+    assert np.array_equal(Z0, Z1)

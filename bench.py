@@ -45,10 +45,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", default="auto", choices=["auto", "128x128", "256x128", "256x256"])
     ap.add_argument("--workspace-mult", type=float, default=1.0)
-    ap.add_argument("--path", default="factor", choices=["factor", "solver", "predict", "stream", "whiten"],
+    ap.add_argument("--path", default="factor", choices=["factor", "solver", "predict", "stream", "whiten", "sparse"],
                     help="factor: Nystrom factor + margin sweep (default); solver: batched dual coordinate ascent "
                          "on G; predict: scores of new points; stream: the factor copied to pinned host memory as it is made; whiten: the one-off preparation "
-                         "(steps 1a-1c) on the device")
+                         "(steps 1a-1c) on the device; sparse: the factor from X in compressed-row form")
     ap.add_argument("--classifiers", type=int, default=10, help="predict: number of classifiers scored at once")
     ap.add_argument("--whiten", default="device", choices=["device", "host"],
                     help="steps 1a-1c (one-off preparation, outside the timed region): lpd_whiten on the GPU, or the "
@@ -378,6 +378,92 @@ def bench_whiten(args):
     print(json.dumps(out))
 
 
+def bench_sparse(args):
+    """Step 1d with X in compressed-row form (default: the 80 %-zeros 'digit' recipe)."""
+    import torch
+    from paper_2207_01016_amd import lpd, workloads
+    dev = torch.device("cuda:0")
+    wl = workloads.WORKLOADS[args.workload]
+    X = workloads.make_X(wl, dev)
+    idx = workloads.landmark_indices(wl)
+    L = X[idx.to(dev)].contiguous()
+    t0 = time.perf_counter()
+    if args.random_w:
+        W_host = torch.randn((wl.B, wl.B), generator=torch.Generator().manual_seed(1)) / wl.B ** 0.5
+        rank = wl.B
+    else:
+        W_host, rank = whiten(args, lpd, L, wl.gamma)
+    t_whiten = time.perf_counter() - t0
+    W = W_host.to(dev)
+    rp, ci, va = workloads.to_csr(X)
+    nnz = int(ci.numel())
+    G = torch.empty((wl.n, wl.B), dtype=torch.float32, device=dev)
+    # the dense factor on the same rows, for comparison
+    ws_d = lpd.alloc_workspace(wl.n, wl.d, wl.B, dev)
+    lpd.lpd_nystrom_factor(X, L, wl.gamma, W, G, ws_d, r=rank)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    lpd.lpd_nystrom_factor(X, L, wl.gamma, W, G, ws_d, r=rank)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_dense = e0.elapsed_time(e1)
+    del X, ws_d
+    chunk_rows, nbytes = lpd.lpd_nystrom_factor_csr_workspace(wl.n, wl.d, wl.B, args.chunk_rows)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    evs = []
+    for i in range(args.warmup + args.steps):
+        if i == args.warmup:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        lpd.lpd_nystrom_factor_csr(rp, ci, va, wl.d, L, wl.gamma, W, G, chunk_rows, ws, r=rank)
+        b.record()
+        if i >= args.warmup:
+            evs.append((a, b))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
+    flop = 2.0 * wl.n * wl.B * (wl.d + rank)
+    tflops = flop / (ms * 1e-3) / 1e12
+    out = {
+        "metric": "nystrom_factor_rows_per_s_from_csr", "value": wl.n * args.steps / elapsed, "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic" + (" (random W: tuning run)" if args.random_w else ""),
+        "config": {"workload": wl.name + " (X in compressed-row form)", "n": wl.n, "d": wl.d, "B": wl.B, "rank": rank,
+                   "gamma": wl.gamma, "nnz": nnz, "density": nnz / (wl.n * wl.d), "chunk_rows": chunk_rows,
+                   "x_bytes_csr": 12 * nnz + 8 * (wl.n + 1), "x_bytes_dense": 4 * wl.n * wl.d},
+        "ms_dense_factor_same_rows": ms_dense,
+        "whiten_s": None if args.random_w else t_whiten,
+        "roofline": {"kernel": "lpd_nystrom_factor_csr: rows written out per chunk, then the dense MFMA schedule; "
+                               "flops counted as for the dense product, 2 n B (d + r)",
+                     "bound": "mfma", "achieved": tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / FP32_MFMA_PEAK_TFLOPS, "flop_per_launch": flop, "avg_launch_ms": ms,
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import lpd_oracle as orc
+        m = 256
+        t0 = time.perf_counter()
+        r0, r1 = int(rp[0]), int(rp[m])
+        sub = (rp[: m + 1] - rp[0]).cpu().numpy(), ci[r0:r1].cpu().numpy(), va[r0:r1].cpu().numpy()
+        Zs = orc.kernel_block_csr(*sub, wl.d, L.cpu().numpy(), wl.gamma)
+        orc.apply_whitening(Zs, W_host.numpy(), rank)
+        per_row = (time.perf_counter() - t0) / m
+        m2 = int(max(m, min(16384, args.cpu_seconds / max(per_row, 1e-9))))
+        r1 = int(rp[m2])
+        sub = (rp[: m2 + 1] - rp[0]).cpu().numpy(), ci[:r1].cpu().numpy(), va[:r1].cpu().numpy()
+        t0 = time.perf_counter()
+        Zs = orc.kernel_block_csr(*sub, wl.d, L.cpu().numpy(), wl.gamma)
+        orc.apply_whitening(Zs, W_host.numpy(), rank)
+        t_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": m2 / t_cpu, "unit": "rows/s", "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"first {m2} of {wl.n} rows, all {wl.B} landmarks, double precision, "
+                                         f"{t_cpu:.1f} s", "gpu_over_cpu": out["value"] / (m2 / t_cpu)}
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -403,6 +489,11 @@ def main():
         return
     if args.path == "whiten":
         bench_whiten(args)
+        return
+    if args.path == "sparse":
+        if args.workload == "cnn":
+            args.workload = "digit"            # the recipe with 80 % zeros
+        bench_sparse(args)
         return
     dev = torch.device("cuda:0")
     wl = workloads.WORKLOADS[args.workload]

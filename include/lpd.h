@@ -212,6 +212,41 @@ int lpd_nystrom_factor_to_host(const float *X, int64_t n, int64_t d, int64_t ldx
                                void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Step 1d and the kernel block for SPARSE inputs (Section 4: the paper runs its
+ * kernel operations on sparse matrix products, since SVM data is often sparse).
+ * X is given in compressed-row form; L, W and the output are dense as above.
+ * Each chunk of rows is written out into a dense panel in the workspace and
+ * goes through the same MFMA kernels as the dense entry points, so a row's
+ * result equals that of the dense call on the written-out row.
+ *
+ *   row_ptr    device in  n+1 offsets (int64), row i owns entries
+ *                         row_ptr[i] .. row_ptr[i+1]-1; row_ptr[0] = 0
+ *   col_idx    device in  column of each entry (int32), distinct within a row,
+ *                         any order; an index outside [0, d) is ignored
+ *   values     device in  value of each entry (float)
+ *              col_idx and values may be NULL when there are no entries.
+ *   chunk_rows rows per dense panel, > 0 (the query suggests one: the factor's
+ *              own panel size); *chunk_rows <= 0 on input asks for it
+ *   workspace  device, 256-byte aligned, at least the query's size for this
+ *              chunk_rows: the dense panel and the dense call's scratch
+ * Stream-ordered like the dense calls.  Errors: as lpd_nystrom_factor.
+ */
+int lpd_nystrom_factor_csr_workspace(int64_t n, int64_t d, int64_t B,
+                                     int64_t *chunk_rows, size_t *bytes);
+int lpd_nystrom_factor_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values,
+                           int64_t n, int64_t d,
+                           const float *L, int64_t B, int64_t ldl,
+                           float gamma,
+                           const float *W, int64_t r, int64_t ldw,
+                           float *G, int64_t ldg, int64_t chunk_rows,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+int lpd_kernel_block_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values,
+                         int64_t n, int64_t d,
+                         const float *L, int64_t B, int64_t ldl,
+                         float gamma, float *Z, int64_t ldz, int64_t chunk_rows,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * The kernel block alone (Figure 1 steps 1a / 1d, Section 4 kernel):
  * Z[i,b] = exp(-gamma ||x_i - l_b||^2), written in full to device memory.
  * With X = L this is the landmark kernel matrix K_LL of step 1a.

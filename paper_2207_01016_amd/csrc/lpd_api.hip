@@ -316,6 +316,84 @@ done:
     return status;
 }
 
+// Workspace of the compressed-row entry points: one dense panel of chunk_rows rows of X (leading
+// dimension d rounded up to 4 floats), followed by the scratch of the dense call on that panel.
+struct CsrCarve { int64_t ldxd; size_t panel_bytes, bytes; };
+CsrCarve csr_carve(int64_t chunk_rows, int64_t d, int64_t B)
+{
+    CsrCarve c;
+    c.ldxd = std::max<int64_t>(4, (d + 3) / 4 * 4);
+    c.panel_bytes = round_up(size_t(chunk_rows) * size_t(c.ldxd) * 4, kAlign);
+    c.bytes = c.panel_bytes + carve(chunk_rows, B).rec_bytes;
+    return c;
+}
+
+int lpd_kernel_block_dense(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,
+                           float gamma, float *Z, int64_t ldz, void *workspace, size_t workspace_bytes, hipStream_t s)
+{
+    if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
+    if (n == 0 || B == 0) return LPD_OK;
+    if (!Z) return LPD_ERR_NULL;
+    if (ldz < B) return LPD_ERR_LD;
+    if (d > 0 && (!X || !L)) return LPD_ERR_NULL;
+    if (d > 0 && (ldx < d || ldl < d)) return LPD_ERR_LD;
+    const size_t off_nl = round_up(size_t(n) * 4, kAlign);
+    const size_t need = off_nl + round_up(size_t(B) * 4, kAlign);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < need)
+        return LPD_ERR_WORKSPACE;
+    float *nx = reinterpret_cast<float *>(workspace);
+    float *nl = reinterpret_cast<float *>(static_cast<char *>(workspace) + off_nl);
+    if (launch_sqnorm(X, n, d, ldx, nx, s) != hipSuccess) return LPD_ERR_HIP;
+    if (launch_sqnorm(L, B, d, ldl, nl, s) != hipSuccess) return LPD_ERR_HIP;
+    GemmArgs k1{};
+    k1.A = X; k1.lda = ldx;
+    k1.B = L; k1.ldb = ldl;
+    k1.C = Z; k1.ldc = ldz;
+    k1.M = int(n); k1.N = int(B); k1.K = int(d); k1.n_store = int(B);
+    k1.na = nx; k1.nb = nl;
+    k1.scale = -gamma * 1.44269504088896340736f;
+    return launch_gemm(k1, EPI_GAUSS, s) == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+}
+
+// Sparse rows go through the dense MFMA path: each chunk of rows is written out into a dense panel and
+// handed to the dense schedule.  With fp32 MFMA at 16 times the vector rate the written-out zeros cost less
+// than a gather-based product would down to a density of a few percent; what the compressed form saves is
+// the memory of X, not arithmetic.  factor: G = K(X, L) W^T; otherwise Z = K(X, L).
+int csr_impl(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d, const float *L,
+             int64_t B, int64_t ldl, float gamma, const float *W, int64_t r, int64_t ldw, float *out, int64_t ldo,
+             int64_t chunk_rows, void *workspace, size_t workspace_bytes, hipStream_t s, bool factor)
+{
+    if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
+    if (factor && (r < 0 || r > B)) return LPD_ERR_SHAPE;
+    if (n == 0 || B == 0) return LPD_OK;
+    if (chunk_rows <= 0 || chunk_rows > kMaxDim) return LPD_ERR_SHAPE;
+    if (!row_ptr || !out || (d > 0 && !L) || (factor && r > 0 && !W)) return LPD_ERR_NULL;
+    if (ldo < B || (d > 0 && ldl < d) || (factor && ldw < B)) return LPD_ERR_LD;
+    chunk_rows = std::min(chunk_rows, n);
+    const CsrCarve cc = csr_carve(chunk_rows, d, B);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < cc.bytes)
+        return LPD_ERR_WORKSPACE;
+    float *Xd = static_cast<float *>(workspace);
+    void *dws = static_cast<char *>(workspace) + cc.panel_bytes;
+    const size_t dws_bytes = workspace_bytes - cc.panel_bytes;
+    for (int64_t c0 = 0; c0 < n; c0 += chunk_rows) {
+        const int64_t rows = std::min(chunk_rows, n - c0);
+        const int64_t count4 = rows * cc.ldxd / 4;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(unsigned(std::min<int64_t>(4096, (count4 + 255) / 256))), dim3(256), 0,
+                           s, reinterpret_cast<rf32x4 *>(Xd), count4);
+        if (col_idx && values)
+            hipLaunchKernelGGL(csr_scatter_kernel, dim3(row_grid(rows, 4)), dim3(256), 0, s, row_ptr, col_idx, values,
+                               c0, rows, int(d), Xd, cc.ldxd);
+        if (hipGetLastError() != hipSuccess) return LPD_ERR_HIP;
+        const int st = factor
+            ? factor_impl(Xd, rows, d, cc.ldxd, L, B, ldl, gamma, W, r, ldw, out + c0 * ldo, ldo, B, dws, dws_bytes, s,
+                          nullptr)
+            : lpd_kernel_block_dense(Xd, rows, d, cc.ldxd, L, B, ldl, gamma, out + c0 * ldo, ldo, dws, dws_bytes, s);
+        if (st != LPD_OK) return st;
+    }
+    return LPD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -443,32 +521,38 @@ done:
     return status;
 }
 
+int lpd_nystrom_factor_csr_workspace(int64_t n, int64_t d, int64_t B, int64_t *chunk_rows, size_t *bytes)
+{
+    if (!chunk_rows || !bytes) return LPD_ERR_NULL;
+    if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
+    if (*chunk_rows <= 0) *chunk_rows = std::max<int64_t>(1, std::min<int64_t>(n, carve(n, B).rec_rows));
+    if (*chunk_rows > kMaxDim) return LPD_ERR_SHAPE;
+    *bytes = csr_carve(*chunk_rows, d, B).bytes;
+    return LPD_OK;
+}
+
+int lpd_nystrom_factor_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d,
+                           const float *L, int64_t B, int64_t ldl, float gamma, const float *W, int64_t r, int64_t ldw,
+                           float *G, int64_t ldg, int64_t chunk_rows, void *workspace, size_t workspace_bytes,
+                           void *hip_stream)
+{
+    return csr_impl(row_ptr, col_idx, values, n, d, L, B, ldl, gamma, W, r, ldw, G, ldg, chunk_rows, workspace,
+                    workspace_bytes, static_cast<hipStream_t>(hip_stream), true);
+}
+
+int lpd_kernel_block_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d,
+                         const float *L, int64_t B, int64_t ldl, float gamma, float *Z, int64_t ldz, int64_t chunk_rows,
+                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return csr_impl(row_ptr, col_idx, values, n, d, L, B, ldl, gamma, nullptr, 0, B, Z, ldz, chunk_rows, workspace,
+                    workspace_bytes, static_cast<hipStream_t>(hip_stream), false);
+}
+
 int lpd_kernel_block(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,
                      float gamma, float *Z, int64_t ldz, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
-    if (n == 0 || B == 0) return LPD_OK;
-    if (!Z) return LPD_ERR_NULL;
-    if (ldz < B) return LPD_ERR_LD;
-    if (d > 0 && (!X || !L)) return LPD_ERR_NULL;
-    if (d > 0 && (ldx < d || ldl < d)) return LPD_ERR_LD;
-    const size_t off_nl = round_up(size_t(n) * 4, kAlign);
-    const size_t need = off_nl + round_up(size_t(B) * 4, kAlign);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < need)
-        return LPD_ERR_WORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    float *nx = reinterpret_cast<float *>(workspace);
-    float *nl = reinterpret_cast<float *>(static_cast<char *>(workspace) + off_nl);
-    if (launch_sqnorm(X, n, d, ldx, nx, s) != hipSuccess) return LPD_ERR_HIP;
-    if (launch_sqnorm(L, B, d, ldl, nl, s) != hipSuccess) return LPD_ERR_HIP;
-    GemmArgs k1{};
-    k1.A = X; k1.lda = ldx;
-    k1.B = L; k1.ldb = ldl;
-    k1.C = Z; k1.ldc = ldz;
-    k1.M = int(n); k1.N = int(B); k1.K = int(d); k1.n_store = int(B);
-    k1.na = nx; k1.nb = nl;
-    k1.scale = -gamma * 1.44269504088896340736f;
-    return launch_gemm(k1, EPI_GAUSS, s) == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+    return lpd_kernel_block_dense(X, n, d, ldx, L, B, ldl, gamma, Z, ldz, workspace, workspace_bytes,
+                                  static_cast<hipStream_t>(hip_stream));
 }
 
 int lpd_margins(const float *G, int64_t n, int64_t r, int64_t ldg, const float *w, float *m, void *hip_stream)

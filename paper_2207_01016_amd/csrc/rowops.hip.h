@@ -196,4 +196,30 @@ __global__ __launch_bounds__(256) void fold_weights_kernel(const float *__restri
         if (j0 + q < c) V[int64_t(j0 + q) * ldv + b] = acc[q];
 }
 
+// Rows p0 .. p0+rows-1 of a matrix in compressed-row form written out into the dense panel Xd
+// (Section 4: kernel operations on sparse data).  The panel is cleared by fill_zero_kernel first; then one
+// wavefront per row scatters its entries.  An index outside [0, d) is skipped, so that no input can make
+// the kernel write outside the panel.
+__global__ __launch_bounds__(256) void fill_zero_kernel(rf32x4 *__restrict__ p, int64_t count4)
+{
+    const rf32x4 z = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < count4; i += int64_t(gridDim.x) * 256) p[i] = z;
+}
+
+__global__ __launch_bounds__(256) void csr_scatter_kernel(const int64_t *__restrict__ row_ptr,
+                                                          const int32_t *__restrict__ col_idx,
+                                                          const float *__restrict__ values, int64_t p0, int64_t rows,
+                                                          int d, float *__restrict__ Xd, int64_t ldxd)
+{
+    const int lane = threadIdx.x & 63;
+    for (int64_t t = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6); t < rows; t += int64_t(gridDim.x) * 4) {
+        const int64_t e0 = row_ptr[p0 + t], e1 = row_ptr[p0 + t + 1];
+        float *x = Xd + t * ldxd;
+        for (int64_t e = e0 + lane; e < e1; e += 64) {
+            const int32_t c = col_idx[e];
+            if (c >= 0 && c < d) x[c] = values[e];
+        }
+    }
+}
+
 }  // namespace lpd

@@ -60,6 +60,12 @@ SIGNATURES = {
                                                             ctypes.POINTER(_sz)]),
     "lpd_nystrom_factor_to_host": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64,
                                                   _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
+    "lpd_nystrom_factor_csr_workspace": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_i64),
+                                                        ctypes.POINTER(_sz)]),
+    "lpd_nystrom_factor_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64,
+                                              _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
+    "lpd_kernel_block_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64,
+                                            _i64, _vp, _sz, _vp]),
     "lpd_kernel_block": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _vp, _sz,
                                         _vp]),
     "lpd_margins": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp, _vp]),
@@ -267,6 +273,80 @@ def lpd_nystrom_factor_to_host(X, L, gamma: float, W, G_host=None, chunk_rows: i
                                             workspace.data_ptr(), workspace.numel(), _stream(X.device)),
            "lpd_nystrom_factor_to_host")
     return G_host
+
+
+def _csr_args(row_ptr, col_idx, values, d):
+    if not (row_ptr.is_cuda and row_ptr.dtype == torch.int64 and row_ptr.dim() == 1 and row_ptr.numel() >= 1):
+        raise TypeError("row_ptr: expected a 1-D int64 device tensor with n + 1 entries")
+    if not (col_idx.is_cuda and col_idx.dtype == torch.int32 and col_idx.dim() == 1):
+        raise TypeError("col_idx: expected a 1-D int32 device tensor")
+    if not (values.is_cuda and values.dtype == torch.float32 and values.shape == col_idx.shape):
+        raise TypeError("values: expected a float32 device tensor shaped like col_idx")
+    row_ptr, col_idx, values = row_ptr.contiguous(), col_idx.contiguous(), values.contiguous()
+    n = row_ptr.numel() - 1
+    # the structure is checked here, on the device, so that the kernels never see offsets outside the arrays
+    if int(row_ptr[0]) != 0 or int(row_ptr[-1]) != col_idx.numel() or (n and bool((row_ptr[1:] < row_ptr[:-1]).any())):
+        raise ValueError("row_ptr: expected non-decreasing offsets from 0 to the number of entries")
+    if col_idx.numel() and (int(col_idx.min()) < 0 or int(col_idx.max()) >= d):
+        raise ValueError("col_idx: column index outside [0, d)")
+    return row_ptr, col_idx, values, n
+
+
+def lpd_nystrom_factor_csr_workspace(n: int, d: int, B: int, chunk_rows: int = 0):
+    """(chunk_rows, bytes) of the compressed-row entry points (the suggested chunk for chunk_rows <= 0)."""
+    cr, nb = _i64(int(chunk_rows)), _sz(0)
+    _check(lib().lpd_nystrom_factor_csr_workspace(n, d, B, ctypes.byref(cr), ctypes.byref(nb)),
+           "lpd_nystrom_factor_csr_workspace")
+    return int(cr.value), int(nb.value)
+
+
+def lpd_nystrom_factor_csr(row_ptr, col_idx, values, d: int, L, gamma: float, W, G=None, chunk_rows: int = 0,
+                           workspace=None, r: int | None = None) -> torch.Tensor:
+    """Step 1d for X in compressed-row form (device tensors). Enqueued on torch's current stream."""
+    row_ptr, col_idx, values, n = _csr_args(row_ptr, col_idx, values, d)
+    L = _dev_f32(L, "L", 2)
+    W = _dev_f32(W, "W", 2)
+    B = L.shape[0]
+    if L.shape[1] != d or W.shape[1] != B:
+        raise ValueError("shape mismatch: L B x d, W r x B")
+    r = W.shape[0] if r is None else int(r)
+    if r > W.shape[0]:
+        raise ValueError("r exceeds the rows of W")
+    if G is None:
+        G = torch.empty((n, B), dtype=torch.float32, device=L.device)
+    G = _dev_f32(G, "G", 2)
+    if G.shape != (n, B):
+        raise ValueError("G: expected n x B")
+    chunk_rows, nbytes = lpd_nystrom_factor_csr_workspace(n, d, B, chunk_rows)
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=L.device)
+    _check(lib().lpd_nystrom_factor_csr(row_ptr.data_ptr(), col_idx.data_ptr(), values.data_ptr(), n, d, L.data_ptr(),
+                                        B, _ld(L), float(gamma), W.data_ptr(), r, _ld(W), G.data_ptr(), _ld(G),
+                                        chunk_rows, workspace.data_ptr(), workspace.numel(), _stream(L.device)),
+           "lpd_nystrom_factor_csr")
+    return G
+
+
+def lpd_kernel_block_csr(row_ptr, col_idx, values, d: int, L, gamma: float, Z=None, chunk_rows: int = 0,
+                         workspace=None) -> torch.Tensor:
+    """Z = K(X, L) for X in compressed-row form (device tensors)."""
+    row_ptr, col_idx, values, n = _csr_args(row_ptr, col_idx, values, d)
+    L = _dev_f32(L, "L", 2)
+    B = L.shape[0]
+    if L.shape[1] != d:
+        raise ValueError("shape mismatch: L B x d")
+    if Z is None:
+        Z = torch.empty((n, B), dtype=torch.float32, device=L.device)
+    Z = _dev_f32(Z, "Z", 2)
+    if Z.shape != (n, B):
+        raise ValueError("Z: expected n x B")
+    chunk_rows, nbytes = lpd_nystrom_factor_csr_workspace(n, d, B, chunk_rows)
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=L.device)
+    _check(lib().lpd_kernel_block_csr(row_ptr.data_ptr(), col_idx.data_ptr(), values.data_ptr(), n, d, L.data_ptr(), B,
+                                      _ld(L), float(gamma), Z.data_ptr(), _ld(Z), chunk_rows, workspace.data_ptr(),
+                                      workspace.numel(), _stream(L.device)), "lpd_kernel_block_csr")
+    return Z
 
 
 def lpd_kernel_block(X, L, gamma: float, Z, workspace) -> torch.Tensor:

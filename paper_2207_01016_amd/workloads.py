@@ -151,3 +151,16 @@ def make_labels(wl: Workload, X: torch.Tensor) -> torch.Tensor:
         v = torch.randn(16, generator=g, dtype=torch.float32).to(dev)
         y = torch.where(torch.tanh(X @ A) @ v >= 0, 1.0, -1.0)
     return y.to(torch.float32)
+
+
+def to_csr(X: torch.Tensor):
+    """The nonzeros of a dense matrix in compressed-row form: (row_ptr int64 [n+1], col_idx int32, values float32),
+    on X's device. A change of storage format only; the entries are X's."""
+    nz = X != 0
+    counts = nz.sum(dim=1, dtype=torch.int64)
+    row_ptr = torch.zeros(X.shape[0] + 1, dtype=torch.int64, device=X.device)
+    row_ptr[1:] = torch.cumsum(counts, dim=0)
+    idx = nz.nonzero(as_tuple=False)            # row-major order: rows ascending, columns ascending within a row
+    col_idx = idx[:, 1].to(torch.int32).contiguous()
+    values = X[nz].contiguous()
+    return row_ptr, col_idx, values

@@ -1,0 +1,113 @@
+"""Compressed-row inputs (`lpd_kernel_block_csr`, `lpd_nystrom_factor_csr`) against the oracle's sparse kernel
+block and against the dense entry points on the written-out matrix."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+TOL_G = 1e-4
+
+
+def relfro(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch.device("cuda:0")
+
+
+@pytest.fixture(scope="module")
+def lpd():
+    from paper_2207_01016_amd import lpd as mod
+    mod.lib()
+    return mod
+
+
+def _sparse_problem(n, d, B, density, seed, dev):
+    g = torch.Generator().manual_seed(seed)
+    X = torch.rand((n, d), generator=g) * (torch.rand((n, d), generator=g) < density)
+    X[::7] = 0.0                                   # empty rows
+    L = torch.rand((B, d), generator=g) * (torch.rand((B, d), generator=g) < density)
+    return X.to(dev), L.to(dev)
+
+
+@pytest.mark.parametrize("n,d,B,density,chunk", [
+    (700, 50, 130, 0.2, 0),        # one chunk, d % 4 != 0 (panel leading dimension padded)
+    (1500, 784, 260, 0.2, 256),    # digit-like rows, several chunks with a ragged last one
+    (300, 33, 40, 0.02, 64),       # very sparse, most rows nearly empty
+    (260, 16, 64, 1.0, 100),       # fully dense given as compressed rows
+])
+def test_kernel_block_csr_matches_oracle_and_dense(lpd, oracle, dev, n, d, B, density, chunk):
+    from paper_2207_01016_amd import workloads
+    X, L = _sparse_problem(n, d, B, density, 11, dev)
+    gamma = 1.0 / max(1.0, density * d)
+    rp, ci, va = workloads.to_csr(X)
+    Z = lpd.lpd_kernel_block_csr(rp, ci, va, d, L, gamma, chunk_rows=chunk)
+    torch.cuda.synchronize()
+    ref = oracle.kernel_block_csr(rp.cpu().numpy(), ci.cpu().numpy(), va.cpu().numpy(), d, L.cpu().numpy(), gamma)
+    assert relfro(Z.cpu().numpy(), ref) <= 1e-5
+    # same kernels on the written-out rows: equal to the dense entry point
+    Zd = torch.empty_like(Z)
+    lpd.lpd_kernel_block(X, L, gamma, Zd, lpd.alloc_workspace(n, d, B, dev))
+    torch.cuda.synchronize()
+    assert relfro(Z.cpu().numpy(), Zd.cpu().numpy()) <= 1e-6
+
+
+def test_factor_csr_digit_recipe(lpd, oracle, dev):
+    """The 80 %-zeros recipe, scaled down: factor from compressed rows against the oracle on sampled rows."""
+    from paper_2207_01016_amd import workloads
+    wl = workloads.WORKLOADS["digit"].with_shape(n=6000, B=512)
+    X = workloads.make_X(wl, dev)
+    assert float((X == 0).float().mean()) > 0.7
+    idx = workloads.landmark_indices(wl)
+    L = X[idx.to(dev)].contiguous()
+    W, eig, rank = lpd.lpd_whiten_host(L.cpu(), wl.gamma)
+    rp, ci, va = workloads.to_csr(X)
+    G = torch.full((wl.n, wl.B), float("nan"), device=dev)
+    lpd.lpd_nystrom_factor_csr(rp, ci, va, wl.d, L, wl.gamma, W.to(dev), G, chunk_rows=1024, r=rank)
+    torch.cuda.synchronize()
+    rows = workloads.sample_rows(wl, 300, include=idx[:32])
+    Zs = oracle.kernel_block_csr(*[t.cpu().numpy() for t in workloads.to_csr(X[rows.to(dev)])], wl.d,
+                                 L.cpu().numpy(), wl.gamma)
+    ref = oracle.apply_whitening(Zs, W.numpy(), rank)
+    Gs = G[rows.to(dev)].cpu().numpy()
+    assert np.all(np.isfinite(G.cpu().numpy()))
+    assert relfro(Gs[:, :rank], ref) <= TOL_G
+    # and the dense factor on the same rows
+    Gd = torch.empty_like(G)
+    lpd.lpd_nystrom_factor(X, L, wl.gamma, W.to(dev), Gd, lpd.alloc_workspace(wl.n, wl.d, wl.B, dev), r=rank)
+    torch.cuda.synchronize()
+    assert relfro(G.cpu().numpy(), Gd.cpu().numpy()) <= 1e-6
+
+
+def test_csr_edge_cases(lpd, oracle, dev):
+    L = torch.rand((8, 5), generator=torch.Generator().manual_seed(2)).to(dev)
+    # no entries at all: every row is the zero vector
+    rp = torch.zeros(4, dtype=torch.int64, device=dev)
+    ci = torch.zeros(0, dtype=torch.int32, device=dev)
+    va = torch.zeros(0, dtype=torch.float32, device=dev)
+    Z = lpd.lpd_kernel_block_csr(rp, ci, va, 5, L, 0.3)
+    torch.cuda.synchronize()
+    ref = torch.exp(-0.3 * (L.double() ** 2).sum(dim=1)).cpu().numpy()
+    assert np.allclose(Z.cpu().numpy(), np.tile(ref, (3, 1)), rtol=1e-5)
+    # no rows
+    Z = lpd.lpd_kernel_block_csr(torch.zeros(1, dtype=torch.int64, device=dev), ci, va, 5, L, 0.3)
+    assert Z.shape == (0, 8)
+    # unsorted columns within a row
+    rp = torch.tensor([0, 3], dtype=torch.int64, device=dev)
+    ci = torch.tensor([4, 0, 2], dtype=torch.int32, device=dev)
+    va = torch.tensor([1.0, 2.0, 3.0], device=dev)
+    Z = lpd.lpd_kernel_block_csr(rp, ci, va, 5, L, 0.3)
+    torch.cuda.synchronize()
+    ref = oracle.kernel_block(np.array([[2.0, 0, 3.0, 0, 1.0]], dtype=np.float32), L.cpu().numpy(), 0.3)
+    assert relfro(Z.cpu().numpy(), ref) <= 1e-5
+    # the binding refuses a broken structure before any kernel runs
+    with pytest.raises(ValueError):
+        lpd.lpd_kernel_block_csr(rp, torch.tensor([4, 0, 5], dtype=torch.int32, device=dev), va, 5, L, 0.3)
+    with pytest.raises(ValueError):
+        lpd.lpd_kernel_block_csr(torch.tensor([0, 2], dtype=torch.int64, device=dev), ci, va, 5, L, 0.3)

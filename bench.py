@@ -248,7 +248,7 @@ def bench_predict(args):
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
-    flop = 2.0 * n_test * wl.B * (wl.d + (c if c > 8 else 0))
+    flop = 2.0 * n_test * wl.B * (wl.d + (c if c > 32 else 0))
     tflops = flop / (ms * 1e-3) / 1e12
     out = {
         "metric": "prediction_rows_per_s", "value": n_test * len(evs) / elapsed, "unit": "rows/s", "n_gpus": 1,

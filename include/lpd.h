@@ -301,7 +301,7 @@ int lpd_margins_multi(const float *G, int64_t n, int64_t r, int64_t ldg,
  * lpd_predict:       F[i, j] = sum_b V[j, b] * exp(-gamma ||x_i - l_b||^2)     (n x c),  c <= B
  *   X device in n x d (ldx);  L device in B x d (ldl);  V device in c x B (ldv);  F device out n x c (ldf)
  *   workspace: as for lpd_nystrom_factor (lpd_nystrom_factor_workspace(n, d, B)); the kernel block is
- *   produced panel by panel and consumed at once, by one multi-vector sweep for c <= 8, by the MFMA
+ *   produced panel by panel and consumed at once, by multi-vector sweeps (8 classifiers each) for c <= 32, by the MFMA
  *   product otherwise.
  * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE (incl. c > B), LPD_ERR_LD, LPD_ERR_WORKSPACE, LPD_ERR_HIP.
  */

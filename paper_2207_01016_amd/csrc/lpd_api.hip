@@ -241,6 +241,8 @@ int check_factor_args(const float *X, int64_t n, int64_t d, int64_t ldx, const f
         if (e__ != hipSuccess) { status = LPD_ERR_HIP; goto done; } \
     } while (0)
 
+constexpr int64_t kSweepClassifiers = 32;   // up to here prediction consumes a panel by sweeps, above by MFMA
+
 // Shared schedule of the factor (out_cols = B: G = Z W^T with zero fill of columns r..B-1) and of
 // prediction (out_cols = r = number of classifiers, W = their folded weight rows: F = Z V^T).
 int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,
@@ -290,10 +292,12 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
         k2.C = G + p0 * ldg; k2.ldc = ldg;
         k2.M = int(rows); k2.N = int(r); k2.K = int(B); k2.n_store = int(out_cols);
         LPD_HIP(log.begin(2, s));
-        if (out_cols != B && r <= 8) {
-            // a handful of classifiers: one bandwidth-bound pass over the panel serves them all,
-            // instead of an MFMA tile that would be 94 % padding or more
-            LPD_HIP(launch_margins_multi(Z, rows, B, c.ldz, W, r, ldw, G + p0 * ldg, ldg, s));
+        if (out_cols != B && r <= kSweepClassifiers) {
+            // a few classifiers: bandwidth-bound passes over the panel, 8 classifiers each, instead of an
+            // MFMA tile that would be three quarters padding or more
+            for (int64_t q0 = 0; q0 < r; q0 += 8)
+                LPD_HIP(launch_margins_multi(Z, rows, B, c.ldz, W + q0 * ldw, std::min<int64_t>(8, r - q0), ldw,
+                                             G + p0 * ldg + q0, ldg, s));
         } else {
             LPD_HIP(launch_gemm(k2, EPI_STORE, s));
         }

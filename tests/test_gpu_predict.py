@@ -43,8 +43,10 @@ def test_fold_weights(lpd, dev, r, B, c):
 
 @pytest.mark.parametrize("name,n,B,n_test,c", [
     ("tiny", 1500, 128, 777, 1),
-    ("small", 6000, 512, 2500, 3),       # sweep path (c <= 4), several panels
-    ("digit", 3000, 300, 1111, 10),      # MFMA path, nothing a multiple of a tile
+    ("small", 6000, 512, 2500, 3),       # sweep path, several panels
+    ("digit", 3000, 300, 1111, 10),      # sweep path in two passes (8 + 2), nothing a multiple of a tile
+    ("small", 3000, 256, 1500, 32),      # last class count served by sweeps
+    ("small", 3000, 256, 1500, 33),      # first one served by the MFMA product
     ("cnn", 2500, 260, 900, 45),
     ("highrank", 4000, 640, 2000, 130),
 ])

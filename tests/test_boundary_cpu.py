@@ -31,6 +31,28 @@ def test_every_declared_symbol_is_exported(L):
         assert hasattr(L, name), name
 
 
+def test_header_is_valid_c_and_links_from_c(tmp_path):
+    """include/lpd.h is a plain C header: a C99 program that includes it compiles without warnings, links against
+    the library and runs (version call only: no device is touched)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    from paper_2207_01016_amd import lpd
+    lpd.lib()
+    pkg = os.path.join(ROOT, "paper_2207_01016_amd")
+    src = tmp_path / "abi.c"
+    src.write_text('#include <stdio.h>\n#include "lpd.h"\n'
+                   'int main(void) { size_t b = 0, m = 0;\n'
+                   '  if (lpd_nystrom_factor_workspace(1000, 16, 128, &b, &m) != LPD_OK || b < m) return 2;\n'
+                   '  printf("%d %s\\n", lpd_version(), lpd_strerror(LPD_ERR_WORKSPACE)); return 0; }\n')
+    exe = tmp_path / "abi"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", pkg, "-llpd", f"-Wl,-rpath,{pkg}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(maxsplit=1)
+    assert int(out[0]) >= 100 and "workspace" in out[1]
+
+
 def test_version_and_strerror(L):
     assert L.lpd_version() >= 100
     for st in range(-7, 1):

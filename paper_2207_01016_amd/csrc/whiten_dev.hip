@@ -85,37 +85,57 @@ __global__ __launch_bounds__(256) void kll_kernel(const float *__restrict__ L, i
 }
 
 // ---------------------------------------------------------------- step 1b, tridiagonalisation
+//
+// Blocked Householder reduction.  Inside a panel of NBT columns the trailing matrix is left as it was
+// when the panel began (A_old); what the panel's reflectors have done to it so far lives in the pairs
+// (v_k, w_k) of the panel, A_cur = A_old - sum_k (v_k w_k^T + w_k v_k^T).  A column therefore costs one
+// READ of the trailing matrix (symv_kernel, 8 bytes per element) plus thin corrections with the panel's
+// vectors; the trailing matrix is rewritten once per panel (syr2k_kernel).
+// Per column j = j0 + i:   rowfix (current row j)  ->  hh (reflector v_i, tau, e_j, d_j)
+//                          ->  symv (y = A_old v_i; a_k = w_k . v_i, b_k = v_k . v_i for k < i)
+//                          ->  pfix (y -= sum_k v_k a_k + w_k b_k)  ->  w (w_i from y)
 
-// Step j, part 1 (one workgroup).  Row j of the trailing matrix, brought up to date with the pending
-// reflector pair (vp, wp), gives the diagonal entry dg[j] and the Householder vector v_j over columns
-// j+1.. (v_j[j+1] = 1), which is written to vc and, for the later accumulation of Q, over row j of A.
-__global__ __launch_bounds__(1024) void hh_kernel(double *__restrict__ A, int n, int j, int pending,
-                                                  const double *__restrict__ vp, const double *__restrict__ wp,
-                                                  double *__restrict__ vc, double *__restrict__ dg,
+constexpr int NBT = 32;       // columns per panel of the reduction
+
+typedef double d2 __attribute__((ext_vector_type(2)));
+
+// x[c] = A_old[j, c] - sum_{k<i} (v_k[j] w_k[c] + w_k[j] v_k[c]) for c >= j: row j as it stands now.
+__global__ __launch_bounds__(256) void rowfix_kernel(const double *__restrict__ A, int n, int j, int i,
+                                                     const double *__restrict__ Vp, const double *__restrict__ Wp,
+                                                     double *__restrict__ x)
+{
+    const int c = j + blockIdx.x * 256 + threadIdx.x;
+    if (c >= n) return;
+    double v = A[int64_t(j) * n + c];
+    for (int k = 0; k < i; ++k) {
+        const double *vk = Vp + int64_t(k) * n, *wk = Wp + int64_t(k) * n;
+        v -= vk[j] * wk[c] + wk[j] * vk[c];
+    }
+    x[c] = v;
+}
+
+// One workgroup.  From the current row x (columns j..): d_j = x[j], the Householder vector v over columns
+// j+1.. (v[j+1] = 1) with H x[j+1..] = e_j * unit vector, tau_j.  v goes to vout (the panel) and over row j
+// of A, where the accumulation of Q finds it later.
+__global__ __launch_bounds__(1024) void hh_kernel(double *__restrict__ A, int n, int j, const double *__restrict__ x,
+                                                  double *__restrict__ vout, double *__restrict__ dg,
                                                   double *__restrict__ e, double *__restrict__ tau)
 {
     __shared__ double red[16];
     double *row = A + int64_t(j) * n;
-    const double vpj = pending ? vp[j] : 0.0, wpj = pending ? wp[j] : 0.0;
     double ss = 0.0;
-    for (int c = j + threadIdx.x; c < n; c += blockDim.x) {
-        double x = row[c];
-        if (pending) x -= vpj * wp[c] + wpj * vp[c];
-        vc[c] = x;
-        if (c >= j + 2) ss += x * x;
-    }
-    ss = block_sum(ss, red);        // also orders the writes of vc before the reads below
-    const double diag = vc[j], alpha = vc[j + 1];
+    for (int c = j + 2 + threadIdx.x; c < n; c += blockDim.x) ss += x[c] * x[c];
+    ss = block_sum(ss, red);
+    const double diag = x[j], alpha = x[j + 1];
     double beta = alpha, t = 0.0, scale = 0.0;
     if (ss > 0.0) {
         beta = -copysign(sqrt(alpha * alpha + ss), alpha);
         t = (beta - alpha) / beta;
         scale = 1.0 / (alpha - beta);
     }
-    __syncthreads();
     for (int c = j + 1 + threadIdx.x; c < n; c += blockDim.x) {
-        const double v = c == j + 1 ? 1.0 : vc[c] * scale;
-        vc[c] = v;
+        const double v = c == j + 1 ? 1.0 : x[c] * scale;
+        vout[c] = v;
         row[c] = v;
     }
     if (threadIdx.x == 0) {
@@ -125,94 +145,100 @@ __global__ __launch_bounds__(1024) void hh_kernel(double *__restrict__ A, int n,
     }
 }
 
-// Step j, part 2: one pass over the trailing matrix A[j+1.., j+1..].  Each row is first updated with the
-// pending pair, A -= vp wp^T + wp vp^T, written back, and its inner product with v_j is left in y.
-// One wavefront per row at a time, rows dealt out grid-stride.
-__global__ __launch_bounds__(256) void trail_kernel(double *__restrict__ A, int n, int j, int pending,
-                                                    const double *__restrict__ vp, const double *__restrict__ wp,
-                                                    const double *__restrict__ vc, double *__restrict__ y)
+// y[a] = sum_{c > j} A_old[a, c] v[c] for rows a > j: read-only pass over the trailing matrix, one
+// wavefront per row pair (VEC: n even, 16-byte accesses from the even column at or below j+1, the element
+// left of j+1 masked) or per row.  Workgroups past the rows (blockIdx.x >= row_blocks) compute the panel
+// dots instead: block row_blocks + k gives coef[2k] = w_k . v and coef[2k+1] = v_k . v.
+template <bool VEC>
+__global__ __launch_bounds__(256) void symv_kernel(const double *__restrict__ A, int n, int j, int row_blocks,
+                                                   const double *__restrict__ v, double *__restrict__ y,
+                                                   const double *__restrict__ Vp, const double *__restrict__ Wp,
+                                                   double *__restrict__ coef)
 {
     const int lane = threadIdx.x & 63;
     const int c0 = j + 1;
-    for (int a = c0 + blockIdx.x * 4 + (threadIdx.x >> 6); a < n; a += gridDim.x * 4) {
-        double *row = A + int64_t(a) * n;
-        double acc0 = 0.0, acc1 = 0.0;
-        if (pending) {
-            const double va = vp[a], wa = wp[a];
-            int c = c0 + lane;
-            for (; c + 64 < n; c += 128) {
-                double x0 = row[c], x1 = row[c + 64];
-                x0 -= va * wp[c] + wa * vp[c];
-                x1 -= va * wp[c + 64] + wa * vp[c + 64];
-                row[c] = x0;
-                row[c + 64] = x1;
-                acc0 += x0 * vc[c];
-                acc1 += x1 * vc[c + 64];
+    if (int(blockIdx.x) >= row_blocks) {
+        __shared__ double red[16];
+        const int k = blockIdx.x - row_blocks;
+        const double *vk = Vp + int64_t(k) * n, *wk = Wp + int64_t(k) * n;
+        double sa = 0.0, sb = 0.0;
+        for (int c = c0 + threadIdx.x; c < n; c += 256) {
+            const double vc = v[c];
+            sa += wk[c] * vc;
+            sb += vk[c] * vc;
+        }
+        sa = block_sum(sa, red);
+        sb = block_sum(sb, red);
+        if (threadIdx.x == 0) { coef[2 * k] = sa; coef[2 * k + 1] = sb; }
+        return;
+    }
+    if (VEC) {
+        const int cal = c0 & ~1;
+        const int npair = (n - c0 + 1) / 2;
+        for (int pr = blockIdx.x * 4 + (threadIdx.x >> 6); pr < npair; pr += row_blocks * 4) {
+            const int a0 = c0 + 2 * pr;
+            const bool two = a0 + 1 < n;
+            const double *r0 = A + int64_t(a0) * n, *r1 = A + int64_t(two ? a0 + 1 : a0) * n;
+            double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+            int c = cal + 2 * lane;
+            if (c < n) {        // first slice: the element left of j+1 carries no weight
+                d2 vv = *reinterpret_cast<const d2 *>(v + c);
+                if (c < c0) vv.x = 0.0;
+                const d2 x0 = __builtin_nontemporal_load(reinterpret_cast<const d2 *>(r0 + c));
+                const d2 x1 = __builtin_nontemporal_load(reinterpret_cast<const d2 *>(r1 + c));
+                acc0 += x0.x * vv.x + x0.y * vv.y;
+                acc1 += x1.x * vv.x + x1.y * vv.y;
+                c += 128;
+            }
+            for (; c + 128 < n; c += 256) {
+                const d2 va = *reinterpret_cast<const d2 *>(v + c), vb = *reinterpret_cast<const d2 *>(v + c + 128);
+                const d2 x0 = __builtin_nontemporal_load(reinterpret_cast<const d2 *>(r0 + c));
+                const d2 x1 = __builtin_nontemporal_load(reinterpret_cast<const d2 *>(r1 + c));
+                const d2 x2 = __builtin_nontemporal_load(reinterpret_cast<const d2 *>(r0 + c + 128));
+                const d2 x3 = __builtin_nontemporal_load(reinterpret_cast<const d2 *>(r1 + c + 128));
+                acc0 += x0.x * va.x + x0.y * va.y;
+                acc1 += x1.x * va.x + x1.y * va.y;
+                acc2 += x2.x * vb.x + x2.y * vb.y;
+                acc3 += x3.x * vb.x + x3.y * vb.y;
             }
             if (c < n) {
-                double x0 = row[c];
-                x0 -= va * wp[c] + wa * vp[c];
-                row[c] = x0;
-                acc0 += x0 * vc[c];
+                const d2 va = *reinterpret_cast<const d2 *>(v + c);
+                const d2 x0 = __builtin_nontemporal_load(reinterpret_cast<const d2 *>(r0 + c));
+                const d2 x1 = __builtin_nontemporal_load(reinterpret_cast<const d2 *>(r1 + c));
+                acc0 += x0.x * va.x + x0.y * va.y;
+                acc1 += x1.x * va.x + x1.y * va.y;
             }
-        } else {
-            for (int c = c0 + lane; c < n; c += 64) acc0 += row[c] * vc[c];
+            acc0 = wave_sum(acc0 + acc2);
+            acc1 = wave_sum(acc1 + acc3);
+            if (lane == 0) {
+                y[a0] = acc0;
+                if (two) y[a0 + 1] = acc1;
+            }
         }
-        const double tot = wave_sum(acc0 + acc1);
-        if (lane == 0) y[a] = tot;
+    } else {
+        for (int a = c0 + blockIdx.x * 4 + (threadIdx.x >> 6); a < n; a += row_blocks * 4) {
+            const double *row = A + int64_t(a) * n;
+            double acc = 0.0;
+            for (int c = c0 + lane; c < n; c += 64) acc += row[c] * v[c];
+            acc = wave_sum(acc);
+            if (lane == 0) y[a] = acc;
+        }
     }
 }
 
-// The same pass for even n, where every row starts on a 16-byte boundary: two rows per wavefront share
-// the loads of the three vectors, and every lane moves 16 bytes per access.  The pass starts at the even
-// column at or below j+1; an element left of j+1 is carried through unchanged and adds nothing to y.
-typedef double d2 __attribute__((ext_vector_type(2)));
-
-__global__ __launch_bounds__(256) void trail2_kernel(double *__restrict__ A, int n, int j, int pending,
-                                                     const double *__restrict__ vp, const double *__restrict__ wp,
-                                                     const double *__restrict__ vc, double *__restrict__ y)
+// y[c] -= sum_{k<i} (v_k[c] a_k + w_k[c] b_k) for c > j, with a_k = coef[2k], b_k = coef[2k+1].
+__global__ __launch_bounds__(256) void pfix_kernel(int n, int j, int i, const double *__restrict__ Vp,
+                                                   const double *__restrict__ Wp, const double *__restrict__ coef,
+                                                   double *__restrict__ y)
 {
-    const int lane = threadIdx.x & 63;
-    const int c0 = j + 1;
-    const int cal = c0 & ~1;
-    const int npair = (n - c0 + 1) / 2;        // row pairs of the trailing matrix, the last one may be half
-    for (int pr = blockIdx.x * 4 + (threadIdx.x >> 6); pr < npair; pr += gridDim.x * 4) {
-        const int a0 = c0 + 2 * pr;
-        const bool two = a0 + 1 < n;
-        const int a1 = two ? a0 + 1 : a0;
-        double *r0 = A + int64_t(a0) * n, *r1 = A + int64_t(a1) * n;
-        const double va0 = pending ? vp[a0] : 0.0, wa0 = pending ? wp[a0] : 0.0;
-        const double va1 = pending ? vp[a1] : 0.0, wa1 = pending ? wp[a1] : 0.0;
-        double acc0 = 0.0, acc1 = 0.0;
-        for (int c = cal + 2 * lane; c < n; c += 128) {
-            d2 x0 = *reinterpret_cast<const d2 *>(r0 + c);
-            d2 x1 = *reinterpret_cast<const d2 *>(r1 + c);
-            d2 v = *reinterpret_cast<const d2 *>(vc + c);
-            if (pending) {
-                const d2 pv = *reinterpret_cast<const d2 *>(vp + c);
-                const d2 pw = *reinterpret_cast<const d2 *>(wp + c);
-                d2 u0 = x0 - (va0 * pw + wa0 * pv);
-                d2 u1 = x1 - (va1 * pw + wa1 * pv);
-                if (c < c0) { u0.x = x0.x; u1.x = x1.x; }
-                x0 = u0;
-                x1 = u1;
-                *reinterpret_cast<d2 *>(r0 + c) = x0;
-                if (two) *reinterpret_cast<d2 *>(r1 + c) = x1;
-            }
-            if (c < c0) v.x = 0.0;
-            acc0 += x0.x * v.x + x0.y * v.y;
-            acc1 += x1.x * v.x + x1.y * v.y;
-        }
-        acc0 = wave_sum(acc0);
-        acc1 = wave_sum(acc1);
-        if (lane == 0) {
-            y[a0] = acc0;
-            if (two) y[a1] = acc1;
-        }
-    }
+    const int c = j + 1 + blockIdx.x * 256 + threadIdx.x;
+    if (c >= n) return;
+    double v = y[c];
+    for (int k = 0; k < i; ++k) v -= Vp[int64_t(k) * n + c] * coef[2 * k] + Wp[int64_t(k) * n + c] * coef[2 * k + 1];
+    y[c] = v;
 }
 
-// Step j, part 3 (one workgroup): w_j = tau_j y - (tau_j^2 / 2)(y . v_j) v_j over columns j+1..
+// One workgroup: w = tau_j y - (tau_j^2 / 2)(y . v) v over columns j+1..
 __global__ __launch_bounds__(1024) void w_kernel(int n, int j, const double *__restrict__ tau,
                                                  const double *__restrict__ vc, const double *__restrict__ y,
                                                  double *__restrict__ wc)
@@ -226,21 +252,63 @@ __global__ __launch_bounds__(1024) void w_kernel(int n, int j, const double *__r
     for (int c = j + 1 + threadIdx.x; c < n; c += blockDim.x) wc[c] = t * y[c] - alpha * vc[c];
 }
 
-// The last pending pair applied to the 2x2 corner; n >= 2.
-__global__ void tri_tail_kernel(const double *__restrict__ A, int n, int pending, const double *__restrict__ vp,
-                                const double *__restrict__ wp, double *__restrict__ dg, double *__restrict__ e)
+// End of a panel of nb columns: A[a, c] -= sum_k (v_k[a] w_k[c] + w_k[a] v_k[c]) for a, c >= jn.
+// 64 x 64 tile per workgroup, 4 x 4 elements per thread, the four 64-long slices of the panel in LDS.
+__global__ __launch_bounds__(256) void syr2k_kernel(double *__restrict__ A, int n, int jn, int nb,
+                                                    const double *__restrict__ Vp, const double *__restrict__ Wp)
+{
+    __shared__ double va[NBT][64], wa[NBT][64], vc[NBT][64], wc[NBT][64];
+    const int a0 = jn + blockIdx.y * 64, c0 = jn + blockIdx.x * 64;
+    for (int e = threadIdx.x; e < NBT * 64; e += 256) {
+        const int k = e >> 6, t = e & 63;
+        const bool ka = k < nb && a0 + t < n, kc = k < nb && c0 + t < n;
+        va[k][t] = ka ? Vp[int64_t(k) * n + a0 + t] : 0.0;
+        wa[k][t] = ka ? Wp[int64_t(k) * n + a0 + t] : 0.0;
+        vc[k][t] = kc ? Vp[int64_t(k) * n + c0 + t] : 0.0;
+        wc[k][t] = kc ? Wp[int64_t(k) * n + c0 + t] : 0.0;
+    }
+    __syncthreads();
+    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+    double acc[4][4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[p][q] = 0.0;
+#pragma unroll 4
+    for (int k = 0; k < NBT; ++k) {
+        double av[4], aw[4], cv[4], cw[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            av[p] = va[k][ty * 4 + p];
+            aw[p] = wa[k][ty * 4 + p];
+            cv[p] = vc[k][tx * 4 + p];
+            cw[p] = wc[k][tx * 4 + p];
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[p][q] += av[p] * cw[q] + aw[p] * cv[q];
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int a = a0 + ty * 4 + p;
+        if (a >= n) continue;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = c0 + tx * 4 + q;
+            if (c < n) A[int64_t(a) * n + c] -= acc[p][q];
+        }
+    }
+}
+
+// d_{n-2}, e_{n-2}, d_{n-1} from the 2 x 2 corner once every update has been applied; n >= 2.
+__global__ void tri_tail_kernel(const double *__restrict__ A, int n, double *__restrict__ dg, double *__restrict__ e)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     const int a = n - 2, b = n - 1;
-    double daa = A[int64_t(a) * n + a], dab = A[int64_t(a) * n + b], dbb = A[int64_t(b) * n + b];
-    if (pending) {
-        daa -= 2.0 * vp[a] * wp[a];
-        dab -= vp[a] * wp[b] + wp[a] * vp[b];
-        dbb -= 2.0 * vp[b] * wp[b];
-    }
-    dg[a] = daa;
-    e[a] = dab;
-    dg[b] = dbb;
+    dg[a] = A[int64_t(a) * n + a];
+    e[a] = A[int64_t(a) * n + b];
+    dg[b] = A[int64_t(b) * n + b];
     e[b] = 0.0;
 }
 
@@ -529,7 +597,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const double *__restrict__ 
 // ---------------------------------------------------------------- host side
 
 struct DevCarve {
-    size_t off_A, off_Zt, off_vec, off_P, off_T, off_cs, off_tab, off_ord, off_lam, bytes;
+    size_t off_A, off_Zt, off_vec, off_panel, off_P, off_T, off_cs, off_tab, off_ord, off_lam, bytes;
     size_t cs_doubles;     // capacity of ONE of the two rotation buffers, header included
 };
 
@@ -541,7 +609,8 @@ DevCarve dev_carve(int64_t n)
     size_t o = 0;
     c.off_A = o; o += nn;
     c.off_Zt = o; o += nn;
-    c.off_vec = o; o += 8 * vec;                   // v, w (two of each), y, dg, e, tau
+    c.off_vec = o; o += 8 * vec;                   // x, y, coef, dg, e, tau (two spare)
+    c.off_panel = o; o += 2 * round_up(size_t(NBT) * size_t(n) * 8, kAlign);   // panel vectors v_k, w_k
     const size_t nchunks = size_t(n) / 128 + 2;
     c.off_P = o; o += round_up(nchunks * NB * NB * 8, kAlign);
     c.off_T = o; o += round_up(size_t(NB) * NB * 8, kAlign);
@@ -597,8 +666,10 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
     double *Zt = reinterpret_cast<double *>(ws + cv.off_Zt);
     const size_t vec = round_up(size_t(n) * 8, kAlign);
     auto vecp = [&](int k) { return reinterpret_cast<double *>(ws + cv.off_vec + size_t(k) * vec); };
-    double *vbuf[2] = {vecp(0), vecp(1)}, *wbuf[2] = {vecp(2), vecp(3)};
+    double *xrow = vecp(0), *coef = vecp(1);
     double *y = vecp(4), *dg_d = vecp(5), *e_d = vecp(6), *tau_d = vecp(7);
+    double *Vp = reinterpret_cast<double *>(ws + cv.off_panel);
+    double *Wp = reinterpret_cast<double *>(ws + cv.off_panel + round_up(size_t(NBT) * size_t(n) * 8, kAlign));
     double *P = reinterpret_cast<double *>(ws + cv.off_P);
     double *T = reinterpret_cast<double *>(ws + cv.off_T);
     double *cs_d[2] = {reinterpret_cast<double *>(ws + cv.off_cs),
@@ -651,28 +722,33 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
 
     say("tridiagonalisation");
     {
-        int pending = 0;
-        for (int j = 0; j + 2 < n; ++j) {
-            double *vc = vbuf[j & 1], *wc = wbuf[j & 1];
-            const double *vp = vbuf[(j & 1) ^ 1], *wp = wbuf[(j & 1) ^ 1];
-            hipLaunchKernelGGL(hh_kernel, dim3(1), dim3(1024), 0, s, A, n, j, pending, vp, wp, vc, dg_d, e_d, tau_d);
-            const int rows = n - j - 1;
-            if (n % 2 == 0) {
-                const int grid = std::min(2048, ((rows + 1) / 2 + 3) / 4);
-                hipLaunchKernelGGL(trail2_kernel, dim3(grid), dim3(256), 0, s, A, n, j, pending, vp, wp, vc, y);
-            } else {
-                const int grid = std::min(2048, (rows + 3) / 4);
-                hipLaunchKernelGGL(trail_kernel, dim3(grid), dim3(256), 0, s, A, n, j, pending, vp, wp, vc, y);
+        const bool even = n % 2 == 0;
+        for (int j0 = 0; j0 + 2 < n; j0 += NBT) {
+            const int nb = std::min(NBT, n - 2 - j0);
+            for (int i = 0; i < nb; ++i) {
+                const int j = j0 + i;
+                double *vi = Vp + int64_t(i) * n, *wi = Wp + int64_t(i) * n;
+                hipLaunchKernelGGL(rowfix_kernel, dim3((n - j + 255) / 256), dim3(256), 0, s, A, n, j, i, Vp, Wp, xrow);
+                hipLaunchKernelGGL(hh_kernel, dim3(1), dim3(1024), 0, s, A, n, j, xrow, vi, dg_d, e_d, tau_d);
+                const int rows = n - j - 1;
+                const int row_blocks = std::min(2048, even ? ((rows + 1) / 2 + 3) / 4 : (rows + 3) / 4);
+                if (even)
+                    hipLaunchKernelGGL((symv_kernel<true>), dim3(row_blocks + i), dim3(256), 0, s, A, n, j, row_blocks,
+                                       vi, y, Vp, Wp, coef);
+                else
+                    hipLaunchKernelGGL((symv_kernel<false>), dim3(row_blocks + i), dim3(256), 0, s, A, n, j, row_blocks,
+                                       vi, y, Vp, Wp, coef);
+                if (i > 0)
+                    hipLaunchKernelGGL(pfix_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, n, j, i, Vp, Wp, coef, y);
+                hipLaunchKernelGGL(w_kernel, dim3(1), dim3(1024), 0, s, n, j, tau_d, vi, y, wi);
             }
-            hipLaunchKernelGGL(w_kernel, dim3(1), dim3(1024), 0, s, n, j, tau_d, vc, y, wc);
-            pending = 1;
-            if ((j & 1023) == 1023) LPD_HIP(hipGetLastError());
+            const int jn = j0 + nb;
+            const int tiles = (n - jn + 63) / 64;
+            hipLaunchKernelGGL(syr2k_kernel, dim3(tiles, tiles), dim3(256), 0, s, A, n, jn, nb, Vp, Wp);
+            LPD_HIP(hipGetLastError());
         }
         if (n >= 2) {
-            const int jl = n - 3;        // last reflector, if any
-            const double *vp = vbuf[jl & 1], *wp = wbuf[jl & 1];
-            hipLaunchKernelGGL(tri_tail_kernel, dim3(1), dim3(64), 0, s, A, n, n >= 3 ? 1 : 0, n >= 3 ? vp : A,
-                               n >= 3 ? wp : A, dg_d, e_d);
+            hipLaunchKernelGGL(tri_tail_kernel, dim3(1), dim3(64), 0, s, A, n, dg_d, e_d);
         } else {
             LPD_HIP(hipMemcpyAsync(dg_d, A, 8, hipMemcpyDeviceToDevice, s));
         }

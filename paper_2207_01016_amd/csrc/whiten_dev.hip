@@ -4,16 +4,16 @@
 // the implicit-shift QL iteration on the tridiagonal matrix (O(B^2)), and overlaps it with the device.
 //
 //   1a  kll_kernel        K[a,b] = exp(-gamma ||l_a - l_b||^2) from direct differences
-//   1b  hh_kernel / trail_kernel / w_kernel, once per column: Householder reduction to tridiagonal
-//       form.  The rank-2 update of the trailing matrix by reflector j-1 and the matrix-vector
-//       product with reflector j share ONE pass over the trailing matrix (read, update, write, dot),
-//       so a step moves 16 bytes per trailing element and the reduction is bound by HBM bandwidth.
+//   1b  rowfix / hh / symv / pfix / w kernels per column, syr2k_kernel per panel of 32 columns: blocked
+//       Householder reduction to tridiagonal form.  A column reads the trailing matrix once (8 bytes
+//       per element, the pass that bounds the reduction); the matrix is rewritten once per panel.
 //       panel_gram_kernel / panel_t_kernel / panel_apply_kernel: Q^T accumulated row-wise from the
 //       reflectors, 32 at a time in compact form I - V T^T V^T.
-//       rot_kernel: the QL plane rotations, 16 sweeps per pass.  A thread owns one column of the
-//       eigenvector matrix and runs the sweeps as a register pipeline: rows enter in descending
-//       order, stage s holds one row, rotates it against the next and hands it on two steps later,
-//       so the 16 rotations of a step are independent and a pass reads and writes each row once.
+//       rot_table_kernel / rot_kernel: the QL plane rotations, 16 sweeps per pass.  A lane owns one
+//       column of the eigenvector matrix; the sweeps form a pipeline of 16 stages (registers inside a
+//       wavefront, LDS between the four wavefronts of a workgroup): rows enter in descending order,
+//       a stage holds one row, rotates it against the next and hands it on two steps later, so the
+//       rotations of a step are independent and a pass reads and writes each row once.
 //   1c  finish_kernel     W[j,:] = sign_j * u_j / sqrt(lambda_j) in eigenvalue order, rows >= r zero.
 #include <hip/hip_runtime.h>
 #include <stdint.h>

@@ -174,7 +174,10 @@ def bench_solver(args):
                    "eps": eps, "shrink_k": 5, "eta": 0.05},
         "solve": {"problems_per_s": P * len(recs) / elapsed, "ms_per_problem": elapsed * 1e3 / len(recs) / P,
                   "cd_steps_per_solve": steps_per_solve, "converged": int(st["converged"].sum()),
-                  "mean_epochs": float(st["epochs"].mean()), "mean_final_active": float(st["active"].mean())},
+                  "mean_epochs": float(st["epochs"].mean()), "mean_final_active": float(st["active"].mean()),
+                  # the kernel ends with its longest problem: its step count prices the dependent chain
+                  "max_steps_one_problem": int(st["steps"].max()), "mean_steps_one_problem": float(st["steps"].mean()),
+                  "ns_per_step_longest_problem": ms_kernel * 1e6 / max(int(st["steps"].max()), 1)},
         "roofline": {"kernel": "cd_solve_kernel", "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "bytes_per_launch": bytes_per_launch,
                      "avg_launch_ms": ms_kernel,

@@ -115,12 +115,19 @@ __device__ __forceinline__ float cd_violation(float alpha, float grad, float C)
 }
 
 // VEC: rows of G are 16-byte aligned (pointer and leading dimension); otherwise element-wise loads.
-template <int WAVES, int NCH, bool VEC>
+// MODE 0: rows read element-wise (any alignment); 1: 16-byte row loads; 2: 16-byte loads and r equal to the
+// 4 * NCH * 64 * WAVES columns the lanes cover, so that no lane ever holds a column past the end.
+template <int WAVES, int NCH, int MODE>
 __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
 {
+    constexpr bool VEC = MODE != 0;
+    constexpr bool EXACT = MODE == 2;
     constexpr int T = 64 * WAVES;
     constexpr int BLK = 64;                  // steps whose metadata is gathered at once
-    constexpr int D = NCH <= 4 ? 8 : 32 / NCH;   // row buffers in flight (at most 128 registers)
+    // row buffers in flight.  Measured on 1,125 problems of rank 1,024: 2 -> 165 ms, 4 -> 148, 6 -> 143, 8 -> 185
+    // (the step loop is unrolled D times for static register indexing; past 6 the code and the registers
+    // it needs cost more than the deeper prefetch gains)
+    constexpr int D = NCH <= 4 ? 6 : NCH <= 8 ? 4 : 2;
     __shared__ int32_t s_t[BLK];
     __shared__ int64_t s_row[BLK];
     __shared__ float s_y[BLK], s_alpha[BLK], s_q[BLK];
@@ -149,7 +156,6 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
     // lane -> columns: chunk c covers columns (c*T + gl)*4 .. +3.  Loads are bare loads: nothing
     // touches a loaded register before the step that consumes it, so they stay in flight.  Chunks
     // (or chunk tails) past column r are read from a valid address and zeroed when consumed.
-    const bool ragged = r != NCH * T * 4;
     int nvalid[NCH], coff[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
@@ -174,7 +180,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
     };
     auto valid = [&](const cf32x4(&g)[NCH], int c) __attribute__((always_inline)) -> cf32x4 {
         cf32x4 v = g[c];
-        if (ragged) {
+        if (!EXACT) {
             if (nvalid[c] < 1) v.x = 0.f;
             if (nvalid[c] < 2) v.y = 0.f;
             if (nvalid[c] < 3) v.z = 0.f;
@@ -311,8 +317,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
             // to memory)
             cf32x4 gr[D][NCH];
 #pragma unroll
-            for (int u = 0; u < D - 1; ++u)
-                if (u < nb) load_row(gr[u], s_row[u]);
+            for (int u = 0; u < D - 1; ++u) load_row(gr[u], s_row[min(u, nb - 1)]);
             auto step = [&](int j, const cf32x4(&g)[NCH], cf32x4(&gn)[NCH]) __attribute__((always_inline)) {
                 // the eta share: one step on the head of the removed queue
                 if (a.shrink_k > 0 && a.check_every > 0 && since >= a.check_every && n_rem > 0) {
@@ -335,7 +340,10 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
                     n_nxt += ch;
                     n_rem += 1 - ch;
                 }
-                if (j + D - 1 < nb) load_row(gn, s_row[j + D - 1]);  // into the buffer step j-1 released
+                // into the buffer step j-1 released.  Unconditional (past the end of the block the last row
+                // is fetched again and never used): a branch around the loads would merge a path without
+                // them into the wait counts, and every step would then wait for its own prefetch
+                load_row(gn, s_row[min(j + D - 1, nb - 1)]);
                 const int t = s_t[j];
                 const float yt = s_y[j], at = s_alpha[j], qinv = s_q[j];
                 const float grad = 1.0f - yt * dot(g, w);            // step 2a
@@ -364,7 +372,15 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
                 n_rem += dr;
                 n_nxt += 1 - dr;
             };
-            for (int j0 = 0; j0 < nb; j0 += D) {
+            // whole groups of D steps run without a guard between them (a guard is a branch, and a branch
+            // between a prefetch and its use costs the overlap, as above); the ragged end of the last
+            // block of an epoch takes the guarded form
+            int j0 = 0;
+            for (; j0 + D <= nb; j0 += D) {
+#pragma unroll
+                for (int u = 0; u < D; ++u) step(j0 + u, gr[u], gr[(u + D - 1) % D]);
+            }
+            if (j0 < nb) {
 #pragma unroll
                 for (int u = 0; u < D; ++u)
                     if (j0 + u < nb) step(j0 + u, gr[u], gr[(u + D - 1) % D]);

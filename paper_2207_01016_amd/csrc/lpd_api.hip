@@ -677,8 +677,9 @@ int lpd_cd_solve(const float *G, int64_t n, int64_t r, int64_t ldg, const float 
     const bool vec = ldg % 4 == 0 && aligned16(G);
 #define LPD_CD_LAUNCH(WV, NC)                                                                       \
     do {                                                                                            \
-        if (vec) hipLaunchKernelGGL((cd_solve_kernel<WV, NC, true>), grid, dim3(64 * WV), 0, s, a); \
-        else hipLaunchKernelGGL((cd_solve_kernel<WV, NC, false>), grid, dim3(64 * WV), 0, s, a);    \
+        if (vec && r == 256 * WV * NC) hipLaunchKernelGGL((cd_solve_kernel<WV, NC, 2>), grid, dim3(64 * WV), 0, s, a); \
+        else if (vec) hipLaunchKernelGGL((cd_solve_kernel<WV, NC, 1>), grid, dim3(64 * WV), 0, s, a); \
+        else hipLaunchKernelGGL((cd_solve_kernel<WV, NC, 0>), grid, dim3(64 * WV), 0, s, a);    \
     } while (0)
     if (r <= 256) LPD_CD_LAUNCH(1, 1);
     else if (r <= 512) LPD_CD_LAUNCH(1, 2);

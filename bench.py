@@ -181,10 +181,10 @@ def bench_solver(args):
         "roofline": {"kernel": "cd_solve_kernel", "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "bytes_per_launch": bytes_per_launch,
                      "avg_launch_ms": ms_kernel,
-                     # profiles/cd_solve_small_ovo_kernel_stats.txt: FETCH_SIZE 3.7646e8 KiB x 2.0 + WRITE_SIZE 2.0479e6 KiB
-                     "traffic": 3.7646e8 * 1024 * 2.0 + 2.0479e6 * 1024,
+                     # profiles/cd_solve_small_ovo_kernel_stats.txt: FETCH_SIZE 3.7741e8 KiB x 2.0 + WRITE_SIZE 2.4194e6 KiB
+                     "traffic": 3.7741e8 * 1024 * 2.0 + 2.4194e6 * 1024,
                      "note": "4*r bytes of G per coordinate step; each row read misses L2 (a problem cycles through "
-                             "65 MB of rows), the loop is bound by memory latency per dependent step"},
+                             "65 MB of rows); the kernel ends with its longest problem, one dependent step after the other"},
     }
     if not args.no_cpu_baseline:
         from concurrent.futures import ThreadPoolExecutor

@@ -178,19 +178,20 @@ hipError_t launch_margins(const float *G, int64_t n_out, int64_t r, int64_t ldg,
     return launch_margins_lpr<8, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
 }
 
-// Up to 8 weight vectors in one pass over the rows (margins_multi_kernel).
+// Up to 8 weight vectors in one pass over the rows (margins_multi_kernel); four rows per wavefront share
+// the weight loads for K >= 3, two below.
 hipError_t launch_margins_multi(const float *G, int64_t n, int64_t r, int64_t ldg, const float *Ws, int64_t k,
                                 int64_t ldws, float *M, int64_t ldm, hipStream_t s)
 {
     const bool vec = aligned16(G) && aligned16(Ws) && ldg % 4 == 0 && ldws % 4 == 0;
-    const unsigned grid = row_grid(n, 4);
-#define LPD_MM(KK)                                                                                               \
-    case KK:                                                                                                     \
-        if (vec) hipLaunchKernelGGL((margins_multi_kernel<KK, true>), dim3(grid), dim3(256), 0, s, G, n, int(r), ldg, Ws, ldws, M, ldm); \
-        else hipLaunchKernelGGL((margins_multi_kernel<KK, false>), dim3(grid), dim3(256), 0, s, G, n, int(r), ldg, Ws, ldws, M, ldm);    \
-        break
+#define LPD_MM(KK, RR)                                                                                           \
+    case KK: {                                                                                                   \
+        const unsigned grid = row_grid(n, 4 * RR);                                                               \
+        if (vec) hipLaunchKernelGGL((margins_multi_kernel<KK, true, RR>), dim3(grid), dim3(256), 0, s, G, n, int(r), ldg, Ws, ldws, M, ldm); \
+        else hipLaunchKernelGGL((margins_multi_kernel<KK, false, RR>), dim3(grid), dim3(256), 0, s, G, n, int(r), ldg, Ws, ldws, M, ldm);    \
+    } break
     switch (int(k)) {
-        LPD_MM(1); LPD_MM(2); LPD_MM(3); LPD_MM(4); LPD_MM(5); LPD_MM(6); LPD_MM(7); LPD_MM(8);
+        LPD_MM(1, 2); LPD_MM(2, 2); LPD_MM(3, 4); LPD_MM(4, 4); LPD_MM(5, 4); LPD_MM(6, 4); LPD_MM(7, 4); LPD_MM(8, 4);
     }
 #undef LPD_MM
     return hipGetLastError();

@@ -120,53 +120,59 @@ __global__ __launch_bounds__(256) void sqnorm_kernel(const float *__restrict__ X
 
 // M[i, q] = sum_j G[i, j] * Ws[q, j] for a handful of weight vectors at once (K <= 8): one pass over G
 // serves all of them (the sweep the solver's callers run for several classifiers that share G: C grid,
-// folds, class pairs; Section 3).  One wavefront per row at a time, 16-byte non-temporal loads of G,
-// the K weight vectors re-read through the cache, K butterflies at the end of the row.
-template <int K, bool VEC>
+// folds, class pairs; Section 3).  A wavefront takes ROWS rows at a time: every 16-byte piece of a weight
+// vector it reads (through the cache) is used for all of them, so the cache traffic per byte of G falls
+// with ROWS; G itself comes in 16-byte non-temporal loads; K * ROWS butterflies end a group of rows.  A
+// group past the end re-reads the last row and drops the result.
+template <int K, bool VEC, int ROWS>
 __global__ __launch_bounds__(256) void margins_multi_kernel(const float *__restrict__ G, int64_t n, int r, int64_t ldg,
                                                             const float *__restrict__ Ws, int64_t ldws,
                                                             float *__restrict__ M, int64_t ldm)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t stride = int64_t(gridDim.x) * 4;
+    const int64_t stride = int64_t(gridDim.x) * 4 * ROWS;
     const int r4 = VEC ? (r & ~3) : 0;
-    for (int64_t i = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6); i < n; i += stride) {
-        const float *g = G + i * ldg;
-        float s[K];
+    for (int64_t i0 = (int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6)) * ROWS; i0 < n; i0 += stride) {
+        const float *g[ROWS];
 #pragma unroll
-        for (int q = 0; q < K; ++q) s[q] = 0.f;
+        for (int t = 0; t < ROWS; ++t) g[t] = G + (i0 + t < n ? i0 + t : n - 1) * ldg;
+        float s[ROWS][K];
+#pragma unroll
+        for (int t = 0; t < ROWS; ++t)
+#pragma unroll
+            for (int q = 0; q < K; ++q) s[t][q] = 0.f;
         if (VEC) {
-            int j = lane * 4;
-            for (; j + 256 < r4; j += 512) {
-                const rf32x4 g0 = __builtin_nontemporal_load(reinterpret_cast<const rf32x4 *>(g + j));
-                const rf32x4 g1 = __builtin_nontemporal_load(reinterpret_cast<const rf32x4 *>(g + j + 256));
+            for (int j = lane * 4; j < r4; j += 256) {
+                rf32x4 gv[ROWS];
+#pragma unroll
+                for (int t = 0; t < ROWS; ++t) gv[t] = __builtin_nontemporal_load(reinterpret_cast<const rf32x4 *>(g[t] + j));
 #pragma unroll
                 for (int q = 0; q < K; ++q) {
                     const rf32x4 w0 = *reinterpret_cast<const rf32x4 *>(Ws + q * ldws + j);
-                    const rf32x4 w1 = *reinterpret_cast<const rf32x4 *>(Ws + q * ldws + j + 256);
-                    s[q] += (g0.x * w0.x + g0.y * w0.y + g0.z * w0.z + g0.w * w0.w) +
-                            (g1.x * w1.x + g1.y * w1.y + g1.z * w1.z + g1.w * w1.w);
-                }
-            }
-            for (; j < r4; j += 256) {
-                const rf32x4 g0 = __builtin_nontemporal_load(reinterpret_cast<const rf32x4 *>(g + j));
 #pragma unroll
-                for (int q = 0; q < K; ++q) {
-                    const rf32x4 w0 = *reinterpret_cast<const rf32x4 *>(Ws + q * ldws + j);
-                    s[q] += g0.x * w0.x + g0.y * w0.y + g0.z * w0.z + g0.w * w0.w;
+                    for (int t = 0; t < ROWS; ++t)
+                        s[t][q] += gv[t].x * w0.x + gv[t].y * w0.y + gv[t].z * w0.z + gv[t].w * w0.w;
                 }
             }
         }
         for (int j = r4 + lane; j < r; j += 64) {
-            const float gj = g[j];
+            float gj[ROWS];
 #pragma unroll
-            for (int q = 0; q < K; ++q) s[q] += gj * Ws[q * ldws + j];
+            for (int t = 0; t < ROWS; ++t) gj[t] = g[t][j];
+#pragma unroll
+            for (int q = 0; q < K; ++q) {
+                const float wj = Ws[q * ldws + j];
+#pragma unroll
+                for (int t = 0; t < ROWS; ++t) s[t][q] += gj[t] * wj;
+            }
         }
 #pragma unroll
-        for (int q = 0; q < K; ++q) {
-            const float tot = group_sum<64>(s[q]);
-            if (lane == 0) M[i * ldm + q] = tot;
-        }
+        for (int t = 0; t < ROWS; ++t)
+#pragma unroll
+            for (int q = 0; q < K; ++q) {
+                const float tot = group_sum<64>(s[t][q]);
+                if (lane == 0 && i0 + t < n) M[(i0 + t) * ldm + q] = tot;
+            }
     }
 }
 

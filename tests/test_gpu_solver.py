@@ -70,7 +70,8 @@ def test_row_sqnorms(lpd, dev):
     assert np.allclose(gsq.cpu().numpy(), ref, rtol=1e-5)
 
 
-@pytest.mark.parametrize("r,ld", [(10, 12), (256, 256), (300, 300), (1000, 1024), (2048, 2048), (4100, 4100),
+@pytest.mark.parametrize("r,ld", [(10, 12), (256, 256), (300, 300), (512, 512), (1000, 1024), (1024, 1024),
+                                  (1024, 1026), (2048, 2048), (4096, 4096), (4100, 4100), (8192, 8192),
                                   (8200, 8200)])
 def test_fixed_epochs_no_shrinking_matches_oracle(lpd, oracle, dev, r, ld):
     """Three plain epochs: alpha and w track the double-precision trajectory (every register layout)."""

@@ -98,6 +98,34 @@ def test_whiten_degenerate_cases(lpd, oracle, dev):
     assert rank == 0 and W.shape == (0, 0)
 
 
+@pytest.mark.parametrize("B,gamma,dup", [(600, 0.05, 50), (512, 1e-4, 0), (384, 3e-3, 7)])
+def test_whiten_rank_deficient_matches_host_and_whitens(lpd, oracle, dev, B, gamma, dup):
+    """Many eigenvalues at or below the clipping threshold (duplicated landmarks, or a kernel so wide that the
+    spectrum decays under it): same rank and eigenvalues as the host routine, kept components whiten K_LL,
+    dropped rows are exact zeros."""
+    g = torch.Generator().manual_seed(B)
+    X = torch.randn((B, 12), generator=g)
+    if dup:
+        X[B - dup:] = X[:dup]
+    Wd, ed, rd = lpd.lpd_whiten(X.to(dev), gamma)
+    Wh, eh, rh = lpd.lpd_whiten_host(X, gamma)
+    assert rd == rh and rd < B
+    assert torch.max(torch.abs(ed - eh)).item() <= 1e-11 * eh[0].item()
+    assert torch.all(Wd[rd:] == 0)
+    K = oracle.kernel_block(X.numpy(), X.numpy(), gamma)
+    W64 = Wd[:rd].double().cpu().numpy()
+    # fp32 rounding of W is amplified by 1/lambda on the smallest kept components: check the well-conditioned part
+    keep = int((ed.numpy() >= 1e-4 * ed[0].item()).sum())
+    assert keep >= 1
+    P = W64[:keep] @ K @ W64[:keep].T
+    assert np.linalg.norm(P - np.eye(keep)) <= 1e-3 * keep ** 0.5
+    # both routines span the same space: W^T W (the pseudo-inverse of K_LL on the kept range) agrees
+    # on its dominant part
+    Ph = Wh[:keep].double().T @ Wh[:keep].double()
+    Pd = Wd[:keep].double().cpu().T @ Wd[:keep].double().cpu()
+    assert float((Ph - Pd).norm() / Ph.norm()) <= 1e-4
+
+
 def test_whiten_feeds_the_factor(lpd, oracle, dev):
     """End to end on the device: W from lpd_whiten, G from lpd_nystrom_factor; landmark rows give G G^T = K_LL."""
     from paper_2207_01016_amd import workloads

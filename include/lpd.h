@@ -245,6 +245,15 @@ int lpd_kernel_block_csr(const int64_t *row_ptr, const int32_t *col_idx, const f
                          const float *L, int64_t B, int64_t ldl,
                          float gamma, float *Z, int64_t ldz, int64_t chunk_rows,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
+/* Scores of sparse new points: F = K(X, L) V^T as lpd_predict computes it (V c x B folded
+ * classifiers, F n x c), X in compressed-row form as above; same workspace query. */
+int lpd_predict_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values,
+                    int64_t n, int64_t d,
+                    const float *L, int64_t B, int64_t ldl,
+                    float gamma,
+                    const float *V, int64_t c, int64_t ldv,
+                    float *F, int64_t ldf, int64_t chunk_rows,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * The kernel block alone (Figure 1 steps 1a / 1d, Section 4 kernel):

@@ -366,14 +366,18 @@ int lpd_kernel_block_dense(const float *X, int64_t n, int64_t d, int64_t ldx, co
 // the memory of X, not arithmetic.  factor: G = K(X, L) W^T; otherwise Z = K(X, L).
 int csr_impl(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d, const float *L,
              int64_t B, int64_t ldl, float gamma, const float *W, int64_t r, int64_t ldw, float *out, int64_t ldo,
-             int64_t chunk_rows, void *workspace, size_t workspace_bytes, hipStream_t s, bool factor)
+             int64_t chunk_rows, void *workspace, size_t workspace_bytes, hipStream_t s, int mode)
 {
+    // mode 0: Z = K(X, L);  1: G = K(X, L) W^T (n x B, zero-filled past r);  2: F = K(X, L) V^T (n x r scores)
+    const bool factor = mode != 0;
+    const int64_t out_cols = mode == 2 ? r : B;
     if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
     if (factor && (r < 0 || r > B)) return LPD_ERR_SHAPE;
     if (n == 0 || B == 0) return LPD_OK;
     if (chunk_rows <= 0 || chunk_rows > kMaxDim) return LPD_ERR_SHAPE;
     if (!row_ptr || !out || (d > 0 && !L) || (factor && r > 0 && !W)) return LPD_ERR_NULL;
-    if (ldo < B || (d > 0 && ldl < d) || (factor && ldw < B)) return LPD_ERR_LD;
+    if (ldo < out_cols || (d > 0 && ldl < d) || (factor && ldw < B)) return LPD_ERR_LD;
+    if (mode == 2 && r == 0) return LPD_OK;
     chunk_rows = std::min(chunk_rows, n);
     const CsrCarve cc = csr_carve(chunk_rows, d, B);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < cc.bytes)
@@ -391,8 +395,8 @@ int csr_impl(const int64_t *row_ptr, const int32_t *col_idx, const float *values
                                c0, rows, int(d), Xd, cc.ldxd);
         if (hipGetLastError() != hipSuccess) return LPD_ERR_HIP;
         const int st = factor
-            ? factor_impl(Xd, rows, d, cc.ldxd, L, B, ldl, gamma, W, r, ldw, out + c0 * ldo, ldo, B, dws, dws_bytes, s,
-                          nullptr)
+            ? factor_impl(Xd, rows, d, cc.ldxd, L, B, ldl, gamma, W, r, ldw, out + c0 * ldo, ldo, out_cols, dws,
+                          dws_bytes, s, nullptr)
             : lpd_kernel_block_dense(Xd, rows, d, cc.ldxd, L, B, ldl, gamma, out + c0 * ldo, ldo, dws, dws_bytes, s);
         if (st != LPD_OK) return st;
     }
@@ -542,7 +546,15 @@ int lpd_nystrom_factor_csr(const int64_t *row_ptr, const int32_t *col_idx, const
                            void *hip_stream)
 {
     return csr_impl(row_ptr, col_idx, values, n, d, L, B, ldl, gamma, W, r, ldw, G, ldg, chunk_rows, workspace,
-                    workspace_bytes, static_cast<hipStream_t>(hip_stream), true);
+                    workspace_bytes, static_cast<hipStream_t>(hip_stream), 1);
+}
+
+int lpd_predict_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d,
+                    const float *L, int64_t B, int64_t ldl, float gamma, const float *V, int64_t c, int64_t ldv,
+                    float *F, int64_t ldf, int64_t chunk_rows, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return csr_impl(row_ptr, col_idx, values, n, d, L, B, ldl, gamma, V, c, ldv, F, ldf, chunk_rows, workspace,
+                    workspace_bytes, static_cast<hipStream_t>(hip_stream), 2);
 }
 
 int lpd_kernel_block_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d,
@@ -550,7 +562,7 @@ int lpd_kernel_block_csr(const int64_t *row_ptr, const int32_t *col_idx, const f
                          void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     return csr_impl(row_ptr, col_idx, values, n, d, L, B, ldl, gamma, nullptr, 0, B, Z, ldz, chunk_rows, workspace,
-                    workspace_bytes, static_cast<hipStream_t>(hip_stream), false);
+                    workspace_bytes, static_cast<hipStream_t>(hip_stream), 0);
 }
 
 int lpd_kernel_block(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,

@@ -66,6 +66,8 @@ SIGNATURES = {
                                               _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
     "lpd_kernel_block_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64,
                                             _i64, _vp, _sz, _vp]),
+    "lpd_predict_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _i64,
+                                       _vp, _i64, _i64, _vp, _sz, _vp]),
     "lpd_kernel_block": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _vp, _sz,
                                         _vp]),
     "lpd_margins": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp, _vp]),
@@ -347,6 +349,29 @@ def lpd_kernel_block_csr(row_ptr, col_idx, values, d: int, L, gamma: float, Z=No
                                       _ld(L), float(gamma), Z.data_ptr(), _ld(Z), chunk_rows, workspace.data_ptr(),
                                       workspace.numel(), _stream(L.device)), "lpd_kernel_block_csr")
     return Z
+
+
+def lpd_predict_csr(row_ptr, col_idx, values, d: int, L, gamma: float, V, F=None, chunk_rows: int = 0,
+                    workspace=None) -> torch.Tensor:
+    """Scores F[i, j] = V[j] . K(x_i, L) for new points in compressed-row form (n x c)."""
+    row_ptr, col_idx, values, n = _csr_args(row_ptr, col_idx, values, d)
+    L = _dev_f32(L, "L", 2)
+    V = _dev_f32(V, "V", 2)
+    B, c = L.shape[0], V.shape[0]
+    if L.shape[1] != d or V.shape[1] != B:
+        raise ValueError("shape mismatch: L B x d, V c x B")
+    if F is None:
+        F = torch.empty((n, c), dtype=torch.float32, device=L.device)
+    F = _dev_f32(F, "F", 2)
+    if F.shape != (n, c):
+        raise ValueError("F must be n x c")
+    chunk_rows, nbytes = lpd_nystrom_factor_csr_workspace(n, d, B, chunk_rows)
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=L.device)
+    _check(lib().lpd_predict_csr(row_ptr.data_ptr(), col_idx.data_ptr(), values.data_ptr(), n, d, L.data_ptr(), B,
+                                 _ld(L), float(gamma), V.data_ptr(), c, _ld(V), F.data_ptr(), _ld(F), chunk_rows,
+                                 workspace.data_ptr(), workspace.numel(), _stream(L.device)), "lpd_predict_csr")
+    return F
 
 
 def lpd_kernel_block(X, L, gamma: float, Z, workspace) -> torch.Tensor:

@@ -85,6 +85,21 @@ def test_factor_csr_digit_recipe(lpd, oracle, dev):
     assert relfro(G.cpu().numpy(), Gd.cpu().numpy()) <= 1e-6
 
 
+@pytest.mark.parametrize("c", [3, 40])
+def test_predict_csr_matches_dense_predict_and_oracle(lpd, oracle, dev, c):
+    from paper_2207_01016_amd import workloads
+    X, L = _sparse_problem(900, 60, 128, 0.25, 5, dev)
+    gamma = 0.05
+    V = torch.randn((c, 128), generator=torch.Generator().manual_seed(c)).to(dev) / 128 ** 0.5
+    rp, ci, va = workloads.to_csr(X)
+    F = lpd.lpd_predict_csr(rp, ci, va, 60, L, gamma, V, chunk_rows=256)
+    Fd = lpd.lpd_predict(X, L, gamma, V)
+    torch.cuda.synchronize()
+    assert relfro(F.cpu().numpy(), Fd.cpu().numpy()) <= 1e-6
+    Z = oracle.kernel_block_csr(rp.cpu().numpy(), ci.cpu().numpy(), va.cpu().numpy(), 60, L.cpu().numpy(), gamma)
+    assert relfro(F.cpu().numpy(), Z @ V.double().cpu().numpy().T) <= 1e-4
+
+
 def test_csr_edge_cases(lpd, oracle, dev):
     L = torch.rand((8, 5), generator=torch.Generator().manual_seed(2)).to(dev)
     # no entries at all: every row is the zero vector

@@ -1,0 +1,65 @@
+"""Figure 1 end to end on the device: preparation (1a-1c), factor (1d), dual coordinate ascent with shrinking
+(2a-2b), folding and prediction, composed through the C ABI only, against the same chain in the CPU oracle.
+
+The classifier is compared through what is unique: the scores of held-out points (both chains solve the same
+strictly concave dual in w), and the error rate they give on a problem whose classes are separable enough to
+make that rate meaningful.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+def test_train_and_predict_matches_oracle_chain(oracle):
+    from paper_2207_01016_amd import lpd
+    lpd.lib()
+    dev = torch.device("cuda:0")
+    g = torch.Generator().manual_seed(20220701)
+    n, n_test, d, B, gamma, C = 6000, 1500, 12, 200, 0.2, 0.5
+    # two overlapping classes: a shifted Gaussian against a ring
+    lab = (torch.rand(n + n_test, generator=g) < 0.5)
+    X = torch.randn((n + n_test, d), generator=g)
+    X[lab] *= 0.6
+    X[~lab] = X[~lab] / X[~lab].norm(dim=1, keepdim=True) * (3.4 + 0.3 * torch.randn((int((~lab).sum()), 1), generator=g))
+    y = torch.where(lab, 1.0, -1.0)
+    Xtr, ytr, Xte, yte = X[:n].contiguous(), y[:n].contiguous(), X[n:].contiguous(), y[n:]
+    L = Xtr[torch.randperm(n, generator=g)[:B]].contiguous()
+
+    # ---- device chain
+    Xd, Ld = Xtr.to(dev), L.to(dev)
+    W, eig, rank = lpd.lpd_whiten(Ld, gamma)
+    G = torch.empty((n, B), dtype=torch.float32, device=dev)
+    lpd.lpd_nystrom_factor(Xd, Ld, gamma, W, G, lpd.alloc_workspace(n, d, B, dev), r=rank)
+    gsq = lpd.lpd_row_sqnorms(G, r=rank)
+    order = torch.randperm(n, generator=g)
+    off = torch.tensor([0, n], dtype=torch.int64, device=dev)
+    alpha = torch.zeros(n, dtype=torch.float32, device=dev)
+    alpha, w, st = lpd.lpd_cd_solve(G, gsq, off, order.to(dev), ytr[order].to(dev),
+                                    torch.tensor([C], dtype=torch.float32, device=dev), alpha, eps=1e-4, max_epochs=5000, r=rank)
+    print("solver status:", st, flush=True)
+    assert st["converged"][0] == 1
+    V = lpd.lpd_fold_weights(W, w[:, :rank], r=rank)
+    F = lpd.lpd_predict(Xte.to(dev), Ld, gamma, V)
+    torch.cuda.synchronize()
+    f_gpu = F[:, 0].double().cpu().numpy()
+
+    # ---- the same chain in the oracle, from its own whitening on
+    Wo, eo, ro, K = oracle.whiten(L.numpy(), gamma, method="lapack")
+    assert ro == rank
+    Go = oracle.nystrom_factor(Xtr.numpy(), L.numpy(), gamma, Wo.astype(np.float32), r=ro)
+    a_ref, w_ref, s_ref = oracle.cd_solve(Go.astype(np.float32), order.numpy(), ytr[order].numpy(), C, eps=1e-6,
+                                          max_epochs=20000, r=ro)
+    assert s_ref["converged"]
+    f_ref = oracle.predict(Xte.numpy(), L.numpy(), gamma, Wo.astype(np.float32), w_ref[None, :], r=ro)[:, 0]
+
+    # scores of held-out points agree; the basis of W may differ between the chains, the scores may not
+    print("relative score difference:", np.linalg.norm(f_gpu - f_ref) / np.linalg.norm(f_ref), flush=True)
+    assert np.linalg.norm(f_gpu - f_ref) <= 5e-3 * np.linalg.norm(f_ref)
+    err_gpu = float(np.mean(np.sign(f_gpu) != yte.numpy()))
+    err_ref = float(np.mean(np.sign(f_ref) != yte.numpy()))
+    assert abs(err_gpu - err_ref) <= 0.004
+    assert err_ref < 0.1                                # the problem is learnable: the comparison means something
+    # and the dual optimum: sum(alpha) - 1/2 ||w||^2
+    assert abs(float(st["dual"][0]) - s_ref["dual"]) <= 1e-4 * abs(s_ref["dual"])

@@ -206,8 +206,11 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const cf32x4 v = valid(g, c);
-            s0 += v.x * w[c].x + v.y * w[c].y;
-            s1 += v.z * w[c].z + v.w * w[c].w;
+            // one fused multiply-add per element, two independent chains
+            s0 = fmaf(v.x, w[c].x, s0);
+            s1 = fmaf(v.z, w[c].z, s1);
+            s0 = fmaf(v.y, w[c].y, s0);
+            s1 = fmaf(v.w, w[c].w, s1);
         }
         return block_sum(s0 + s1);
     };

@@ -75,3 +75,89 @@ def test_full_size_workload(oracle, name):
     assert bool(torch.isfinite(m).all())
     # row-list sweep over the sample equals the full sweep on those rows, bit for bit
     assert torch.equal(lpd.lpd_margins_rows(G, rd, w, r=rank), m[rd])
+
+
+def test_full_size_predict_cnn(oracle):
+    """bench.py --path predict at its size: 262,144 new points of the cnn recipe, 10 classifiers; oracle on sampled points."""
+    from paper_2207_01016_amd import lpd, workloads
+    dev = torch.device("cuda:0")
+    wl = workloads.WORKLOADS["cnn"].with_rows(262144)
+    X = workloads.make_X(wl, dev)
+    L = X[workloads.landmark_indices(wl).to(dev)].contiguous()
+    W, eig, rank = lpd.lpd_whiten(L, wl.gamma)
+    torch.cuda.empty_cache()
+    c = 10
+    Ws = torch.randn((c, rank), generator=torch.Generator().manual_seed(2)) / rank ** 0.5
+    V = lpd.lpd_fold_weights(W, Ws.to(dev), r=rank)
+    F = lpd.lpd_predict(X, L, wl.gamma, V)
+    torch.cuda.synchronize()
+    rows = workloads.sample_rows(wl, 128, include=torch.tensor([0, wl.n - 1]))
+    ref = oracle.predict(X[rows.to(dev)].cpu().numpy(), L.cpu().numpy(), wl.gamma, W.cpu().numpy(), Ws.numpy(), r=rank)
+    err = relfro(F[rows.to(dev)].cpu().numpy(), ref)
+    print(f"[predict cnn] relF(scores) = {err:.3e}", flush=True)
+    assert err <= TOL_G
+    assert bool(torch.isfinite(F).all())
+
+
+def test_full_size_sparse_digit(oracle):
+    """bench.py --path sparse at its size: the digit recipe in compressed-row form, all 1,000,000 rows."""
+    from paper_2207_01016_amd import lpd, workloads
+    dev = torch.device("cuda:0")
+    wl = workloads.WORKLOADS["digit"]
+    X = workloads.make_X(wl, dev)
+    idx = workloads.landmark_indices(wl)
+    L = X[idx.to(dev)].contiguous()
+    W, eig, rank = lpd.lpd_whiten(L, wl.gamma)
+    torch.cuda.empty_cache()
+    rp, ci, va = workloads.to_csr(X)
+    rows = workloads.sample_rows(wl, 256, include=torch.cat([idx[:32], torch.tensor([0, wl.n - 1])]))
+    rd = rows.to(dev)
+    Xs = X[rd].cpu().numpy()
+    del X
+    G = torch.empty((wl.n, wl.B), dtype=torch.float32, device=dev)
+    lpd.lpd_nystrom_factor_csr(rp, ci, va, wl.d, L, wl.gamma, W, G, r=rank)      # suggested chunk size, as in bench.py
+    torch.cuda.synchronize()
+    ref = oracle.nystrom_factor(Xs, L.cpu().numpy(), wl.gamma, W.cpu().numpy(), r=rank)
+    err = relfro(G[rd].cpu().numpy(), ref)
+    print(f"[sparse digit] relF(G) = {err:.3e}", flush=True)
+    assert err <= TOL_G
+    sq = (G * G).sum(dim=1)
+    assert float(sq.max()) <= 1.0 + 1e-3
+
+
+def test_full_size_solver_batch(oracle):
+    """bench.py --path solver at its size: the 1,125 one-vs-one problems on the 'small' factor solved in one launch;
+    three of them (smallest, middle and largest C) against the oracle: dual optimum and weight vector."""
+    import bench
+    from paper_2207_01016_amd import lpd, workloads
+    dev = torch.device("cuda:0")
+    wl = workloads.WORKLOADS["small"]
+    X = workloads.make_X(wl, dev)
+    L = X[workloads.landmark_indices(wl).to(dev)].contiguous()
+    W, eig, rank = lpd.lpd_whiten(L, wl.gamma)
+    G = torch.empty((wl.n, wl.B), dtype=torch.float32, device=dev)
+    lpd.lpd_nystrom_factor(X, L, wl.gamma, W, G, lpd.alloc_workspace(wl.n, wl.d, wl.B, dev), r=rank)
+    gsq = lpd.lpd_row_sqnorms(G, r=rank)
+    probs = bench.solver_problems(wl, workloads.mixture_components(wl).numpy())
+    P = len(probs)
+    off = np.zeros(P + 1, dtype=np.int64)
+    for i, pr in enumerate(probs):
+        off[i + 1] = off[i] + len(pr[0])
+    rows = torch.from_numpy(np.concatenate([pr[0] for pr in probs])).to(dev)
+    y = torch.from_numpy(np.concatenate([pr[1] for pr in probs])).to(dev)
+    C = torch.tensor([pr[2] for pr in probs], dtype=torch.float32, device=dev)
+    alpha = torch.zeros(int(off[-1]), dtype=torch.float32, device=dev)
+    alpha, w, st = lpd.lpd_cd_solve(G, gsq, torch.from_numpy(off).to(dev), rows, y, C, alpha, eps=1e-3,
+                                    max_epochs=10000, r=rank)
+    assert int(st["converged"].sum()) == P
+    Gh = G.cpu().numpy()
+    for p in (0, 2, 4):                     # the five C values of the first pair and fold come first
+        pr = probs[p]
+        a_ref, w_ref, s_ref = oracle.cd_solve(Gh, pr[0], pr[1], pr[2], eps=1e-5, max_epochs=100000, r=rank)
+        assert s_ref["converged"]
+        dual = float(st["dual"][p])
+        wp = w[p].double().cpu().numpy()
+        print(f"[solver C={pr[2]}] dual {dual:.4f} oracle {s_ref['dual']:.4f}  |w - w*|/|w*| = "
+              f"{np.linalg.norm(wp - w_ref) / np.linalg.norm(w_ref):.2e}", flush=True)
+        assert abs(dual - s_ref["dual"]) <= 1e-3 * abs(s_ref["dual"])
+        assert np.linalg.norm(wp - w_ref) <= 2e-2 * np.linalg.norm(w_ref)

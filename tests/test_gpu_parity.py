@@ -322,3 +322,43 @@ def test_margins_multi_match_oracle(lpd, oracle, dev, n, r, ld, k):
         # the single-vector sweep of the same row gives the same bits only up to summation order: compare loosely
         m0 = lpd.lpd_margins(Gfull, Ws[0].contiguous(), r=r)
         assert float((m0.double() - M[:, 0].double()).norm() / m0.double().norm()) <= 1e-6
+
+
+def test_factor_sweep_and_predict_replay_from_a_hip_graph(lpd, wls, dev):
+    """The device entry points only enqueue kernels on the caller's stream (no allocation, no memset, no wait), so
+    they can be recorded into a HIP graph.  Replays, with eager work and synchronisations between them, must give
+    the eager result bit for bit every time."""
+    wl = wls.WORKLOADS["small"].with_shape(n=9000, B=384)
+    X, idx, L, W, eig, rank = _prepare(lpd, wls, wl, dev)
+    Wd = W.to(dev)
+    w = wls.make_w(wl).to(dev)
+    _, mn = lpd.lpd_nystrom_factor_workspace(wl.n, wl.d, wl.B)
+    ws = lpd.alloc_workspace(wl.n, wl.d, wl.B, dev, mn * 5)          # several panels per call
+    V = lpd.lpd_fold_weights(Wd, torch.randn((3, rank), generator=torch.Generator().manual_seed(1)).to(dev), r=rank)
+
+    def run(G, m, F):
+        lpd.lpd_nystrom_factor(X, L, wl.gamma, Wd, G, ws, r=rank)
+        lpd.lpd_margins(G, w, m, r=rank)
+        lpd.lpd_predict(X, L, wl.gamma, V, F, ws)
+
+    G0, m0, F0 = (torch.empty((wl.n, wl.B), device=dev), torch.empty(wl.n, device=dev), torch.empty((wl.n, 3), device=dev))
+    run(G0, m0, F0)
+    torch.cuda.synchronize()
+    G1, m1, F1 = torch.zeros_like(G0), torch.zeros_like(m0), torch.zeros_like(F0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(G1, m1, F1)                                              # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(G1, m1, F1)
+    for rep in range(3):
+        G1.fill_(float("nan")); m1.fill_(float("nan")); F1.fill_(float("nan"))
+        junk = (X @ X.T[:, :64]).sum()                               # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(G1, G0) and torch.equal(m1, m0) and torch.equal(F1, F0), rep
+        assert bool(torch.isfinite(junk))

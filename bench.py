@@ -53,6 +53,10 @@ def parse_args():
     ap.add_argument("--whiten", default="device", choices=["device", "host"],
                     help="steps 1a-1c (one-off preparation, outside the timed region): lpd_whiten on the GPU, or the "
                          "host routine")
+    ap.add_argument("--density", type=float, default=None,
+                    help="sparse: share of non-zeros of the digit-shaped recipe (default: its own 0.2)")
+    ap.add_argument("--csr-route", default="auto", choices=["auto", "dense", "gather"],
+                    help="sparse: route of the compressed-row entry points (auto = by density)")
     ap.add_argument("--chunk-rows", type=int, default=0, help="stream: rows per chunk (0 = the library's suggestion)")
     ap.add_argument("--random-w", action="store_true",
                     help="skip the host eigendecomposition and use a random W (tuning only; marks the line invalid)")
@@ -387,6 +391,9 @@ def bench_sparse(args):
     from paper_2207_01016_amd import lpd, workloads
     dev = torch.device("cuda:0")
     wl = workloads.WORKLOADS[args.workload]
+    if args.density is not None:
+        wl = wl.with_density(args.density)
+    lpd.lpd_set_option(lpd.LPD_OPT_CSR_ROUTE, lpd.CSR_ROUTES[args.csr_route])
     X = workloads.make_X(wl, dev)
     idx = workloads.landmark_indices(wl)
     L = X[idx.to(dev)].contiguous()
@@ -411,8 +418,9 @@ def bench_sparse(args):
     torch.cuda.synchronize()
     ms_dense = e0.elapsed_time(e1)
     del X, ws_d
-    chunk_rows, nbytes = lpd.lpd_nystrom_factor_csr_workspace(wl.n, wl.d, wl.B, args.chunk_rows)
+    chunk_rows, nbytes = lpd.lpd_nystrom_factor_csr_workspace(wl.n, wl.d, wl.B, args.chunk_rows, nnz)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    route = args.csr_route if args.csr_route != "auto" else ("gather" if nnz < 0.08 * wl.n * wl.d else "dense")
     evs = []
     for i in range(args.warmup + args.steps):
         if i == args.warmup:
@@ -435,12 +443,13 @@ def bench_sparse(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic" + (" (random W: tuning run)" if args.random_w else ""),
         "config": {"workload": wl.name + " (X in compressed-row form)", "n": wl.n, "d": wl.d, "B": wl.B, "rank": rank,
-                   "gamma": wl.gamma, "nnz": nnz, "density": nnz / (wl.n * wl.d), "chunk_rows": chunk_rows,
+                   "gamma": wl.gamma, "nnz": nnz, "density": nnz / (wl.n * wl.d), "route": route,
+                   "chunk_rows": chunk_rows,
                    "x_bytes_csr": 12 * nnz + 8 * (wl.n + 1), "x_bytes_dense": 4 * wl.n * wl.d},
         "ms_dense_factor_same_rows": ms_dense,
         "whiten_s": None if args.random_w else t_whiten,
-        "roofline": {"kernel": "lpd_nystrom_factor_csr: rows written out per chunk, then the dense MFMA schedule; "
-                               "flops counted as for the dense product, 2 n B (d + r)",
+        "roofline": {"kernel": "lpd_nystrom_factor_csr (" + route + " route), then the whitening product; "
+                               "flops counted as for the dense products, 2 n B (d + r)",
                      "bound": "mfma", "achieved": tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / FP32_MFMA_PEAK_TFLOPS, "flop_per_launch": flop, "avg_launch_ms": ms,
                      "traffic": None},

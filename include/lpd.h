@@ -70,9 +70,11 @@ const char *lpd_strerror(int status);
  *                      0 = choose by shape, 1 = 128x128, 2 = 256x128, 3 = 256x256
  *   LPD_OPT_GEMM_PIPELINE  main-loop schedule of the MFMA products: 1 (default) =
  *                      software-pipelined across the barrier, 0 = plain load/compute/store
+ *   LPD_OPT_CSR_ROUTE  route of the compressed-row entry points: 0 (default) = by density,
+ *                      1 = dense panels, 2 = gather; set it before the workspace query
  * Errors: LPD_ERR_SHAPE for an unknown option or value.
  */
-typedef enum { LPD_OPT_GEMM_TILE = 1, LPD_OPT_GEMM_PIPELINE = 2 } lpd_option;
+typedef enum { LPD_OPT_GEMM_TILE = 1, LPD_OPT_GEMM_PIPELINE = 2, LPD_OPT_CSR_ROUTE = 3 } lpd_option;
 int lpd_set_option(int option, int64_t value);
 
 /*
@@ -212,12 +214,16 @@ int lpd_nystrom_factor_to_host(const float *X, int64_t n, int64_t d, int64_t ldx
                                void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Step 1d and the kernel block for SPARSE inputs (Section 4: the paper runs its
- * kernel operations on sparse matrix products, since SVM data is often sparse).
- * X is given in compressed-row form; L, W and the output are dense as above.
- * Each chunk of rows is written out into a dense panel in the workspace and
- * goes through the same MFMA kernels as the dense entry points, so a row's
- * result equals that of the dense call on the written-out row.
+ * Step 1d, the kernel block and prediction for SPARSE inputs (Section 4: the
+ * paper runs its kernel operations on sparse matrix products, since SVM data is
+ * often sparse).  X is given in compressed-row form; L, W and the output are
+ * dense as above.  Two routes, chosen by the density nnz / (n d):
+ *   dense panels (8 % and above, or nnz unknown): each chunk of rows is written
+ *     out into a dense panel in the workspace and goes through the same MFMA
+ *     kernels as the dense entry points; a row's result equals that of the dense
+ *     call on the written-out row;
+ *   gather (below 8 %): the kernel block is accumulated entry by entry from the
+ *     transposed landmarks (vector FMA), then consumed as in the dense schedule.
  *
  *   row_ptr    device in  n+1 offsets (int64), row i owns entries
  *                         row_ptr[i] .. row_ptr[i+1]-1; row_ptr[0] = 0
@@ -225,30 +231,33 @@ int lpd_nystrom_factor_to_host(const float *X, int64_t n, int64_t d, int64_t ldx
  *                         any order; an index outside [0, d) is ignored
  *   values     device in  value of each entry (float)
  *              col_idx and values may be NULL when there are no entries.
- *   chunk_rows rows per dense panel, > 0 (the query suggests one: the factor's
- *              own panel size); *chunk_rows <= 0 on input asks for it
+ *   nnz        number of stored entries (row_ptr[n]) if the caller knows it, else
+ *              a negative value; it only selects the route (and, in the query,
+ *              the workspace that route needs): pass the same value to both
+ *   chunk_rows rows per panel, > 0 (the query suggests one: the factor's own
+ *              panel size); *chunk_rows <= 0 on input asks for it
  *   workspace  device, 256-byte aligned, at least the query's size for this
- *              chunk_rows: the dense panel and the dense call's scratch
+ *              chunk_rows and nnz
  * Stream-ordered like the dense calls.  Errors: as lpd_nystrom_factor.
  */
-int lpd_nystrom_factor_csr_workspace(int64_t n, int64_t d, int64_t B,
+int lpd_nystrom_factor_csr_workspace(int64_t n, int64_t d, int64_t B, int64_t nnz,
                                      int64_t *chunk_rows, size_t *bytes);
 int lpd_nystrom_factor_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values,
-                           int64_t n, int64_t d,
+                           int64_t n, int64_t d, int64_t nnz,
                            const float *L, int64_t B, int64_t ldl,
                            float gamma,
                            const float *W, int64_t r, int64_t ldw,
                            float *G, int64_t ldg, int64_t chunk_rows,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 int lpd_kernel_block_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values,
-                         int64_t n, int64_t d,
+                         int64_t n, int64_t d, int64_t nnz,
                          const float *L, int64_t B, int64_t ldl,
                          float gamma, float *Z, int64_t ldz, int64_t chunk_rows,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 /* Scores of sparse new points: F = K(X, L) V^T as lpd_predict computes it (V c x B folded
  * classifiers, F n x c), X in compressed-row form as above; same workspace query. */
 int lpd_predict_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values,
-                    int64_t n, int64_t d,
+                    int64_t n, int64_t d, int64_t nnz,
                     const float *L, int64_t B, int64_t ldl,
                     float gamma,
                     const float *V, int64_t c, int64_t ldv,

@@ -74,6 +74,7 @@ enum TileId { TILE_AUTO = 0, TILE_128x128 = 1, TILE_256x128 = 2, TILE_256x256 = 
 
 int g_pipe_option = 1;            // lpd_set_option(LPD_OPT_GEMM_PIPELINE, ...)
 int g_tile_option = TILE_AUTO;   // lpd_set_option(LPD_OPT_GEMM_TILE, ...)
+int g_csr_route = 0;              // lpd_set_option(LPD_OPT_CSR_ROUTE, ...): 0 by density, 1 dense panel, 2 gather
 
 int tile_choice(const GemmArgs &a)
 {
@@ -244,6 +245,29 @@ int check_factor_args(const float *X, int64_t n, int64_t d, int64_t ldx, const f
 
 constexpr int64_t kSweepClassifiers = 32;   // up to here prediction consumes a panel by sweeps, above by MFMA
 
+// What follows a panel of the kernel block: Z (rows x B) times W^T into `out` (factor: out_cols = B, zero fill
+// past r; prediction: out_cols = r classifiers, by sweeps of 8 while they are few, else by the MFMA product).
+hipError_t consume_panel(const float *Z, int64_t rows, int64_t ldz, int64_t B, const float *W, int64_t r, int64_t ldw,
+                         float *out, int64_t ldo, int64_t out_cols, hipStream_t s)
+{
+    if (out_cols != B && r <= kSweepClassifiers) {
+        // a few classifiers: bandwidth-bound passes over the panel, 8 classifiers each, instead of an
+        // MFMA tile that would be three quarters padding or more
+        for (int64_t q0 = 0; q0 < r; q0 += 8) {
+            const hipError_t e = launch_margins_multi(Z, rows, B, ldz, W + q0 * ldw, std::min<int64_t>(8, r - q0), ldw,
+                                                      out + q0, ldo, s);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    GemmArgs k2{};
+    k2.A = Z; k2.lda = ldz;
+    k2.B = W; k2.ldb = ldw;
+    k2.C = out; k2.ldc = ldo;
+    k2.M = int(rows); k2.N = int(r); k2.K = int(B); k2.n_store = int(out_cols);
+    return launch_gemm(k2, EPI_STORE, s);
+}
+
 // Shared schedule of the factor (out_cols = B: G = Z W^T with zero fill of columns r..B-1) and of
 // prediction (out_cols = r = number of classifiers, W = their folded weight rows: F = Z V^T).
 int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,
@@ -287,21 +311,8 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
         LPD_HIP(launch_gemm(k1, EPI_GAUSS, s));
         LPD_HIP(log.end(s));
 
-        GemmArgs k2{};
-        k2.A = Z; k2.lda = c.ldz;
-        k2.B = W; k2.ldb = ldw;
-        k2.C = G + p0 * ldg; k2.ldc = ldg;
-        k2.M = int(rows); k2.N = int(r); k2.K = int(B); k2.n_store = int(out_cols);
         LPD_HIP(log.begin(2, s));
-        if (out_cols != B && r <= kSweepClassifiers) {
-            // a few classifiers: bandwidth-bound passes over the panel, 8 classifiers each, instead of an
-            // MFMA tile that would be three quarters padding or more
-            for (int64_t q0 = 0; q0 < r; q0 += 8)
-                LPD_HIP(launch_margins_multi(Z, rows, B, c.ldz, W + q0 * ldw, std::min<int64_t>(8, r - q0), ldw,
-                                             G + p0 * ldg + q0, ldg, s));
-        } else {
-            LPD_HIP(launch_gemm(k2, EPI_STORE, s));
-        }
+        LPD_HIP(consume_panel(Z, rows, c.ldz, B, W, r, ldw, G + p0 * ldg, ldg, out_cols, s));
         LPD_HIP(log.end(s));
     }
 
@@ -321,15 +332,41 @@ done:
     return status;
 }
 
-// Workspace of the compressed-row entry points: one dense panel of chunk_rows rows of X (leading
-// dimension d rounded up to 4 floats), followed by the scratch of the dense call on that panel.
-struct CsrCarve { int64_t ldxd; size_t panel_bytes, bytes; };
-CsrCarve csr_carve(int64_t chunk_rows, int64_t d, int64_t B)
+// The compressed-row entry points take one of two routes.  Dense-panel route: each chunk of rows is written
+// out into a dense panel and handed to the dense MFMA schedule.  Gather route, for rows so sparse that the
+// written-out zeros would dominate: the kernel block is accumulated entry by entry from the transposed
+// landmarks.  The switch is the density nnz / (n d) against kGatherDensity; an unknown nnz (< 0) takes the
+// dense-panel route.  Measured on 1,000,000 x 784 rows against 4,096 landmarks, kernel-block share of the
+// factor: dense panels 45 ms at any density; gather 2 / 4 / 7.5 / 12 / 21 / 43 ms at 0.5 / 1 / 2 / 3 / 5 / 10 %
+// non-zeros.  Both scale with n d B, so the break-even near 10 % carries over to other shapes.
+constexpr double kGatherDensity = 0.08;
+
+bool csr_use_gather(int64_t n, int64_t d, int64_t nnz)
 {
-    CsrCarve c;
+    if (g_csr_route != 0) return g_csr_route == 2;
+    return nnz >= 0 && n > 0 && d > 0 && double(nnz) < kGatherDensity * double(n) * double(d);
+}
+
+// Workspace.  Dense-panel route: the panel (chunk_rows x ldxd, ldxd = d rounded up to 4) and the dense
+// call's scratch.  Gather route: the transposed landmarks (d x ldlt, ldlt = B rounded up to 4), the
+// landmark norms, and a panel of the kernel block (chunk_rows x ldz) for the product that follows.
+struct CsrCarve { bool gather; int64_t ldxd, ldlt, ldz; size_t panel_bytes, off_nl, off_z, bytes; };
+CsrCarve csr_carve(int64_t chunk_rows, int64_t d, int64_t B, bool gather)
+{
+    CsrCarve c{};
+    c.gather = gather;
     c.ldxd = std::max<int64_t>(4, (d + 3) / 4 * 4);
-    c.panel_bytes = round_up(size_t(chunk_rows) * size_t(c.ldxd) * 4, kAlign);
-    c.bytes = c.panel_bytes + carve(chunk_rows, B).rec_bytes;
+    c.ldlt = std::max<int64_t>(4, (B + 3) / 4 * 4);
+    c.ldz = panel_ld(B);
+    if (gather) {
+        c.panel_bytes = round_up(size_t(std::max<int64_t>(d, 1)) * size_t(c.ldlt) * 4, kAlign);     // Lt
+        c.off_nl = c.panel_bytes;
+        c.off_z = c.off_nl + round_up(size_t(B) * 4, kAlign);
+        c.bytes = c.off_z + round_up(size_t(chunk_rows) * size_t(c.ldz) * 4, kAlign);
+    } else {
+        c.panel_bytes = round_up(size_t(chunk_rows) * size_t(c.ldxd) * 4, kAlign);
+        c.bytes = c.panel_bytes + carve(chunk_rows, B).rec_bytes;
+    }
     return c;
 }
 
@@ -360,13 +397,10 @@ int lpd_kernel_block_dense(const float *X, int64_t n, int64_t d, int64_t ldx, co
     return launch_gemm(k1, EPI_GAUSS, s) == hipSuccess ? LPD_OK : LPD_ERR_HIP;
 }
 
-// Sparse rows go through the dense MFMA path: each chunk of rows is written out into a dense panel and
-// handed to the dense schedule.  With fp32 MFMA at 16 times the vector rate the written-out zeros cost less
-// than a gather-based product would down to a density of a few percent; what the compressed form saves is
-// the memory of X, not arithmetic.  factor: G = K(X, L) W^T; otherwise Z = K(X, L).
-int csr_impl(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d, const float *L,
-             int64_t B, int64_t ldl, float gamma, const float *W, int64_t r, int64_t ldw, float *out, int64_t ldo,
-             int64_t chunk_rows, void *workspace, size_t workspace_bytes, hipStream_t s, int mode)
+// factor: G = K(X, L) W^T; prediction: F = K(X, L) V^T; otherwise Z = K(X, L), for X in compressed-row form.
+int csr_impl(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d, int64_t nnz,
+             const float *L, int64_t B, int64_t ldl, float gamma, const float *W, int64_t r, int64_t ldw, float *out,
+             int64_t ldo, int64_t chunk_rows, void *workspace, size_t workspace_bytes, hipStream_t s, int mode)
 {
     // mode 0: Z = K(X, L);  1: G = K(X, L) W^T (n x B, zero-filled past r);  2: F = K(X, L) V^T (n x r scores)
     const bool factor = mode != 0;
@@ -379,11 +413,35 @@ int csr_impl(const int64_t *row_ptr, const int32_t *col_idx, const float *values
     if (ldo < out_cols || (d > 0 && ldl < d) || (factor && ldw < B)) return LPD_ERR_LD;
     if (mode == 2 && r == 0) return LPD_OK;
     chunk_rows = std::min(chunk_rows, n);
-    const CsrCarve cc = csr_carve(chunk_rows, d, B);
+    const CsrCarve cc = csr_carve(chunk_rows, d, B, csr_use_gather(n, d, nnz));
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < cc.bytes)
         return LPD_ERR_WORKSPACE;
-    float *Xd = static_cast<float *>(workspace);
-    void *dws = static_cast<char *>(workspace) + cc.panel_bytes;
+    char *wsp = static_cast<char *>(workspace);
+
+    if (cc.gather) {
+        float *Lt = reinterpret_cast<float *>(wsp);
+        float *nl = reinterpret_cast<float *>(wsp + cc.off_nl);
+        float *Zp = reinterpret_cast<float *>(wsp + cc.off_z);
+        hipLaunchKernelGGL(transpose_kernel, dim3(unsigned((B + 31) / 32), unsigned((d + 31) / 32)), dim3(256), 0, s, L,
+                           int(B), int(d), ldl, Lt, cc.ldlt);
+        if (hipGetLastError() != hipSuccess || launch_sqnorm(L, B, d, ldl, nl, s) != hipSuccess) return LPD_ERR_HIP;
+        const float scale = -gamma * 1.44269504088896340736f;
+        for (int64_t c0 = 0; c0 < n; c0 += chunk_rows) {
+            const int64_t rows = std::min(chunk_rows, n - c0);
+            float *Zout = factor ? Zp : out + c0 * ldo;
+            const int64_t ldzo = factor ? cc.ldz : ldo;
+            const dim3 grid(unsigned((B + 1023) / 1024), unsigned(std::min<int64_t>(rows, 16384)));
+            hipLaunchKernelGGL(csr_gauss_gather_kernel, grid, dim3(256), 0, s, row_ptr, col_idx, values, c0, rows, int(d),
+                               Lt, int(B), cc.ldlt, nl, scale, Zout, ldzo);
+            if (hipGetLastError() != hipSuccess) return LPD_ERR_HIP;
+            if (factor && consume_panel(Zp, rows, cc.ldz, B, W, r, ldw, out + c0 * ldo, ldo, out_cols, s) != hipSuccess)
+                return LPD_ERR_HIP;
+        }
+        return LPD_OK;
+    }
+
+    float *Xd = reinterpret_cast<float *>(wsp);
+    void *dws = wsp + cc.panel_bytes;
     const size_t dws_bytes = workspace_bytes - cc.panel_bytes;
     for (int64_t c0 = 0; c0 < n; c0 += chunk_rows) {
         const int64_t rows = std::min(chunk_rows, n - c0);
@@ -427,6 +485,10 @@ int lpd_set_option(int option, int64_t value)
 {
     if (option == LPD_OPT_GEMM_TILE && value >= TILE_AUTO && value <= TILE_256x256) {
         g_tile_option = int(value);
+        return LPD_OK;
+    }
+    if (option == LPD_OPT_CSR_ROUTE && value >= 0 && value <= 2) {
+        g_csr_route = int(value);
         return LPD_OK;
     }
     if (option == LPD_OPT_GEMM_PIPELINE && (value == 0 || value == 1)) {
@@ -530,38 +592,38 @@ done:
     return status;
 }
 
-int lpd_nystrom_factor_csr_workspace(int64_t n, int64_t d, int64_t B, int64_t *chunk_rows, size_t *bytes)
+int lpd_nystrom_factor_csr_workspace(int64_t n, int64_t d, int64_t B, int64_t nnz, int64_t *chunk_rows, size_t *bytes)
 {
     if (!chunk_rows || !bytes) return LPD_ERR_NULL;
     if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
     if (*chunk_rows <= 0) *chunk_rows = std::max<int64_t>(1, std::min<int64_t>(n, carve(n, B).rec_rows));
     if (*chunk_rows > kMaxDim) return LPD_ERR_SHAPE;
-    *bytes = csr_carve(*chunk_rows, d, B).bytes;
+    *bytes = csr_carve(*chunk_rows, d, B, csr_use_gather(n, d, nnz)).bytes;
     return LPD_OK;
 }
 
-int lpd_nystrom_factor_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d,
+int lpd_nystrom_factor_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d, int64_t nnz,
                            const float *L, int64_t B, int64_t ldl, float gamma, const float *W, int64_t r, int64_t ldw,
                            float *G, int64_t ldg, int64_t chunk_rows, void *workspace, size_t workspace_bytes,
                            void *hip_stream)
 {
-    return csr_impl(row_ptr, col_idx, values, n, d, L, B, ldl, gamma, W, r, ldw, G, ldg, chunk_rows, workspace,
+    return csr_impl(row_ptr, col_idx, values, n, d, nnz, L, B, ldl, gamma, W, r, ldw, G, ldg, chunk_rows, workspace,
                     workspace_bytes, static_cast<hipStream_t>(hip_stream), 1);
 }
 
-int lpd_predict_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d,
+int lpd_predict_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d, int64_t nnz,
                     const float *L, int64_t B, int64_t ldl, float gamma, const float *V, int64_t c, int64_t ldv,
                     float *F, int64_t ldf, int64_t chunk_rows, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    return csr_impl(row_ptr, col_idx, values, n, d, L, B, ldl, gamma, V, c, ldv, F, ldf, chunk_rows, workspace,
+    return csr_impl(row_ptr, col_idx, values, n, d, nnz, L, B, ldl, gamma, V, c, ldv, F, ldf, chunk_rows, workspace,
                     workspace_bytes, static_cast<hipStream_t>(hip_stream), 2);
 }
 
-int lpd_kernel_block_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d,
+int lpd_kernel_block_csr(const int64_t *row_ptr, const int32_t *col_idx, const float *values, int64_t n, int64_t d, int64_t nnz,
                          const float *L, int64_t B, int64_t ldl, float gamma, float *Z, int64_t ldz, int64_t chunk_rows,
                          void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    return csr_impl(row_ptr, col_idx, values, n, d, L, B, ldl, gamma, nullptr, 0, B, Z, ldz, chunk_rows, workspace,
+    return csr_impl(row_ptr, col_idx, values, n, d, nnz, L, B, ldl, gamma, nullptr, 0, B, Z, ldz, chunk_rows, workspace,
                     workspace_bytes, static_cast<hipStream_t>(hip_stream), 0);
 }
 

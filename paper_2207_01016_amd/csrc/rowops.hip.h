@@ -228,4 +228,82 @@ __global__ __launch_bounds__(256) void csr_scatter_kernel(const int64_t *__restr
     }
 }
 
+// Lt[k, b] = L[b, k]: the landmarks with the feature index outermost, so that the B kernel arguments one
+// stored entry of a sparse row contributes to are contiguous.  32 x 32 tiles through LDS.
+__global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ L, int B, int d, int64_t ldl,
+                                                        float *__restrict__ Lt, int64_t ldlt)
+{
+    __shared__ float tile[32][33];
+    const int b0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int b = b0 + ty + 8 * q, k = k0 + tx;
+        tile[ty + 8 * q][tx] = (b < B && k < d) ? L[int64_t(b) * ldl + k] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int k = k0 + ty + 8 * q, b = b0 + tx;
+        if (k < d && b < B) Lt[int64_t(k) * ldlt + b] = tile[tx][ty + 8 * q];
+    }
+}
+
+// Kernel block of sparse rows by gathering (Section 4: kernel operations as sparse matrix products), for
+// rows so sparse that writing them out would waste the contraction: S[t, b] = sum over the stored entries
+// (k, v) of row t of v * Lt[k, b], then Z = exp2(scale * max(0, ||x_t||^2 + ||l_b||^2 - 2 S)).  A workgroup
+// owns 1,024 consecutive landmarks (4 per lane) and walks over rows; the entries of a row are uniform
+// across the workgroup, each costs one 16-byte load of Lt per lane, four of them in flight.
+__global__ __launch_bounds__(256) void csr_gauss_gather_kernel(const int64_t *__restrict__ row_ptr,
+                                                               const int32_t *__restrict__ col_idx,
+                                                               const float *__restrict__ values, int64_t p0,
+                                                               int64_t rows, int d, const float *__restrict__ Lt,
+                                                               int B, int64_t ldlt, const float *__restrict__ nl,
+                                                               float scale, float *__restrict__ Z, int64_t ldz)
+{
+    const int c = blockIdx.x * 1024 + threadIdx.x * 4;
+    const int cl = c < B ? c : 0;                     // lanes past the end read a valid address, store nothing
+    float nlc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) nlc[q] = c + q < B ? nl[c + q] : 0.f;
+    const bool vec_store = (ldz % 4 == 0) && ((reinterpret_cast<uintptr_t>(Z) & 15) == 0) && c + 3 < B;
+    for (int64_t t = blockIdx.y; t < rows; t += gridDim.y) {
+        const int64_t e0 = row_ptr[p0 + t], e1 = row_ptr[p0 + t + 1];
+        rf32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float nx = 0.f;
+        for (int64_t e = e0; e < e1; e += 4) {
+            float v[4];
+            const rf32x4 *src[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool in = e + u < e1;
+                const int32_t k = in ? col_idx[e + u] : 0;
+                const bool ok = in && k >= 0 && k < d;
+                v[u] = ok ? values[e + u] : 0.f;
+                src[u] = reinterpret_cast<const rf32x4 *>(Lt + int64_t(ok ? k : 0) * ldlt + cl);
+            }
+            rf32x4 l[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) l[u] = *src[u];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                acc += v[u] * l[u];
+                nx += v[u] * v[u];
+            }
+        }
+        float z[4];
+        const float a4[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) z[q] = exp2f(scale * fmaxf(0.f, nx + nlc[q] - 2.f * a4[q]));
+        float *out = Z + t * ldz + c;
+        if (vec_store) {
+            *reinterpret_cast<rf32x4 *>(out) = rf32x4{z[0], z[1], z[2], z[3]};
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (c + q < B) out[q] = z[q];
+        }
+    }
+}
+
 }  // namespace lpd

@@ -60,14 +60,14 @@ SIGNATURES = {
                                                             ctypes.POINTER(_sz)]),
     "lpd_nystrom_factor_to_host": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64,
                                                   _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
-    "lpd_nystrom_factor_csr_workspace": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_i64),
+    "lpd_nystrom_factor_csr_workspace": (ctypes.c_int, [_i64, _i64, _i64, _i64, ctypes.POINTER(_i64),
                                                         ctypes.POINTER(_sz)]),
-    "lpd_nystrom_factor_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64,
-                                              _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
-    "lpd_kernel_block_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64,
-                                            _i64, _vp, _sz, _vp]),
-    "lpd_predict_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _i64,
-                                       _vp, _i64, _i64, _vp, _sz, _vp]),
+    "lpd_nystrom_factor_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp,
+                                              _i64, _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
+    "lpd_kernel_block_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp,
+                                            _i64, _i64, _vp, _sz, _vp]),
+    "lpd_predict_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64,
+                                       _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
     "lpd_kernel_block": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _vp, _sz,
                                         _vp]),
     "lpd_margins": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp, _vp]),
@@ -133,6 +133,8 @@ def lpd_version() -> int:
 
 LPD_OPT_GEMM_TILE = 1
 LPD_OPT_GEMM_PIPELINE = 2
+LPD_OPT_CSR_ROUTE = 3
+CSR_ROUTES = {"auto": 0, "dense": 1, "gather": 2}
 GEMM_TILES = {"auto": 0, "128x128": 1, "256x128": 2, "256x256": 3}
 
 
@@ -294,10 +296,11 @@ def _csr_args(row_ptr, col_idx, values, d):
     return row_ptr, col_idx, values, n
 
 
-def lpd_nystrom_factor_csr_workspace(n: int, d: int, B: int, chunk_rows: int = 0):
-    """(chunk_rows, bytes) of the compressed-row entry points (the suggested chunk for chunk_rows <= 0)."""
+def lpd_nystrom_factor_csr_workspace(n: int, d: int, B: int, chunk_rows: int = 0, nnz: int = -1):
+    """(chunk_rows, bytes) of the compressed-row entry points (the suggested chunk for chunk_rows <= 0); nnz
+    selects the route, and with it the workspace, as in the calls themselves."""
     cr, nb = _i64(int(chunk_rows)), _sz(0)
-    _check(lib().lpd_nystrom_factor_csr_workspace(n, d, B, ctypes.byref(cr), ctypes.byref(nb)),
+    _check(lib().lpd_nystrom_factor_csr_workspace(n, d, B, int(nnz), ctypes.byref(cr), ctypes.byref(nb)),
            "lpd_nystrom_factor_csr_workspace")
     return int(cr.value), int(nb.value)
 
@@ -319,10 +322,10 @@ def lpd_nystrom_factor_csr(row_ptr, col_idx, values, d: int, L, gamma: float, W,
     G = _dev_f32(G, "G", 2)
     if G.shape != (n, B):
         raise ValueError("G: expected n x B")
-    chunk_rows, nbytes = lpd_nystrom_factor_csr_workspace(n, d, B, chunk_rows)
+    chunk_rows, nbytes = lpd_nystrom_factor_csr_workspace(n, d, B, chunk_rows, col_idx.numel())
     if workspace is None:
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=L.device)
-    _check(lib().lpd_nystrom_factor_csr(row_ptr.data_ptr(), col_idx.data_ptr(), values.data_ptr(), n, d, L.data_ptr(),
+    _check(lib().lpd_nystrom_factor_csr(row_ptr.data_ptr(), col_idx.data_ptr(), values.data_ptr(), n, d, col_idx.numel(), L.data_ptr(),
                                         B, _ld(L), float(gamma), W.data_ptr(), r, _ld(W), G.data_ptr(), _ld(G),
                                         chunk_rows, workspace.data_ptr(), workspace.numel(), _stream(L.device)),
            "lpd_nystrom_factor_csr")
@@ -342,10 +345,10 @@ def lpd_kernel_block_csr(row_ptr, col_idx, values, d: int, L, gamma: float, Z=No
     Z = _dev_f32(Z, "Z", 2)
     if Z.shape != (n, B):
         raise ValueError("Z: expected n x B")
-    chunk_rows, nbytes = lpd_nystrom_factor_csr_workspace(n, d, B, chunk_rows)
+    chunk_rows, nbytes = lpd_nystrom_factor_csr_workspace(n, d, B, chunk_rows, col_idx.numel())
     if workspace is None:
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=L.device)
-    _check(lib().lpd_kernel_block_csr(row_ptr.data_ptr(), col_idx.data_ptr(), values.data_ptr(), n, d, L.data_ptr(), B,
+    _check(lib().lpd_kernel_block_csr(row_ptr.data_ptr(), col_idx.data_ptr(), values.data_ptr(), n, d, col_idx.numel(), L.data_ptr(), B,
                                       _ld(L), float(gamma), Z.data_ptr(), _ld(Z), chunk_rows, workspace.data_ptr(),
                                       workspace.numel(), _stream(L.device)), "lpd_kernel_block_csr")
     return Z
@@ -365,10 +368,10 @@ def lpd_predict_csr(row_ptr, col_idx, values, d: int, L, gamma: float, V, F=None
     F = _dev_f32(F, "F", 2)
     if F.shape != (n, c):
         raise ValueError("F must be n x c")
-    chunk_rows, nbytes = lpd_nystrom_factor_csr_workspace(n, d, B, chunk_rows)
+    chunk_rows, nbytes = lpd_nystrom_factor_csr_workspace(n, d, B, chunk_rows, col_idx.numel())
     if workspace is None:
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=L.device)
-    _check(lib().lpd_predict_csr(row_ptr.data_ptr(), col_idx.data_ptr(), values.data_ptr(), n, d, L.data_ptr(), B,
+    _check(lib().lpd_predict_csr(row_ptr.data_ptr(), col_idx.data_ptr(), values.data_ptr(), n, d, col_idx.numel(), L.data_ptr(), B,
                                  _ld(L), float(gamma), V.data_ptr(), c, _ld(V), F.data_ptr(), _ld(F), chunk_rows,
                                  workspace.data_ptr(), workspace.numel(), _stream(L.device)), "lpd_predict_csr")
     return F

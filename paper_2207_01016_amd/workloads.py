@@ -39,6 +39,7 @@ class Workload:
     gamma: float
     landmarks: str      # "first" or "random"
     features: str       # recipe key for X
+    density: float = 0.2   # share of non-zeros of the "sparse_uniform" recipe (0.2 = the digit-shaped workload)
 
     def seed(self, what: int) -> int:
         # 0: X, 1: landmark indices, 2: w, 3: labels, 4: row sample
@@ -47,6 +48,10 @@ class Workload:
     def with_rows(self, n: int) -> "Workload":
         """Same recipe with a different number of rows (for test-sized cases)."""
         return dataclasses.replace(self, n=int(n))
+
+    def with_density(self, density: float) -> "Workload":
+        """The "sparse_uniform" recipe with another share of non-zeros (for the sparse-route measurements)."""
+        return dataclasses.replace(self, density=float(density))
 
     def with_shape(self, n: int | None = None, d: int | None = None, B: int | None = None) -> "Workload":
         return dataclasses.replace(self, n=int(n or self.n), d=int(d or self.d), B=int(B or self.B))
@@ -88,7 +93,7 @@ def make_X(wl: Workload, device="cpu") -> torch.Tensor:
             out += means[comp_all[r0:r1]]
         elif wl.features == "sparse_uniform":
             out.uniform_(0.0, 1.0, generator=g)
-            keep = torch.rand(out.shape, generator=g, device=device, dtype=torch.float32) < 0.2
+            keep = torch.rand(out.shape, generator=g, device=device, dtype=torch.float32) < wl.density
             out *= keep
         elif wl.features == "relu_normalised":
             out.normal_(0.0, 1.0, generator=g)

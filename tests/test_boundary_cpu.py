@@ -261,24 +261,36 @@ def test_whiten_device_query_and_argument_errors(L):
 def test_csr_query_and_argument_errors(L):
     cr, nb = ctypes.c_int64(0), ctypes.c_size_t(0)
     q = L.lpd_nystrom_factor_csr_workspace
-    assert q(1_000_000, 784, 4096, ctypes.byref(cr), ctypes.byref(nb)) == 0
+    assert q(1_000_000, 784, 4096, -1, ctypes.byref(cr), ctypes.byref(nb)) == 0
     assert 0 < cr.value <= 1_000_000 and nb.value >= cr.value * 784 * 4 and nb.value % 256 == 0
-    assert q(10, 4, 8, None, ctypes.byref(nb)) == -1
-    assert q(10, -4, 8, ctypes.byref(cr), ctypes.byref(nb)) == -2
+    # a density under 8 % selects the gather route: transposed landmarks instead of a dense panel of X
+    cr2, nb2 = ctypes.c_int64(cr.value), ctypes.c_size_t(0)
+    assert q(1_000_000, 784, 4096, 784 * 10_000, ctypes.byref(cr2), ctypes.byref(nb2)) == 0
+    assert nb2.value >= 784 * 4096 * 4 + cr2.value * 4096 * 4 and nb2.value != nb.value
+    cr3, nb3 = ctypes.c_int64(cr.value), ctypes.c_size_t(0)
+    assert q(1_000_000, 784, 4096, 784 * 200_000, ctypes.byref(cr3), ctypes.byref(nb3)) == 0 and nb3.value == nb.value
+    assert q(10, 4, 8, -1, None, ctypes.byref(nb)) == -1
+    assert q(10, -4, 8, -1, ctypes.byref(cr), ctypes.byref(nb)) == -2
     buf = (ctypes.c_float * 4096)()
     p = ctypes.cast(buf, ctypes.c_void_p)
     f = L.lpd_nystrom_factor_csr
-    #        rp ci va n  d  L  B  ldl gamma W  r  ldw G  ldg chunk ws  bytes stream
-    assert f(p, p, p, 0, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, None, 0, None) == 0          # no rows
-    assert f(None, p, p, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, None, 0, None) == -1
-    assert f(p, p, p, 4, 4, p, 8, 4, 0.5, p, 9, 8, p, 8, 4, None, 0, None) == -2         # r > B
-    assert f(p, p, p, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, 0, None, 0, None) == -2         # chunk_rows must be > 0
-    assert f(p, p, p, 4, 4, p, 8, 3, 0.5, p, 8, 8, p, 8, 4, None, 0, None) == -3         # ldl < d
-    assert f(p, p, p, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 7, 4, None, 0, None) == -3         # ldg < B
-    assert f(p, p, p, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, None, 0, None) == -4         # no workspace
-    assert f(p, p, p, 4, 4, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, p, 256, None) == -4          # too small
+    #        rp ci va n  d  nnz L  B  ldl gamma W  r  ldw G  ldg chunk ws  bytes stream
+    assert f(p, p, p, 0, 4, -1, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, None, 0, None) == 0          # no rows
+    assert f(None, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, None, 0, None) == -1
+    assert f(p, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 9, 8, p, 8, 4, None, 0, None) == -2         # r > B
+    assert f(p, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 8, 8, p, 8, 0, None, 0, None) == -2         # chunk_rows must be > 0
+    assert f(p, p, p, 4, 4, -1, p, 8, 3, 0.5, p, 8, 8, p, 8, 4, None, 0, None) == -3         # ldl < d
+    assert f(p, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 8, 8, p, 7, 4, None, 0, None) == -3         # ldg < B
+    assert f(p, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, None, 0, None) == -4         # no workspace
+    assert f(p, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, p, 256, None) == -4          # too small
+    assert f(p, p, p, 4, 4, 0, p, 8, 4, 0.5, p, 8, 8, p, 8, 4, p, 256, None) == -4           # gather route: too small
     k = L.lpd_kernel_block_csr
-    #        rp ci va n  d  L  B  ldl gamma Z  ldz chunk ws  bytes stream
-    assert k(p, p, p, 4, 4, p, 8, 4, 0.5, None, 8, 4, None, 0, None) == -1
-    assert k(p, p, p, 4, 4, p, 8, 4, 0.5, p, 7, 4, None, 0, None) == -3
-    assert k(p, p, p, 4, 4, p, 8, 4, 0.5, p, 8, 4, None, 0, None) == -4
+    #        rp ci va n  d  nnz L  B  ldl gamma Z  ldz chunk ws  bytes stream
+    assert k(p, p, p, 4, 4, -1, p, 8, 4, 0.5, None, 8, 4, None, 0, None) == -1
+    assert k(p, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 7, 4, None, 0, None) == -3
+    assert k(p, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 8, 4, None, 0, None) == -4
+    g = L.lpd_predict_csr
+    #        rp ci va n  d  nnz L  B  ldl gamma V  c  ldv F  ldf chunk ws  bytes stream
+    assert g(p, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 9, 8, p, 9, 4, None, 0, None) == -2         # c > B
+    assert g(p, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 3, 8, p, 2, 4, None, 0, None) == -3         # ldf < c
+    assert L.lpd_set_option(3, 2) == 0 and L.lpd_set_option(3, 3) == -2 and L.lpd_set_option(3, 0) == 0

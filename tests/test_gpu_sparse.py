@@ -36,13 +36,22 @@ def _sparse_problem(n, d, B, density, seed, dev):
     return X.to(dev), L.to(dev)
 
 
+@pytest.fixture(params=["auto", "dense", "gather"])
+def route(request, lpd):
+    """Both routes of the compressed-row entry points, forced, and the choice by density."""
+    lpd.lpd_set_option(lpd.LPD_OPT_CSR_ROUTE, lpd.CSR_ROUTES[request.param])
+    yield request.param
+    lpd.lpd_set_option(lpd.LPD_OPT_CSR_ROUTE, 0)
+
+
 @pytest.mark.parametrize("n,d,B,density,chunk", [
-    (700, 50, 130, 0.2, 0),        # one chunk, d % 4 != 0 (panel leading dimension padded)
+    (700, 50, 130, 0.2, 0),        # one chunk, d % 4 != 0 (panel leading dimension padded), B % 4 != 0
     (1500, 784, 260, 0.2, 256),    # digit-like rows, several chunks with a ragged last one
-    (300, 33, 40, 0.02, 64),       # very sparse, most rows nearly empty
+    (300, 33, 40, 0.02, 64),       # very sparse, most rows nearly empty (gather route by density)
     (260, 16, 64, 1.0, 100),       # fully dense given as compressed rows
+    (900, 300, 2100, 0.01, 400),   # more than two 1,024-landmark slices of the gather kernel
 ])
-def test_kernel_block_csr_matches_oracle_and_dense(lpd, oracle, dev, n, d, B, density, chunk):
+def test_kernel_block_csr_matches_oracle_and_dense(lpd, oracle, dev, route, n, d, B, density, chunk):
     from paper_2207_01016_amd import workloads
     X, L = _sparse_problem(n, d, B, density, 11, dev)
     gamma = 1.0 / max(1.0, density * d)
@@ -58,7 +67,7 @@ def test_kernel_block_csr_matches_oracle_and_dense(lpd, oracle, dev, n, d, B, de
     assert relfro(Z.cpu().numpy(), Zd.cpu().numpy()) <= 1e-6
 
 
-def test_factor_csr_digit_recipe(lpd, oracle, dev):
+def test_factor_csr_digit_recipe(lpd, oracle, dev, route):
     """The 80 %-zeros recipe, scaled down: factor from compressed rows against the oracle on sampled rows."""
     from paper_2207_01016_amd import workloads
     wl = workloads.WORKLOADS["digit"].with_shape(n=6000, B=512)
@@ -82,11 +91,13 @@ def test_factor_csr_digit_recipe(lpd, oracle, dev):
     Gd = torch.empty_like(G)
     lpd.lpd_nystrom_factor(X, L, wl.gamma, W.to(dev), Gd, lpd.alloc_workspace(wl.n, wl.d, wl.B, dev), r=rank)
     torch.cuda.synchronize()
-    assert relfro(G.cpu().numpy(), Gd.cpu().numpy()) <= 1e-6
+    # dense panels run the very kernels of the dense call; the gather route sums the kernel argument in another
+    # order, and the whitening product amplifies that rounding difference as it does any other
+    assert relfro(G.cpu().numpy(), Gd.cpu().numpy()) <= (5e-5 if route == "gather" else 1e-6)
 
 
 @pytest.mark.parametrize("c", [3, 40])
-def test_predict_csr_matches_dense_predict_and_oracle(lpd, oracle, dev, c):
+def test_predict_csr_matches_dense_predict_and_oracle(lpd, oracle, dev, route, c):
     from paper_2207_01016_amd import workloads
     X, L = _sparse_problem(900, 60, 128, 0.25, 5, dev)
     gamma = 0.05
@@ -95,12 +106,12 @@ def test_predict_csr_matches_dense_predict_and_oracle(lpd, oracle, dev, c):
     F = lpd.lpd_predict_csr(rp, ci, va, 60, L, gamma, V, chunk_rows=256)
     Fd = lpd.lpd_predict(X, L, gamma, V)
     torch.cuda.synchronize()
-    assert relfro(F.cpu().numpy(), Fd.cpu().numpy()) <= 1e-6
+    assert relfro(F.cpu().numpy(), Fd.cpu().numpy()) <= (5e-5 if route == "gather" else 1e-6)
     Z = oracle.kernel_block_csr(rp.cpu().numpy(), ci.cpu().numpy(), va.cpu().numpy(), 60, L.cpu().numpy(), gamma)
     assert relfro(F.cpu().numpy(), Z @ V.double().cpu().numpy().T) <= 1e-4
 
 
-def test_csr_edge_cases(lpd, oracle, dev):
+def test_csr_edge_cases(lpd, oracle, dev, route):
     L = torch.rand((8, 5), generator=torch.Generator().manual_seed(2)).to(dev)
     # no entries at all: every row is the zero vector
     rp = torch.zeros(4, dtype=torch.int64, device=dev)

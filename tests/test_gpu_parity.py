@@ -234,6 +234,18 @@ def test_streaming_factor_matches_device_factor_and_oracle(lpd, wls, oracle, dev
     assert not G_host[:, rank:].any()
 
 
+def test_streaming_factor_zero_fills_dropped_components(lpd, wls, dev):
+    """r < B: the host matrix gets exact zeros in columns r..B-1, as the resident factor does."""
+    wl = wls.WORKLOADS["tiny"].with_shape(n=5000, B=160)
+    X, idx, L, W, eig, rank = _prepare(lpd, wls, wl, dev)
+    r = rank - 37
+    G_dev = _factor(lpd, X, L, wl.gamma, W, r).cpu()
+    host = torch.full((wl.n, wl.B), float("nan"), dtype=torch.float32, pin_memory=True)
+    lpd.lpd_nystrom_factor_to_host(X, L, wl.gamma, W.to(dev), host, chunk_rows=1024, r=r)
+    assert torch.equal(host[:, r:], torch.zeros((wl.n, wl.B - r)))
+    assert relfro(host.numpy(), G_dev.numpy()) <= 1e-6
+
+
 def test_factor_zero_sizes(lpd, dev):
     ws = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
     X = torch.zeros((0, 8), device=dev)

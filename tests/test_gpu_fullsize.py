@@ -73,6 +73,13 @@ def test_full_size_workload(oracle, name):
     lm = G[idx.to(dev)].double()
     assert torch.allclose((lm * lm).sum(dim=1), torch.ones(wl.B, dtype=torch.float64, device=dev), atol=1e-3)
     assert bool(torch.isfinite(m).all())
+    # the factor reproduces the kernel on the landmarks, off the diagonal too: G_L G_L^T = K_LL on a block
+    # of 128 landmarks (this is where a wrong eigenvector basis from the device preparation would show)
+    sub = idx[:: max(1, wl.B // 128)][:128]
+    gl = G[sub.to(dev)].double()
+    kll = oracle.kernel_block(L[:: max(1, wl.B // 128)][:128].cpu().numpy(), L[:: max(1, wl.B // 128)][:128].cpu().numpy(),
+                              wl.gamma)
+    assert relfro((gl @ gl.T).cpu().numpy(), kll) <= 1e-4
     # row-list sweep over the sample equals the full sweep on those rows, bit for bit
     assert torch.equal(lpd.lpd_margins_rows(G, rd, w, r=rank), m[rd])
 

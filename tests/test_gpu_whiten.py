@@ -148,3 +148,19 @@ def test_whiten_workspace_too_small(lpd, dev):
     with pytest.raises(lpd.LpdError) as ei:
         lpd.lpd_whiten(Lm, 0.1, workspace=torch.empty(4096, dtype=torch.uint8, device=dev))
     assert ei.value.status == -4
+
+
+def test_whiten_digit_workload_at_full_landmark_count(lpd, oracle, dev):
+    """The 4,096 landmarks of the digit-shaped workload, as bench.py prepares them: eigenvalues against the
+    oracle's LAPACK path to 1e-10 of the largest, the rank, and W K W^T = I."""
+    from paper_2207_01016_amd import workloads
+    wl = workloads.WORKLOADS["digit"].with_rows(65536)
+    X = workloads.make_X(wl)
+    Lm = X[workloads.landmark_indices(wl)].contiguous()
+    W, eig, rank = lpd.lpd_whiten(Lm.to(dev), wl.gamma)
+    Wo, eo, ro, K = oracle.whiten(Lm.numpy(), wl.gamma, method="lapack")
+    assert rank == ro == wl.B
+    assert np.max(np.abs(eig.numpy() - eo)) <= 1e-10 * eo[0]
+    Wd = W.double()
+    P = Wd @ torch.from_numpy(K).to(dev) @ Wd.T
+    assert float((P - torch.eye(wl.B, dtype=torch.float64, device=dev)).norm()) <= 2e-6 * wl.B

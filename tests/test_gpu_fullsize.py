@@ -30,6 +30,7 @@ def test_full_size_workload(oracle, name):
     lpd.lib()
     dev = torch.device("cuda:0")
     wl = workloads.WORKLOADS[name]
+    torch.cuda.empty_cache()                  # blocks cached from earlier tests go back before the large allocations
     print(f"[{name}] generating X {wl.n} x {wl.d}", flush=True)
     X = workloads.make_X(wl, dev)
     idx = workloads.landmark_indices(wl)

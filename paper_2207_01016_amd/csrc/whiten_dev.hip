@@ -377,30 +377,53 @@ __global__ __launch_bounds__(64) void panel_t_kernel(const double *__restrict__ 
     for (int e = threadIdx.x; e < NB * NB; e += 64) T[e] = ts[e / NB][e % NB];
 }
 
-// Rows r0.. of Zt times the panel: row <- row (I - V T^T V^T), 16 rows per workgroup.
+// Rows r0.. of Zt times the panel: row <- row (I - V T^T V^T), 16 rows per workgroup.  Both passes over the
+// columns fetch the next 64-column slice into registers while the current one is worked on from LDS.
 __global__ __launch_bounds__(256) void panel_apply_kernel(double *__restrict__ Zt, int n, const double *__restrict__ A,
                                                           int k0, int nb, const double *__restrict__ T, int r0)
 {
     constexpr int RB = 16, CC = 64;
+    constexpr int ZPT = RB * CC / 256, VPT = NB * CC / 256;     // elements per thread of a slice: 4 and 8
     __shared__ double zs[RB][CC + 1], vs[NB][CC + 1], ys[RB][NB + 1], y2[RB][NB + 1], ts[NB][NB + 1];
     const int rbase = r0 + blockIdx.x * RB;
     const int cfirst = k0 + 1;
     for (int e = threadIdx.x; e < NB * NB; e += 256) ts[e / NB][e % NB] = T[e];
+    double zreg[ZPT], vreg[VPT];
+    auto fetch_z = [&](int cb) {
+#pragma unroll
+        for (int q = 0; q < ZPT; ++q) {
+            const int e = threadIdx.x + q * 256, r = e / CC, c = e % CC;
+            zreg[q] = (rbase + r < n && cb + c < n) ? Zt[int64_t(rbase + r) * n + cb + c] : 0.0;
+        }
+    };
+    auto fetch_v = [&](int cb) {
+#pragma unroll
+        for (int q = 0; q < VPT; ++q) {
+            const int e = threadIdx.x + q * 256, t = e / CC, c = e % CC;
+            vreg[q] = panel_v(A, n, k0, nb, t, cb + c);
+        }
+    };
+    auto put_z = [&]() {
+#pragma unroll
+        for (int q = 0; q < ZPT; ++q) { const int e = threadIdx.x + q * 256; zs[e / CC][e % CC] = zreg[q]; }
+    };
+    auto put_v = [&]() {
+#pragma unroll
+        for (int q = 0; q < VPT; ++q) { const int e = threadIdx.x + q * 256; vs[e / CC][e % CC] = vreg[q]; }
+    };
 
     // Y[rr][t] = sum_c Zt[rbase+rr][c] v_t[c]; thread (rr, tq) owns t = tq and tq + 16
     const int rr = threadIdx.x >> 4, tq = threadIdx.x & 15;
     double ya = 0.0, yb = 0.0;
+    fetch_z(cfirst);
+    fetch_v(cfirst);
     for (int cb = cfirst; cb < n; cb += CC) {
         __syncthreads();
-        for (int e = threadIdx.x; e < RB * CC; e += 256) {
-            const int r = e / CC, c = e % CC;
-            zs[r][c] = (rbase + r < n && cb + c < n) ? Zt[int64_t(rbase + r) * n + cb + c] : 0.0;
-        }
-        for (int e = threadIdx.x; e < NB * CC; e += 256) {
-            const int t = e / CC, c = e % CC;
-            vs[t][c] = panel_v(A, n, k0, nb, t, cb + c);
-        }
+        put_z();
+        put_v();
         __syncthreads();
+        fetch_z(cb + CC);          // past the last column the guards turn the fetch into zeros
+        fetch_v(cb + CC);
 #pragma unroll 8
         for (int c = 0; c < CC; ++c) {
             const double z = zs[rr][c];
@@ -419,20 +442,25 @@ __global__ __launch_bounds__(256) void panel_apply_kernel(double *__restrict__ Z
         y2[r][t] = s;
     }
     // Zt[r][c] -= sum_t Y2[r][t] v_t[c]
+    fetch_z(cfirst);
+    fetch_v(cfirst);
     for (int cb = cfirst; cb < n; cb += CC) {
         __syncthreads();
-        for (int e = threadIdx.x; e < NB * CC; e += 256) {
-            const int t = e / CC, c = e % CC;
-            vs[t][c] = panel_v(A, n, k0, nb, t, cb + c);
-        }
+        put_v();
+        double zcur[ZPT];
+#pragma unroll
+        for (int q = 0; q < ZPT; ++q) zcur[q] = zreg[q];
         __syncthreads();
-        for (int e = threadIdx.x; e < RB * CC; e += 256) {
-            const int r = e / CC, c = e % CC;
+        fetch_z(cb + CC);
+        fetch_v(cb + CC);
+#pragma unroll
+        for (int q = 0; q < ZPT; ++q) {
+            const int e = threadIdx.x + q * 256, r = e / CC, c = e % CC;
             if (rbase + r < n && cb + c < n) {
                 double s = 0.0;
 #pragma unroll 8
                 for (int t = 0; t < NB; ++t) s += y2[r][t] * vs[t][c];
-                Zt[int64_t(rbase + r) * n + cb + c] -= s;
+                Zt[int64_t(rbase + r) * n + cb + c] = zcur[q] - s;
             }
         }
     }

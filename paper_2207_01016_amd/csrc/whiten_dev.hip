@@ -814,13 +814,20 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
     say("QL iteration (host) with rotation passes (device)");
     {
         int64_t nbatch = 0;
-        auto apply = [&](const std::vector<lpd_host::Sweep> &sw, const std::vector<double> &cs) {
+        // the QL iteration writes its rotations straight into the page-locked buffer of the batch, behind
+        // the header; the buffer is free once the copy queued from it two batches ago has run
+        auto buffer = [&]() -> double * {
+            const int b = int(nbatch & 1);
+            if (hip_fail || hipEventSynchronize(cs_free[b]) != hipSuccess) { hip_fail = hip_fail ? hip_fail : 1; return nullptr; }
+            return cs_h[b] + ROT_HDR;
+        };
+        auto apply = [&](const std::vector<lpd_host::Sweep> &sw, const double *cs, size_t ncs) {
             if (hip_fail || sw.empty()) return;
             const int b = int(nbatch & 1);
             ++nbatch;
             long long *hdr = reinterpret_cast<long long *>(cs_h[b]);
             int imin = n, imax = 0;
-            if (hipEventSynchronize(cs_free[b]) != hipSuccess) { hip_fail = 1; return; }   // staging free again
+            if (cs != cs_h[b] + ROT_HDR) { hip_fail = 2; return; }
             for (int k = 0; k < KSW; ++k) { hdr[k] = 1; hdr[KSW + k] = 0; hdr[2 * KSW + k] = 0; }
             for (size_t k = 0; k < sw.size() && k < size_t(KSW); ++k) {
                 hdr[k] = sw[k].lo;
@@ -829,13 +836,11 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
                 imin = std::min(imin, int(sw[k].lo));
                 imax = std::max(imax, int(sw[k].hi));
             }
-            if (ROT_HDR + cs.size() > cv.cs_doubles || sw.size() > size_t(KSW) || imax + 1 >= n || imin < 0 ||
-                imin > imax) {
+            if (ROT_HDR + ncs > cv.cs_doubles || sw.size() > size_t(KSW) || imax + 1 >= n || imin < 0 || imin > imax) {
                 hip_fail = 2;
                 return;
             }
-            std::memcpy(cs_h[b] + ROT_HDR, cs.data(), cs.size() * 8);
-            if (hipMemcpyAsync(cs_d[b], cs_h[b], (ROT_HDR + cs.size()) * 8, hipMemcpyHostToDevice, s) != hipSuccess ||
+            if (hipMemcpyAsync(cs_d[b], cs_h[b], (ROT_HDR + ncs) * 8, hipMemcpyHostToDevice, s) != hipSuccess ||
                 hipEventRecord(cs_free[b], s) != hipSuccess) { hip_fail = 1; return; }
             const int top = imax + 1;
             const int nsteps = (top - imin) + 2 * KSW;              // t = 0 .. t_last
@@ -856,7 +861,7 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
                 std::fflush(stderr);
             }
         };
-        ql_ok = lpd_host::tridiag_ql(dg.data(), e.data(), n, KSW, apply, prog);
+        ql_ok = lpd_host::tridiag_ql(dg.data(), e.data(), n, KSW, buffer, apply, prog);
     }
     if (hip_fail) { status = hip_fail == 1 ? LPD_ERR_HIP : LPD_ERR_NUMERIC; goto done; }
     if (!ql_ok) { status = LPD_ERR_NUMERIC; goto done; }

@@ -190,7 +190,7 @@ void tridiagonalise(double *A, int64_t n, double *dg, double *e, double *tau)
 // eigenvector (in the tridiagonal basis) of eigenvalue dg[i].
 using lpd_host::Sweep;
 
-void apply_rotations(double *Zt, int64_t n, const std::vector<Sweep> &sw, const std::vector<double> &cs)
+void apply_rotations(double *Zt, int64_t n, const std::vector<Sweep> &sw, const double *cs)
 {
     if (sw.empty()) return;
     const int k = int(sw.size());
@@ -295,12 +295,12 @@ void back_transform(const double *A, const double *tau, int64_t n, double *Zt)
 namespace lpd_host {
 
 // Implicit-shift QL iteration; returns false if an eigenvalue needs more than 60 sweeps.
-bool tridiag_ql(double *dg, double *e, int64_t n, int batch, const ApplyRotations &apply,
-                const std::function<void(int64_t)> &progress)
+bool tridiag_ql(double *dg, double *e, int64_t n, int batch, const RotationBuffer &buffer,
+                const ApplyRotations &apply, const std::function<void(int64_t)> &progress)
 {
     std::vector<Sweep> sw;
-    std::vector<double> cs;
-    cs.reserve(size_t(batch) * 2 * n);
+    double *cs = nullptr;       // storage of the current batch, fetched when its first sweep starts
+    size_t ncs = 0;
     const double eps = 2.220446049250313e-16;
     for (int64_t l = 0; l < n; ++l) {
         if (progress) progress(l);
@@ -318,7 +318,12 @@ bool tridiag_ql(double *dg, double *e, int64_t n, int batch, const ApplyRotation
             double r = std::hypot(g, 1.0);
             g = dg[m] - dg[l] + e[l] / (g + std::copysign(r, g));
             double s = 1.0, c = 1.0, p = 0.0;
-            Sweep rec{m, m - 1, cs.size()};
+            if (!cs) {
+                cs = buffer();
+                if (!cs) return false;
+                ncs = 0;
+            }
+            Sweep rec{m, m - 1, ncs};
             int64_t i = m - 1;
             bool underflow = false;
             for (; i >= l; --i) {
@@ -341,8 +346,9 @@ bool tridiag_ql(double *dg, double *e, int64_t n, int batch, const ApplyRotation
                 p = s * r;
                 dg[i + 1] = g + p;
                 g = c * r - b;
-                cs.push_back(c);
-                cs.push_back(s);
+                cs[ncs] = c;
+                cs[ncs + 1] = s;
+                ncs += 2;
                 rec.lo = i;
             }
             if (rec.lo <= rec.hi) sw.push_back(rec);
@@ -352,13 +358,13 @@ bool tridiag_ql(double *dg, double *e, int64_t n, int batch, const ApplyRotation
                 e[m] = 0.0;
             }
             if (int(sw.size()) >= batch) {
-                apply(sw, cs);
+                apply(sw, cs, ncs);
                 sw.clear();
-                cs.clear();
+                cs = nullptr;
             }
         }
     }
-    if (!sw.empty()) apply(sw, cs);
+    if (!sw.empty()) apply(sw, cs, ncs);
     return true;
 }
 
@@ -404,9 +410,11 @@ extern "C" int lpd_whiten_host(const float *L_host, int64_t B, int64_t d, int64_
     say("QL iteration");
     {
         double *zt = Zt.data();
-        auto apply = [&](const std::vector<Sweep> &sw, const std::vector<double> &cs) { apply_rotations(zt, n, sw, cs); };
+        std::vector<double> store(size_t(32) * 2 * size_t(n));
+        auto buffer = [&]() { return store.data(); };
+        auto apply = [&](const std::vector<Sweep> &sw, const double *cs, size_t) { apply_rotations(zt, n, sw, cs); };
         auto prog = [&](int64_t l) { progress("QL iteration", l, n); };
-        if (!lpd_host::tridiag_ql(dg.data(), e.data(), n, 32, apply, prog)) return LPD_ERR_NUMERIC;
+        if (!lpd_host::tridiag_ql(dg.data(), e.data(), n, 32, buffer, apply, prog)) return LPD_ERR_NUMERIC;
     }
     say("back-transformation");
     back_transform(A.data(), tau.data(), n, Zt.data());

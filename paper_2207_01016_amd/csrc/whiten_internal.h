@@ -13,14 +13,18 @@ namespace lpd_host {
 // their (c, s) pairs sit at cs[off + 2*(hi - i)].
 struct Sweep { int64_t lo, hi; size_t off; };
 
-using ApplyRotations = std::function<void(const std::vector<Sweep> &, const std::vector<double> &)>;
+// The caller supplies the storage the (c, s) pairs of a batch are written to: `buffer` returns room for
+// batch * 2 * n doubles (it may block until such a buffer is free again); `apply` then gets the sweeps of the
+// batch, that same pointer and the number of doubles written.
+using RotationBuffer = std::function<double *()>;
+using ApplyRotations = std::function<void(const std::vector<Sweep> &, const double *, size_t)>;
 
 // Eigenvalues of the symmetric tridiagonal matrix (dg, e; e[j] couples j and j+1) into dg.  Every
 // `batch` sweeps the recorded rotations are passed to `apply`, in order, and forgotten.  `progress`
 // (may be empty) is called with the number of eigenvalues found so far.  False if an eigenvalue
-// needs more than 60 sweeps.
-bool tridiag_ql(double *dg, double *e, int64_t n, int batch, const ApplyRotations &apply,
-                const std::function<void(int64_t)> &progress);
+// needs more than 60 sweeps or `buffer` returns NULL.
+bool tridiag_ql(double *dg, double *e, int64_t n, int batch, const RotationBuffer &buffer,
+                const ApplyRotations &apply, const std::function<void(int64_t)> &progress);
 
 // Descending order of the eigenvalues (stable) and the number r of leading ones that are positive and
 // at least clip_ratio times the largest (step 1c).  eig_sorted may be NULL.

@@ -32,6 +32,8 @@ HBM_PEAK_GBPS = 8000.0
 MEASURED_TRAFFIC = {
     # profiles/factor_and_sweep_cnn_hbm_traffic.txt: FETCH_SIZE 1.5676e6 KiB x 2.0 + WRITE_SIZE 2.6089e5 KiB x 1.0
     "cnn": 1.5676e6 * 1024 * 2.0 + 2.6089e5 * 1024 * 1.0,
+    # profiles/factor_and_sweep_highrank_hbm_traffic.txt: FETCH_SIZE 3.1444e6 KiB x 2.0 + WRITE_SIZE 2.6176e5 KiB x 1.0
+    "highrank": 3.1444e6 * 1024 * 2.0 + 2.6176e5 * 1024 * 1.0,
 }
 
 
@@ -40,7 +42,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="cnn", choices=["tiny", "small", "digit", "cnn", "highrank"])
+    ap.add_argument("--workload", default=None, choices=["tiny", "small", "digit", "cnn", "highrank"],
+                    help="default: highrank for the factor path (the largest configuration that fits one GPU), "
+                         "cnn for predict and whiten, digit for stream and sparse")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", default="auto", choices=["auto", "128x128", "256x128", "256x256"])
@@ -60,7 +64,11 @@ def parse_args():
     ap.add_argument("--chunk-rows", type=int, default=0, help="stream: rows per chunk (0 = the library's suggestion)")
     ap.add_argument("--random-w", action="store_true",
                     help="skip the host eigendecomposition and use a random W (tuning only; marks the line invalid)")
-    return ap.parse_args()
+    args = ap.parse_args()
+    if args.workload is None:
+        args.workload = {"factor": "highrank", "predict": "cnn", "whiten": "cnn", "stream": "digit", "sparse": "digit",
+                         "solver": "small"}[args.path]
+    return args
 
 
 def whiten(args, lpd, L, gamma):
@@ -503,8 +511,6 @@ def main():
         bench_whiten(args)
         return
     if args.path == "sparse":
-        if args.workload == "cnn":
-            args.workload = "digit"            # the recipe with 80 % zeros
         bench_sparse(args)
         return
     dev = torch.device("cuda:0")

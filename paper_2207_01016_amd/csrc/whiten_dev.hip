@@ -759,7 +759,7 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
                 hipLaunchKernelGGL(rowfix_kernel, dim3((n - j + 255) / 256), dim3(256), 0, s, A, n, j, i, Vp, Wp, xrow);
                 hipLaunchKernelGGL(hh_kernel, dim3(1), dim3(1024), 0, s, A, n, j, xrow, vi, dg_d, e_d, tau_d);
                 const int rows = n - j - 1;
-                const int row_blocks = std::min(2048, even ? ((rows + 1) / 2 + 3) / 4 : (rows + 3) / 4);
+                const int row_blocks = std::min(512, even ? ((rows + 1) / 2 + 3) / 4 : (rows + 3) / 4);
                 if (even)
                     hipLaunchKernelGGL((symv_kernel<true>), dim3(row_blocks + i), dim3(256), 0, s, A, n, j, row_blocks,
                                        vi, y, Vp, Wp, coef);

@@ -607,7 +607,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const double *__restrict__ 
     besti[threadIdx.x] = bi;
     __syncthreads();
     for (int off = 128; off > 0; off >>= 1) {
-        if (threadIdx.x < off) {
+        if (int(threadIdx.x) < off) {
             const double ov = bestv[threadIdx.x + off];
             const int oi = besti[threadIdx.x + off];
             if (ov > bestv[threadIdx.x] || (ov == bestv[threadIdx.x] && oi < besti[threadIdx.x])) {

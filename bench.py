@@ -587,7 +587,9 @@ def main():
         "dtype": "f32",
         "data": "synthetic" + (" (random W: tuning run, not a valid measurement)" if args.random_w else ""),
         "config": {"workload": wl.name, "n": wl.n, "d": wl.d, "B": wl.B, "rank": rank, "gamma": wl.gamma,
-                   "panel_rows": records[0][0].panel_rows if records else None, "gemm_tile": args.tile},
+                   "panel_rows": records[0][0].panel_rows if records else None, "gemm_tile": args.tile,
+                   "choice": "largest of BASELINE.json's five configurations (all fit one GPU, its metric names none)"
+                             if wl.name == "highrank" else "selected with --workload"},
         "factor": {"ms_per_step": ms_factor / steps, "rows_per_s": wl.n * steps / (ms_factor * 1e-3),
                    "tflops": factor_tflops, "frac_of_fp32_mfma_peak": factor_tflops / FP32_MFMA_PEAK_TFLOPS,
                    "ms_kernel_block": ms_kb / steps, "ms_whiten": ms_whiten / steps, "ms_norms": ms_norms / steps},

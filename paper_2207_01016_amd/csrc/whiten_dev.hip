@@ -351,11 +351,13 @@ __global__ __launch_bounds__(256) void panel_gram_kernel(const double *__restric
 }
 
 // T of the compact form H_k0 ... H_{k0+nb-1} = I - V T V^T (upper triangular), from the summed Gram matrix.
-__global__ __launch_bounds__(64) void panel_t_kernel(const double *__restrict__ P, int nchunks, int k0, int nb,
-                                                     const double *__restrict__ tau, double *__restrict__ T)
+__global__ __launch_bounds__(NB * NB) void panel_t_kernel(const double *__restrict__ P, int nchunks, int k0, int nb,
+                                                          const double *__restrict__ tau, double *__restrict__ T)
 {
     __shared__ double gm[NB][NB + 1], ts[NB][NB + 1];
-    for (int e = threadIdx.x; e < NB * NB; e += 64) {
+    {
+        // one thread per entry of the Gram matrix, chunks added in order
+        const int e = threadIdx.x;
         double s = 0.0;
         for (int ch = 0; ch < nchunks; ++ch) s += P[int64_t(ch) * NB * NB + e];
         gm[e / NB][e % NB] = s;
@@ -374,7 +376,7 @@ __global__ __launch_bounds__(64) void panel_t_kernel(const double *__restrict__ 
         }
         __syncthreads();
     }
-    for (int e = threadIdx.x; e < NB * NB; e += 64) T[e] = ts[e / NB][e % NB];
+    T[threadIdx.x] = ts[threadIdx.x / NB][threadIdx.x % NB];
 }
 
 // Rows r0.. of Zt times the panel: row <- row (I - V T^T V^T), 16 rows per workgroup.  Both passes over the
@@ -797,7 +799,7 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
             const int nb = std::min(NB, nref - k0);
             const int nchunks = (n - (k0 + 1) + 127) / 128;
             hipLaunchKernelGGL(panel_gram_kernel, dim3(nchunks), dim3(256), 0, s, A, n, k0, nb, P);
-            hipLaunchKernelGGL(panel_t_kernel, dim3(1), dim3(64), 0, s, P, nchunks, k0, nb, tau_d, T);
+            hipLaunchKernelGGL(panel_t_kernel, dim3(1), dim3(NB * NB), 0, s, P, nchunks, k0, nb, tau_d, T);
             // rows up to k0 are still unit vectors with nothing in the columns this panel touches
             const int r0 = k0 + 1;
             const int nblk = (n - r0 + 15) / 16;

@@ -91,13 +91,11 @@ hipError_t launch_one(GemmArgs a, hipStream_t s)
 {
     constexpr size_t lds = gemm_lds_bytes<BM, BN>();
     auto kern = gemm_nt_kernel<BM, BN, WGM, WGN, ALIGNED, EPI, PIPE>;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    // once per instantiation (initialisation of a function-local static is thread-safe): these kernels use
+    // more dynamic LDS than the default limit
+    static const hipError_t configured = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+    if (configured != hipSuccess) return configured;
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n = (a.n_store + BN - 1) / BN;
     const int64_t wgs = int64_t(a.tiles_m) * a.tiles_n;

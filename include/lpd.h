@@ -10,7 +10,7 @@
  *
  * plus the one-off host preparation of steps 1a-1c (landmark kernel matrix,
  * symmetric eigendecomposition, inverse-square-root factor with small
- * components dropped, Section 3).
+ * components dropped, Section 4).
  *
  * Symbols.  The paper calls the B x B factor of step 1c "L = U sqrt(D^-1)" and
  * sets G = Z L.  This interface stores its transpose W = sqrt(D^-1) U^T, one
@@ -78,18 +78,18 @@ typedef enum { LPD_OPT_GEMM_TILE = 1, LPD_OPT_GEMM_PIPELINE = 2, LPD_OPT_CSR_ROU
 int lpd_set_option(int option, int64_t value);
 
 /*
- * Host preparation, Figure 1 steps 1a-1c with the dropping rule of Section 3
+ * Host preparation, Figure 1 steps 1a-1c with the dropping rule of Section 4
  * (second bullet).  Runs on the calling host in double precision, blocking.
  *
- *   K_LL[a,b] = exp(-gamma ||l_a - l_b||^2)                        (1a, Section 4 kernel)
+ *   K_LL[a,b] = exp(-gamma ||l_a - l_b||^2)                        (1a, Section 5 kernel)
  *   K_LL = U D U^T, eigenvalues sorted descending                  (1b)
  *   r = #{ j : D_j >= clip_ratio * D_0 and D_j > 0 }
  *   W[j,:] = D_j^-1/2 u_j^T  for j < r, rows r..B-1 are zero       (1c)
  *
  * Each kept eigenvector's sign makes its largest-magnitude entry positive
- * (first such entry on ties).  The paper leaves the threshold open ("close to
- * machine precision times the largest eigenvalue"); callers pass it, 1e-10 in
- * this project's workloads.
+ * (first such entry on ties).  Section 4 (second bullet) ties the threshold to
+ * machine precision relative to the largest eigenvalue and names no constant;
+ * callers pass it, 1e-10 in this project's workloads.
  *
  *   L_host   in   B x d landmarks, leading dimension ldl
  *   W_host   out  B x B, leading dimension ldw
@@ -145,7 +145,7 @@ int lpd_nystrom_factor_workspace(int64_t n, int64_t d, int64_t B,
 /*
  * Figure 1 step 1d on the device:  G[i, j] = sum_b W[j,b] * Z[i,b]  for j < r,
  * G[i, j] = 0 for r <= j < B, with Z[i,b] = exp(-gamma ||x_i - l_b||^2)
- * (Gaussian kernel of Section 4).  The n x B block Z is produced panel by
+ * (Gaussian kernel of Section 5).  The n x B block Z is produced panel by
  * panel into the workspace and consumed at once; it never exists as a whole.
  *
  *   X  device in   n x d, ldx          L  device in   B x d, ldl
@@ -183,7 +183,7 @@ int lpd_nystrom_factor_profiled(const float *X, int64_t n, int64_t d, int64_t ld
 
 /*
  * Streaming form of step 1d for a factor that fits host memory but not device
- * memory (Section 3, "Algorithm Overview": every stage must be able to work in
+ * memory (Section 4, "Algorithm Overview": every stage must be able to work in
  * chunks).  X, L and W stay on the device; G is produced chunk_rows rows at a
  * time into one of two device chunk buffers and copied to G_host on a second
  * stream of default priority while the next chunk is computed, so the copy
@@ -265,7 +265,7 @@ int lpd_predict_csr(const int64_t *row_ptr, const int32_t *col_idx, const float 
                     void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * The kernel block alone (Figure 1 steps 1a / 1d, Section 4 kernel):
+ * The kernel block alone (Figure 1 steps 1a / 1d, Section 5 kernel):
  * Z[i,b] = exp(-gamma ||x_i - l_b||^2), written in full to device memory.
  * With X = L this is the landmark kernel matrix K_LL of step 1a.
  *
@@ -288,7 +288,7 @@ int lpd_margins(const float *G, int64_t n, int64_t r, int64_t ldg,
 
 /*
  * Step 2a over a subset of rows, as the solver's shrinking re-check and
- * cross-validation folds need it (Section 3, "Shrinking" and
+ * cross-validation folds need it (Section 4, "Shrinking" and
  * "Cross Validation"):  m[t] = sum_{j<r} G[rows[t], j] * w[j],  t < n_rows.
  *
  *   rows device in  n_rows int64 indices, each in [0, n)  (not checked on the device)
@@ -299,7 +299,7 @@ int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg,
 
 /*
  * Step 2a for several weight vectors that share G (the classifiers of a C grid, of the folds, of the
- * class pairs; Section 3):  M[i, q] = sum_{j<r} G[i,j] * Ws[q,j],  q < k.
+ * class pairs; Section 4):  M[i, q] = sum_{j<r} G[i,j] * Ws[q,j],  q < k.
  * Up to 8 vectors are served by one bandwidth-bound pass over G, more by the MFMA product G Ws^T.
  *   G device in n x r (ldg);  Ws device in k x r (ldws), one vector per row;  M device out n x k (ldm)
  * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE, LPD_ERR_LD, LPD_ERR_HIP.
@@ -309,7 +309,7 @@ int lpd_margins_multi(const float *G, int64_t n, int64_t r, int64_t ldg,
                       float *M, int64_t ldm, void *hip_stream);
 
 /*
- * Prediction (Section 3, "Algorithm Overview": the prediction step; Section 2: f(x) = <w, phi(x)>,
+ * Prediction (Section 4, "Algorithm Overview": the prediction step; Section 2: f(x) = <w, phi(x)>,
  * no offset).  A classifier trained on the rows of G has weights ws (r values); a new point x has
  * features W z(x), z(x)_b = exp(-gamma ||x - l_b||^2), so its score is ws . (W z(x)) = v . z(x) with
  * v = W^T ws folded once per classifier.
@@ -356,16 +356,16 @@ int lpd_cd_solve_workspace(int64_t n_problems, int64_t total_rows, size_t *bytes
 /*
  * Stage 2 of the method on the device: dual coordinate ascent with shrinking on
  * the rows of G, for a batch of independent binary problems that share G (grid
- * search over C, cross-validation folds, one-versus-one pairs; Section 3).
+ * search over C, cross-validation folds, one-versus-one pairs; Section 4).
  * Per problem p (Section 2, equation (2); Figure 1 steps 2a-2b):
  *
  *   maximise sum_t alpha_t - 1/2 ||w||^2,  0 <= alpha_t <= C[p],
  *   w = sum_t alpha_t y_t g_{rows[t]},   t over the problem's listed rows;
  *   step on t: f = g.w;  alpha_t <- clip(alpha_t + (1 - y_t f)/||g||^2, 0, C);  w += d_alpha y_t g.
  *
- * Order, shrinking and stopping (the paper fixes k = 5 and eta = 5 % and leaves
- * the stopping rule as "similar to LIBLINEAR"; this reading is shared with the
- * CPU oracle): round-robin over the active list, initially the listed order; a
+ * Order, shrinking and stopping (Section 4, "Shrinking", fixes k = 5 and
+ * eta = 5 %; the third bullet of the comparison with LLSVM in Section 4 names a
+ * standard stopping criterion without spelling it out; the reading is this): round-robin over the active list, initially the listed order; a
  * variable whose step left alpha bit-for-bit unchanged shrink_k times in a row is
  * removed; after every round((1-eta)/eta) active steps one step is spent on the
  * oldest removed variable, which rejoins if the step changes it; when an epoch's

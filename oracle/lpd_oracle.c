@@ -3,19 +3,19 @@
  *
  * A plain, slow, double-precision CPU statement of what the low-rank stage of
  * the LPD-SVM method (Glasmachers, "Recipe for Fast Large-scale SVM Training",
- * Section 3, Figure 1) computes.  Every function is the definition written
+ * Section 4, Figure 1) computes.  Every function is the definition written
  * out: no blocking, no fusion, no algebraic expansion of the distance, no BLAS.
  * Nothing in the HIP library shares code with this file, and only tests, the
  * smoke check and the CPU-baseline leg of the benchmark may call it.
  *
- * Notation (Figure 1, steps 1a-1d and 2a; Section 4 for the kernel):
+ * Notation (Figure 1, steps 1a-1d and 2a; Section 5 for the kernel):
  *   landmarks      : B rows of the training set (the "random subset" of 1a)
  *   K_LL  (B x B)  : Gaussian kernel matrix on the landmarks            (1a)
  *   K_LL = U D U^T : symmetric eigendecomposition                       (1b)
  *   U sqrt(D^-1)   : factor of the inverse kernel matrix                (1c)
  *   W (r x B)      : its transpose, W[j,:] = D_j^-1/2 u_j^T -- row j is one
  *                    whitened direction; components whose eigenvalue is below
- *                    tau * D_max are dropped (Section 3, second bullet)
+ *                    tau * D_max are dropped (Section 4, second bullet)
  *   Z (n x B)      : Gaussian kernel between all points and the landmarks (1d)
  *   G = Z W^T      : the low-rank factor, G G^T ~ K                     (1d)
  *   m_i = G_i w    : the margin the coordinate-ascent solver evaluates  (2a)
@@ -38,7 +38,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-/* Section 4: k(x, x') = exp(-gamma * ||x - x'||^2), by direct differences. */
+/* Section 5: k(x, x') = exp(-gamma * ||x - x'||^2), by direct differences. */
 static double gauss_kernel(const float *x, const float *y, int64_t d, double gamma)
 {
     double s = 0.0;
@@ -62,8 +62,9 @@ void orc_kernel_block(const float *X, int64_t n, int64_t d, int64_t ldx,
             Z[i * B + b] = gauss_kernel(X + i * ldx, L + b * ldl, d, gamma);
 }
 
-/* The kernel block for sparse inputs (Section 4, "we implemented all kernel
- * operations based on efficient sparse matrix products"): row i of X is given
+/* The kernel block for sparse inputs (Section 4, "Multi-core and GPU
+ * Implementation": every kernel operation of the method also runs on sparse
+ * data, through sparse matrix products): row i of X is given
  * in compressed-row form, entries row_ptr[i] .. row_ptr[i+1]-1 of (col_idx,
  * values), every other coordinate zero; column indices of a row are distinct,
  * in any order.  The kernel value is that of the vector so described:
@@ -144,7 +145,7 @@ int orc_jacobi_eigh(double *A, int64_t B, double *V, double *ev)
     return sweep < 60 ? sweep : -1;
 }
 
-/* Figure 1, step 1c with the dropping rule of Section 3 (second bullet):
+/* Figure 1, step 1c with the dropping rule of Section 4 (second bullet):
  * given eigenpairs (ev[j], column j of V), order them by descending
  * eigenvalue, keep those with ev >= tau * ev_max, fix each kept vector's sign
  * so that its largest-magnitude entry is positive (first such entry on ties),
@@ -259,7 +260,7 @@ void orc_set_num_threads(int t) { (void)t; }
 /* ------------------------------------------------------------------------
  * Stage 2: dual coordinate ascent on the linear problem whose data points are
  * the rows of G (Section 2, equation (2) and the truncated Newton step;
- * Section 3, "Shrinking"; Figure 1 steps 2a-2b).
+ * Section 4, "Shrinking"; Figure 1 steps 2a-2b).
  *
  *   maximise  D(alpha) = sum_i alpha_i - 1/2 ||w||^2,   0 <= alpha_i <= C,
  *   w = sum_i alpha_i y_i g_i,   Q_ij = y_i y_j g_i . g_j
@@ -269,9 +270,11 @@ void orc_set_num_threads(int t) { (void)t; }
  *   w <- w + (alpha_new - alpha_old) y_i g_i.
  * A row with Q_ii = 0 cannot change w; its alpha goes to C (grad = 1 > 0).
  *
- * The paper fixes k = 5 and eta = 5 % for shrinking and names the stopping rule
- * only as "standard, similar to LIBLINEAR"; the reading implemented here, step
- * for step the same as the GPU solver's:
+ * Section 4, "Shrinking", fixes k = 5 and eta = 5 % and says no more about how
+ * the eta share is spent; the stopping criterion is named (Section 4, third
+ * point of the comparison with LLSVM) as a standard one of the kind the
+ * linear-SVM dual solvers use, and not spelled out.  Where the text is silent
+ * this file takes the plainest sequential reading:
  *   - variables are visited round-robin in the order of the active list, which
  *     starts as the caller's order; an epoch is one pass over that list;
  *   - a variable whose step left alpha exactly unchanged k times in a row is
@@ -283,12 +286,18 @@ void orc_set_num_threads(int t) { (void)t; }
  *     goes into re-checking removed variables;
  *   - KKT violation of a variable, measured before its step: max(grad, 0) at
  *     alpha = 0, max(-grad, 0) at alpha = C, |grad| inside;
- *   - when the largest violation seen in an epoch is <= eps, w is recomputed
- *     from alpha and all removed variables are checked with that w (a margin
- *     sweep over their rows); those violating by more than eps are reactivated;
- *     the solver stops when there are none and the epoch itself had started
- *     from a recomputed w (so every variable was verified against a w free of
- *     the rounding drift of the incremental updates).
+ *   - stopping, in two parts as in the dual linear solvers the paper points to
+ *     (criterion met on the shrunk problem, then confirmed on the whole one):
+ *     when the largest violation seen in an epoch is <= eps, w is set to its
+ *     definition sum_i alpha_i y_i g_i and all removed variables are checked
+ *     with that w (a margin sweep over their rows, step 2a); those violating by
+ *     more than eps are reactivated.  The solver stops when there are none AND
+ *     the epoch that met the criterion had itself started from such a w, i.e.
+ *     the criterion is confirmed by one whole epoch in which every active
+ *     variable was measured against w = sum alpha y g and not against the sum
+ *     of all increments since the start.  The first epoch qualifies (the start
+ *     w is computed from the start alpha).  In exact arithmetic the confirming
+ *     epoch changes nothing but costs its steps; they are counted.
  *
  * G: fp32 factor (ldg), rows/y: the problem's np variables in visiting order,
  * alpha: in (warm start) / out, w: out (r doubles).  stats (6 doubles): epochs,
@@ -434,7 +443,7 @@ void orc_cd_solve(const float *G, int64_t r, int64_t ldg,
 }
 
 /* ------------------------------------------------------------------------
- * Prediction (Section 3, "Algorithm Overview": the prediction step; Section 2:
+ * Prediction (Section 4, "Algorithm Overview": the prediction step; Section 2:
  * f(x) = <w, phi(x)>, no offset).  In the low-rank feature space the features of
  * a new point x are g(x) = W z(x), z(x)_b = k(x, l_b) -- the same map that
  * produced the rows of G (Figure 1, 1d) -- and classifier j scores it with

@@ -9,7 +9,7 @@ eigendecomposition of step 1b (Figure 1) is LAPACK's, through
 code either way.
 
 Notation follows Figure 1 of the paper: K_LL (1a), K_LL = U D U^T (1b),
-W = (U sqrt(D^-1))^T with small components dropped (1c and Section 3),
+W = (U sqrt(D^-1))^T with small components dropped (1c and Section 4),
 Z and G = Z W^T (1d), m = G w (2a).
 """
 from __future__ import annotations
@@ -102,7 +102,7 @@ def set_num_threads(t: int) -> None:
 
 
 def kernel_block(X, L, gamma: float) -> np.ndarray:
-    """Z[i,b] = exp(-gamma ||x_i - l_b||^2) (Section 4 kernel; Figure 1 steps 1a/1d)."""
+    """Z[i,b] = exp(-gamma ||x_i - l_b||^2) (Section 5 kernel; Figure 1 steps 1a/1d)."""
     X, L = _f32(X), _f32(L)
     n, d = X.shape
     B, d2 = L.shape
@@ -143,6 +143,20 @@ def jacobi_eigh(K):
     return ev, V
 
 
+def check_eigendecomposition(K, ev, V, tol: float = 1e-12) -> None:
+    """Accept a library eigendecomposition K = V diag(ev) V^T (Figure 1 step 1b) only if it reproduces K and V is
+    orthogonal: ||K - V diag(ev) V^T||_F <= tol ||K||_F and ||V^T V - I||_F <= tol B.  Raises otherwise."""
+    K, ev, V = _f64(K), _f64(ev), _f64(V)
+    B = K.shape[0]
+    if B == 0:
+        return
+    res = np.linalg.norm(K - (V * ev) @ V.T) / max(np.linalg.norm(K), np.finfo(np.float64).tiny)
+    orth = np.linalg.norm(V.T @ V - np.eye(B))
+    if not (res <= tol) or not (orth <= tol * B):
+        raise RuntimeError(f"library eigendecomposition rejected: residual {res:.3e} (bound {tol:.1e}), "
+                           f"orthogonality {orth:.3e} (bound {tol * B:.1e})")
+
+
 def whiten(L, gamma: float, tau: float = 1e-10, method: str = "auto"):
     """Steps 1a-1c: returns (W float64 BxB with rows >= rank zero, eig descending, rank, K_LL)."""
     L = _f32(L)
@@ -154,6 +168,7 @@ def whiten(L, gamma: float, tau: float = 1e-10, method: str = "auto"):
         ev, V = jacobi_eigh(K)
     elif method == "lapack":
         ev, V = np.linalg.eigh(K)
+        check_eigendecomposition(K, ev, V)
     else:
         raise ValueError(method)
     V = _f64(V)
@@ -211,7 +226,7 @@ def margins_f64(G, w) -> np.ndarray:
 
 def cd_solve(G, rows, y, C: float, eps: float = 1e-3, max_epochs: int = 1000, shrink_k: int = 5, eta: float = 0.05,
              alpha0=None, r: int | None = None):
-    """Dual coordinate ascent with shrinking on the rows of G (Figure 1 steps 2a-2b; Section 3 "Shrinking").
+    """Dual coordinate ascent with shrinking on the rows of G (Figure 1 steps 2a-2b; Section 4 "Shrinking").
 
     G: fp32 factor; rows: the problem's row indices in visiting order; y: +-1 per listed row.
     Returns (alpha float64 per listed row, w float64 (r), stats dict)."""
@@ -231,7 +246,7 @@ def cd_solve(G, rows, y, C: float, eps: float = 1e-3, max_epochs: int = 1000, sh
 
 
 def predict(X, L, gamma: float, W, Ws, r: int | None = None) -> np.ndarray:
-    """Scores f_j(x_i) = ws_j . (W z(x_i)) of c classifiers (Section 3 prediction step). Ws: c x r. Returns n x c."""
+    """Scores f_j(x_i) = ws_j . (W z(x_i)) of c classifiers (Section 4 prediction step). Ws: c x r. Returns n x c."""
     X, L, W = _f32(X), _f32(L), _f32(W)
     Ws = np.atleast_2d(_f32(Ws))
     n, d = X.shape

@@ -1,6 +1,6 @@
 // Dual coordinate ascent with shrinking on the rows of the factor G, many
 // independent binary problems at once (Section 2, equation (2) and the truncated
-// Newton step; Section 3, "Shrinking"; Figure 1 steps 2a-2b).
+// Newton step; Section 4, "Shrinking"; Figure 1 steps 2a-2b).
 //
 //   maximise  sum_i alpha_i - 1/2 ||w||^2,  0 <= alpha_i <= C,  w = sum_i alpha_i y_i g_i
 //   step on i:  f = g_i . w (2a);  alpha_i <- clip(alpha_i + (1 - y_i f) / ||g_i||^2, 0, C);
@@ -24,9 +24,9 @@
 //     leaves the same bits in all lanes), so control flow is uniform; one lane
 //     writes alpha, counters and the lists.
 //
-// Shrinking and stopping rule (the paper fixes k = 5, eta = 5 % and calls the
-// stopping rule "similar to LIBLINEAR"); this is the reading the CPU oracle
-// implements step for step:
+// Shrinking and stopping rule (Section 4, "Shrinking", fixes k = 5 and eta = 5 %;
+// the stopping criterion is named there as a standard one and not spelled out).
+// The reading implemented here:
 //   - round-robin over the active list (initially the caller's order), one pass
 //     = one epoch; a variable whose step left alpha bit-for-bit unchanged k times
 //     in a row moves to a FIFO queue of removed variables;

@@ -1,6 +1,6 @@
 // Bandwidth-bound row kernels for gfx950:
 //   margins_kernel    m[t] = sum_j G[row(t), j] * w[j]      (Figure 1 step 2a, all rows or a row list)
-//   sqnorm_kernel     s[i] = sum_k X[i,k]^2                  (the ||x||^2 terms of the Gaussian kernel, Section 4)
+//   sqnorm_kernel     s[i] = sum_k X[i,k]^2                  (the ||x||^2 terms of the Gaussian kernel, Section 5)
 //
 // A row is spread over LPR lanes of a wavefront (LPR = 64 for long rows down to
 // 8 for short ones, so narrow factors still fill every lane); each lane streams
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256) void sqnorm_kernel(const float *__restrict__ X
 
 // M[i, q] = sum_j G[i, j] * Ws[q, j] for a handful of weight vectors at once (K <= 8): one pass over G
 // serves all of them (the sweep the solver's callers run for several classifiers that share G: C grid,
-// folds, class pairs; Section 3).  A wavefront takes ROWS rows at a time: every 16-byte piece of a weight
+// folds, class pairs; Section 4).  A wavefront takes ROWS rows at a time: every 16-byte piece of a weight
 // vector it reads (through the cache) is used for all of them, so the cache traffic per byte of G falls
 // with ROWS; G itself comes in 16-byte non-temporal loads; K * ROWS butterflies end a group of rows.  A
 // group past the end re-reads the last row and drops the result.
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(256) void margins_multi_kernel(const float *__restr
 }
 
 // V[j, b] = sum_k Ws[j, k] * W[k, b]: classifier weights folded through the whitening map, so that a
-// score becomes one inner product with the kernel row, f_j(x) = V_j . z(x) (Section 3, prediction step).
+// score becomes one inner product with the kernel row, f_j(x) = V_j . z(x) (Section 4, prediction step).
 // One thread per column b of W, CPT classifiers per pass held in registers; W is streamed once per
 // pass with coalesced rows, the CPT weights of row k are broadcast loads.
 template <int CPT>

@@ -1,4 +1,4 @@
-// Stage-1 preparation on the device (Figure 1 steps 1a-1c, Section 3): landmark kernel matrix,
+// Stage-1 preparation on the device (Figure 1 steps 1a-1c, Section 4): landmark kernel matrix,
 // symmetric eigendecomposition and the whitening factor W = Lambda^{-1/2} U^T, in double precision,
 // for gfx950.  All O(B^3) work runs in the kernels below; the host keeps only the serial scalar part,
 // the implicit-shift QL iteration on the tridiagonal matrix (O(B^2)), and overlaps it with the device.

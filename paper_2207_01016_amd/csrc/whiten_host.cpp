@@ -1,4 +1,4 @@
-// Host preparation of the low-rank stage (Figure 1 steps 1a-1c, Section 3):
+// Host preparation of the low-rank stage (Figure 1 steps 1a-1c, Section 4):
 // landmark kernel matrix, symmetric eigendecomposition, inverse-square-root
 // factor with small components dropped.  Double precision, OpenMP, no external
 // numerical library.

@@ -1,4 +1,4 @@
-"""Seeded synthetic inputs shaped like the paper's workloads (Section 4, Table 1).
+"""Seeded synthetic inputs shaped like the paper's workloads (Section 5, Table 1).
 
 This module only draws numbers: it holds none of the method's arithmetic (no
 kernel, no eigendecomposition, no products) and imports neither the HIP

@@ -24,7 +24,7 @@ def _points(seed, n, d):
     return _rng(seed).standard_normal((n, d)).astype(np.float32)
 
 
-# ---------------------------------------------------------------- Section 4 kernel
+# ---------------------------------------------------------------- Section 5 kernel
 
 def test_kernel_two_point_hand_values(oracle):
     # d=1, x=0, x'=1, gamma=ln2 -> 1/2 ; d=3 with squared distance 9, gamma=0.1 -> exp(-0.9)
@@ -79,6 +79,65 @@ def test_jacobi_against_lapack_and_residual(oracle):
 def test_jacobi_known_2x2(oracle):
     ev, V = oracle.jacobi_eigh(np.array([[1.0, 0.5], [0.5, 1.0]]))
     assert np.allclose(np.sort(ev), [0.5, 1.5], atol=1e-15)
+
+
+def test_library_eigendecomposition_path_above_the_jacobi_limit(oracle):
+    # 600 landmarks in 4 dimensions, above the size where the oracle hands step 1b to LAPACK.  The spectrum
+    # decays fast, so the dropping rule of Section 4 is active too.  What must hold whatever routine did 1b:
+    # the kept part reproduces the kernel matrix up to the dropped eigenvalues, W K W^T = I_r, trace = B.
+    from oracle import lpd_oracle
+    assert 600 > lpd_oracle.JACOBI_MAX_B
+    Lm = _points(21, 600, 4)
+    gamma, tau = 0.25, 1e-10
+    W, eig, rank, K = oracle.whiten(Lm, gamma, tau=tau)                  # "auto" -> LAPACK + self-check
+    assert 0 < rank < 600 and np.all(np.diff(eig) <= 0)
+    assert eig[rank - 1] >= tau * eig[0] > eig[rank]
+    assert abs(eig.sum() - 600.0) < 1e-9
+    Wr = W[:rank]
+    GL = oracle.apply_whitening(K, W, rank)                              # landmark rows of the factor: Z = K_LL
+    dropped = np.sqrt(np.sum(eig[rank:] ** 2))
+    assert np.linalg.norm(GL @ GL.T - K) <= dropped + 1e-9 * np.linalg.norm(K)
+    # W K W^T = I_r: the error of row j carries a factor 1 / eig_j of the eigenvector's own rounding
+    I_r = Wr @ K @ Wr.T
+    assert np.max(np.abs(I_r - np.eye(rank)) * np.sqrt(np.outer(eig[:rank], eig[:rank]))) < 1e-9
+    assert np.all(W[rank:] == 0.0)
+
+
+def test_library_and_jacobi_paths_agree(oracle):
+    # 300 landmarks, well-conditioned kernel matrix: both routes of step 1b must give the same eigenvalues, the
+    # same rank, and the same basis-independent quantities K~ = G_L G_L^T and W^T W (= K^-1 when nothing is dropped).
+    Lm = _points(22, 300, 16)
+    gamma = 1.0 / 16
+    Wj, ej, rj, K = oracle.whiten(Lm, gamma, method="jacobi")
+    Wl, el, rl, _ = oracle.whiten(Lm, gamma, method="lapack")
+    assert rj == rl == 300
+    assert np.max(np.abs(ej - el)) <= 1e-11 * ej[0]
+    Gj, Gl = oracle.apply_whitening(K, Wj), oracle.apply_whitening(K, Wl)
+    assert _relfro(Gj @ Gj.T, Gl @ Gl.T) < 1e-10 and _relfro(Gl @ Gl.T, K) < 1e-10
+    assert _relfro(Wj.T @ Wj, Wl.T @ Wl) < 1e-7
+    assert _relfro(Wl.T @ Wl, np.linalg.inv(K)) < 1e-7
+    # simple spectrum: the rows themselves agree, sign convention included
+    gaps = np.min(np.abs(np.diff(ej))) / ej[0]
+    if gaps > 1e-6:
+        assert np.max(np.abs(Wj - Wl) * np.sqrt(ej)[:, None]) < 1e-6
+
+
+def test_library_eigendecomposition_is_checked_before_use(oracle):
+    # a decomposition that does not reproduce K, or whose vectors are not orthonormal, must be refused
+    Lm = _points(23, 40, 5)
+    K = oracle.kernel_block(Lm, Lm, 0.3)
+    ev, V = np.linalg.eigh(K)
+    oracle.check_eigendecomposition(K, ev, V)
+    with pytest.raises(RuntimeError):
+        oracle.check_eigendecomposition(K, ev[::-1].copy(), V)           # values paired with the wrong vectors
+    V_bad = V.copy()
+    V_bad[:, 0] *= 1.0 + 1e-9                                            # not normalised
+    with pytest.raises(RuntimeError):
+        oracle.check_eigendecomposition(K, ev, V_bad)
+    V_rot = V.copy()
+    V_rot[:, 1] += 1e-8 * V[:, 0]                                        # not orthogonal
+    with pytest.raises(RuntimeError):
+        oracle.check_eigendecomposition(K, ev, V_rot)
 
 
 # ---------------------------------------------------------------- steps 1a-1d, closed form
@@ -265,7 +324,7 @@ def test_workload_recipes_keep_landmark_kernel_well_conditioned(oracle):
         assert eig[-1] > 1e-3, (name, eig[-1])
 
 
-# ---------------------------------------------------------------- prediction (Section 3, prediction step)
+# ---------------------------------------------------------------- prediction (Section 4, prediction step)
 
 def test_predict_closed_form_two_landmarks(oracle):
     rows, Wg, Dg = _read_golden()

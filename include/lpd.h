@@ -35,6 +35,25 @@
  *     Execution faults of an enqueued kernel surface at the caller's next
  *     synchronisation, launch failures are returned as LPD_ERR_HIP.
  *   - Inputs and outputs must not overlap.
+ *
+ * Accuracy of the kernel block.  The device evaluates the squared distance of
+ * the Gaussian kernel (Section 5) as ||x-c||^2 + ||l-c||^2 - 2 (x-c).(l-c) in
+ * fp32, with the origin c at the mean of (a sample of) the landmarks, so that a
+ * constant offset of the features costs no accuracy, and clamps it at 0.  Its
+ * rounding error grows with the spread of the data around c, not with the
+ * distance: |error of gamma * dist| <~ 2^-22 * gamma * (||x-c||^2 + ||l-c||^2),
+ * and the same relative error appears in Z[i,b].  Measured against double
+ * precision: 1e-7 relative Frobenius error of Z while gamma * ||x-c||^2 is of
+ * order 1 (all of this project's workloads, also with features offset by 30 or
+ * 1000 standard deviations, and 8-bit pixel values with gamma = 2^-22), 7e-6 for
+ * two clusters 60 standard deviations apart (gamma * ||x-c||^2 about 30), where
+ * the factor still meets its 1e-4.  Beyond gamma * ||x-c||^2 of about 1e2 for
+ * the bulk of the points the 1e-4 of the factor is no longer assured; such data
+ * has a kernel matrix close to the identity, and the fp32 factor degrades
+ * gradually, it does not fail.  Kernel arguments gamma * dist beyond about 87
+ * give exactly 0 in fp32 where double precision gives less than 1e-38.  The
+ * gather route of the compressed-row entry points keeps the origin at 0 (sparse
+ * rows stay sparse).
  */
 #ifndef LPD_H
 #define LPD_H
@@ -270,7 +289,9 @@ int lpd_predict_csr(const int64_t *row_ptr, const int32_t *col_idx, const float 
  * With X = L this is the landmark kernel matrix K_LL of step 1a.
  *
  *   X device in n x d, ldx;  L device in B x d, ldl;  Z device out n x B, ldz
- *   workspace: at least 4 * (n + B) bytes rounded up to 256 (row norms only).
+ *   workspace: 256-byte aligned, at least 4 n + 4 B + 4 d bytes with each of the three
+ *   terms rounded up to 256 (row norms and the origin, see "Accuracy" above); the
+ *   minimum lpd_nystrom_factor_workspace reports is always enough.
  */
 int lpd_kernel_block(const float *X, int64_t n, int64_t d, int64_t ldx,
                      const float *L, int64_t B, int64_t ldl,

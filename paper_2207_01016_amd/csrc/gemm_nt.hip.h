@@ -41,8 +41,12 @@ struct GemmArgs {
     int M, N, K;
     int n_store;     // columns [N, n_store) of C are written as zeros
     int tiles_m, tiles_n;
-    // EPI_GAUSS: C = exp2(scale * max(0, na[row] + nb[col] - 2 acc)), scale = -gamma * log2(e)
-    const float *na, *nb;
+    // EPI_GAUSS: C = exp2(scale * max(0, na[row] + nb[col] - 2 acc)), scale = -gamma * log2(e).
+    // Both operands are read as A[i,k] - cen[k], B[j,k] - cen[k] (cen: K floats, 16-byte aligned) and
+    // na, nb are the squared norms of the shifted rows: a distance does not depend on the origin, and
+    // with the origin inside the data the three terms of the expansion are of the size of the
+    // distance itself instead of the size of ||x||^2, which is what their fp32 rounding scales with.
+    const float *na, *nb, *cen;
     float scale;
 };
 
@@ -114,7 +118,9 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
         gb[q] = p.B + int64_t(rr) * p.ldb + lch * 4;
     }
 
-    f32x4 ra[PA], rb[PB];
+    // rc: the four centre values of this thread's k columns (all its rows share them).  They are loaded with
+    // the tile and subtracted on the way into LDS, so that nothing waits for a global load before it must.
+    f32x4 ra[PA], rb[PB], rc = {0.f, 0.f, 0.f, 0.f};
     auto gload = [&](int k0) {
         const int k = k0 + lch * 4;
         if (ALIGNED) {
@@ -123,11 +129,13 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                 for (int q = 0; q < PA; ++q) ra[q] = *reinterpret_cast<const f32x4 *>(ga[q] + k0);
 #pragma unroll
                 for (int q = 0; q < PB; ++q) rb[q] = *reinterpret_cast<const f32x4 *>(gb[q] + k0);
+                if (EPI == EPI_GAUSS) rc = *reinterpret_cast<const f32x4 *>(p.cen + k);
             } else {
 #pragma unroll
                 for (int q = 0; q < PA; ++q) ra[q] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int q = 0; q < PB; ++q) rb[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+                rc = f32x4{0.f, 0.f, 0.f, 0.f};
             }
         } else {
 #pragma unroll
@@ -138,6 +146,10 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
             for (int q = 0; q < PB; ++q)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) rb[q][e] = (k + e < p.K) ? gb[q][k0 + e] : 0.0f;
+            if (EPI == EPI_GAUSS) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rc[e] = (k + e < p.K) ? p.cen[k + e] : 0.0f;
+            }
         }
     };
     auto lstore = [&](int buf) {
@@ -145,10 +157,10 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
         float *Bs = As + BM * LDK;
 #pragma unroll
         for (int q = 0; q < PA; ++q)
-            *reinterpret_cast<f32x4 *>(&As[(lrow + q * RPP) * LDK + lch * 4]) = ra[q];
+            *reinterpret_cast<f32x4 *>(&As[(lrow + q * RPP) * LDK + lch * 4]) = EPI == EPI_GAUSS ? ra[q] - rc : ra[q];
 #pragma unroll
         for (int q = 0; q < PB; ++q)
-            *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) = rb[q];
+            *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) = EPI == EPI_GAUSS ? rb[q] - rc : rb[q];
     };
 
     f32x16 acc[TM][TN];
@@ -217,7 +229,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
         // barrier.  A partial last tile (K % 16 != 0) is handled after the loop by the plain schedule.
         static_assert(BK == 16, "the pipelined schedule assumes two chunks per tile");
         static_assert(ALIGNED, "the pipelined schedule is for the 16-byte aligned fast path");
-        constexpr int MEMOPS = TM + TN + PA + PB;
+        constexpr int MEMOPS = TM + TN + PA + PB + (EPI == EPI_GAUSS ? 1 : 0);   // + the load of the centre values
         constexpr int MPG = (4 * TM * TN) / MEMOPS > 0 ? (4 * TM * TN) / MEMOPS : 1;
         const int nfull = p.K / BK;
 
@@ -238,6 +250,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                 for (int q = 0; q < PA; ++q) ra[q] = *reinterpret_cast<const f32x4 *>(pa + oa[q]);
 #pragma unroll
                 for (int q = 0; q < PB; ++q) rb[q] = *reinterpret_cast<const f32x4 *>(pb + ob[q]);
+                if (EPI == EPI_GAUSS) rc = *reinterpret_cast<const f32x4 *>(p.cen + tile * BK + lch * 4);
             };
             f32x4 a0[TM], b0[TN], a1[TM], b1[TN];
             auto fetch = [&](f32x4(&a)[TM], f32x4(&b)[TN], int buf, int kc) {
@@ -287,7 +300,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                 fetch(a0, b0, cur ^ 1, 0);
                 mma(a1, b1);
 #pragma unroll
-                for (int g = 0; g < PA + PB; ++g) {
+                for (int g = 0; g < PA + PB + (EPI == EPI_GAUSS ? 1 : 0); ++g) {
                     __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
                     __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0);
                 }

@@ -33,17 +33,19 @@ inline int64_t panel_ld(int64_t B)
 }
 
 struct Carve {
-    size_t off_nx, off_nl, off_z, min_bytes, rec_bytes;
+    size_t off_nx, off_nl, off_cen, off_z, min_bytes, rec_bytes;
     int64_t ldz, rec_rows, min_rows;
 };
 
-Carve carve(int64_t n, int64_t B)
+// norms of X (n), norms of L (B), the origin of the kernel block (d), then the Z panel
+Carve carve(int64_t n, int64_t d, int64_t B)
 {
     Carve c;
     c.ldz = panel_ld(B);
     c.off_nx = 0;
     c.off_nl = round_up(size_t(n) * 4, kAlign);
-    c.off_z = c.off_nl + round_up(size_t(B) * 4, kAlign);
+    c.off_cen = c.off_nl + round_up(size_t(B) * 4, kAlign);
+    c.off_z = c.off_cen + round_up(size_t(d) * 4, kAlign);
     c.min_rows = std::min<int64_t>(n, 256);
     // recommended panel: about 64 Mi kernel values.  Rows = 64 Mi / B rounded to 256 makes the
     // 256x256 tile count of a panel a multiple of the 256 CUs whenever B is a power of two
@@ -60,11 +62,11 @@ Carve carve(int64_t n, int64_t B)
 // Workspace of the streaming factor: two device chunk buffers (chunk_rows x B, dense) followed by the
 // factor scratch of one chunk.
 struct StreamCarve { size_t buf_bytes, bytes; };
-StreamCarve stream_carve(int64_t chunk_rows, int64_t B)
+StreamCarve stream_carve(int64_t chunk_rows, int64_t d, int64_t B)
 {
     StreamCarve sc;
     sc.buf_bytes = round_up(size_t(chunk_rows) * size_t(B) * 4, kAlign);
-    sc.bytes = 2 * sc.buf_bytes + carve(chunk_rows, B).rec_bytes;
+    sc.bytes = 2 * sc.buf_bytes + carve(chunk_rows, d, B).rec_bytes;
     return sc;
 }
 
@@ -140,18 +142,36 @@ inline unsigned row_grid(int64_t rows, int groups, int64_t cap = 4096)
     return unsigned(std::max<int64_t>(1, std::min<int64_t>(need, cap)));
 }
 
-hipError_t launch_sqnorm(const float *X, int64_t n, int64_t d, int64_t ldx, float *out, hipStream_t s)
+// out[i] = ||X_i - cen||^2 (cen = nullptr: ||X_i||^2)
+hipError_t launch_sqnorm(const float *X, int64_t n, int64_t d, int64_t ldx, const float *cen, float *out, hipStream_t s)
 {
     if (n == 0) return hipSuccess;
     const bool vec = aligned16(X) && ldx % 4 == 0;
     if (d >= 256) {
-        if (vec) hipLaunchKernelGGL((sqnorm_kernel<64, true>), dim3(row_grid(n, 4)), dim3(256), 0, s, X, n, int(d), ldx, out);
-        else hipLaunchKernelGGL((sqnorm_kernel<64, false>), dim3(row_grid(n, 4)), dim3(256), 0, s, X, n, int(d), ldx, out);
+        if (vec) hipLaunchKernelGGL((sqnorm_kernel<64, true>), dim3(row_grid(n, 4)), dim3(256), 0, s, X, n, int(d), ldx, cen, out);
+        else hipLaunchKernelGGL((sqnorm_kernel<64, false>), dim3(row_grid(n, 4)), dim3(256), 0, s, X, n, int(d), ldx, cen, out);
     } else {
-        if (vec) hipLaunchKernelGGL((sqnorm_kernel<8, true>), dim3(row_grid(n, 32)), dim3(256), 0, s, X, n, int(d), ldx, out);
-        else hipLaunchKernelGGL((sqnorm_kernel<8, false>), dim3(row_grid(n, 32)), dim3(256), 0, s, X, n, int(d), ldx, out);
+        if (vec) hipLaunchKernelGGL((sqnorm_kernel<8, true>), dim3(row_grid(n, 32)), dim3(256), 0, s, X, n, int(d), ldx, cen, out);
+        else hipLaunchKernelGGL((sqnorm_kernel<8, false>), dim3(row_grid(n, 32)), dim3(256), 0, s, X, n, int(d), ldx, cen, out);
     }
     return hipGetLastError();
+}
+
+// The origin of the kernel block and the squared norms of X and L relative to it (see centre_kernel):
+// the mean of up to 256 landmark rows spread evenly over L.
+hipError_t launch_centred_norms(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B,
+                                int64_t ldl, float *cen, float *nx, float *nl, hipStream_t s)
+{
+    if (d > 0 && B > 0) {
+        const int rows = int(std::min<int64_t>(B, 256));
+        hipLaunchKernelGGL(centre_kernel, dim3(unsigned((d + 63) / 64)), dim3(256), 0, s, L, ldl, int(d), rows,
+                           B / rows, cen);
+        const hipError_t ec = hipGetLastError();
+        if (ec != hipSuccess) return ec;
+    }
+    hipError_t e = launch_sqnorm(X, n, d, ldx, cen, nx, s);
+    if (e != hipSuccess) return e;
+    return launch_sqnorm(L, B, d, ldl, cen, nl, s);
 }
 
 template <int LPR, bool INDEXED, int ROWS>
@@ -281,12 +301,13 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
     if (prof) std::memset(prof, 0, sizeof(*prof));
     if (status != LPD_OK || n == 0 || B == 0) return status;
 
-    const Carve c = carve(n, B);
+    const Carve c = carve(n, d, B);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < c.min_bytes)
         return LPD_ERR_WORKSPACE;
     char *ws = static_cast<char *>(workspace);
     float *nx = reinterpret_cast<float *>(ws + c.off_nx);
     float *nl = reinterpret_cast<float *>(ws + c.off_nl);
+    float *cen = reinterpret_cast<float *>(ws + c.off_cen);
     float *Z = reinterpret_cast<float *>(ws + c.off_z);
     int64_t panel = int64_t((workspace_bytes - c.off_z) / (size_t(c.ldz) * 4));
     if (panel >= n) panel = n;
@@ -296,8 +317,7 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
     log.on = prof != nullptr;
 
     LPD_HIP(log.begin(0, s));
-    LPD_HIP(launch_sqnorm(X, n, d, ldx, nx, s));
-    LPD_HIP(launch_sqnorm(L, B, d, ldl, nl, s));
+    LPD_HIP(launch_centred_norms(X, n, d, ldx, L, B, ldl, cen, nx, nl, s));
     LPD_HIP(log.end(s));
 
     for (int64_t p0 = 0; p0 < n; p0 += panel) {
@@ -307,7 +327,7 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
         k1.B = L; k1.ldb = ldl;
         k1.C = Z; k1.ldc = c.ldz;
         k1.M = int(rows); k1.N = int(B); k1.K = int(d); k1.n_store = int(B);
-        k1.na = nx + p0; k1.nb = nl;
+        k1.na = nx + p0; k1.nb = nl; k1.cen = cen;
         k1.scale = -gamma * 1.44269504088896340736f;
         LPD_HIP(log.begin(1, s));
         LPD_HIP(launch_gemm(k1, EPI_GAUSS, s));
@@ -367,7 +387,7 @@ CsrCarve csr_carve(int64_t chunk_rows, int64_t d, int64_t B, bool gather)
         c.bytes = c.off_z + round_up(size_t(chunk_rows) * size_t(c.ldz) * 4, kAlign);
     } else {
         c.panel_bytes = round_up(size_t(chunk_rows) * size_t(c.ldxd) * 4, kAlign);
-        c.bytes = c.panel_bytes + carve(chunk_rows, B).rec_bytes;
+        c.bytes = c.panel_bytes + carve(chunk_rows, d, B).rec_bytes;
     }
     return c;
 }
@@ -381,20 +401,19 @@ int lpd_kernel_block_dense(const float *X, int64_t n, int64_t d, int64_t ldx, co
     if (ldz < B) return LPD_ERR_LD;
     if (d > 0 && (!X || !L)) return LPD_ERR_NULL;
     if (d > 0 && (ldx < d || ldl < d)) return LPD_ERR_LD;
-    const size_t off_nl = round_up(size_t(n) * 4, kAlign);
-    const size_t need = off_nl + round_up(size_t(B) * 4, kAlign);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < need)
+    const Carve c = carve(n, d, B);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < c.off_z)
         return LPD_ERR_WORKSPACE;
     float *nx = reinterpret_cast<float *>(workspace);
-    float *nl = reinterpret_cast<float *>(static_cast<char *>(workspace) + off_nl);
-    if (launch_sqnorm(X, n, d, ldx, nx, s) != hipSuccess) return LPD_ERR_HIP;
-    if (launch_sqnorm(L, B, d, ldl, nl, s) != hipSuccess) return LPD_ERR_HIP;
+    float *nl = reinterpret_cast<float *>(static_cast<char *>(workspace) + c.off_nl);
+    float *cen = reinterpret_cast<float *>(static_cast<char *>(workspace) + c.off_cen);
+    if (launch_centred_norms(X, n, d, ldx, L, B, ldl, cen, nx, nl, s) != hipSuccess) return LPD_ERR_HIP;
     GemmArgs k1{};
     k1.A = X; k1.lda = ldx;
     k1.B = L; k1.ldb = ldl;
     k1.C = Z; k1.ldc = ldz;
     k1.M = int(n); k1.N = int(B); k1.K = int(d); k1.n_store = int(B);
-    k1.na = nx; k1.nb = nl;
+    k1.na = nx; k1.nb = nl; k1.cen = cen;
     k1.scale = -gamma * 1.44269504088896340736f;
     return launch_gemm(k1, EPI_GAUSS, s) == hipSuccess ? LPD_OK : LPD_ERR_HIP;
 }
@@ -426,7 +445,7 @@ int csr_impl(const int64_t *row_ptr, const int32_t *col_idx, const float *values
         float *Zp = reinterpret_cast<float *>(wsp + cc.off_z);
         hipLaunchKernelGGL(transpose_kernel, dim3(unsigned((B + 31) / 32), unsigned((d + 31) / 32)), dim3(256), 0, s, L,
                            int(B), int(d), ldl, Lt, cc.ldlt);
-        if (hipGetLastError() != hipSuccess || launch_sqnorm(L, B, d, ldl, nl, s) != hipSuccess) return LPD_ERR_HIP;
+        if (hipGetLastError() != hipSuccess || launch_sqnorm(L, B, d, ldl, nullptr, nl, s) != hipSuccess) return LPD_ERR_HIP;
         const float scale = -gamma * 1.44269504088896340736f;
         for (int64_t c0 = 0; c0 < n; c0 += chunk_rows) {
             const int64_t rows = std::min(chunk_rows, n - c0);
@@ -504,7 +523,7 @@ int lpd_nystrom_factor_workspace(int64_t n, int64_t d, int64_t B, size_t *bytes,
 {
     if (!bytes) return LPD_ERR_NULL;
     if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
-    const Carve c = carve(n, B);
+    const Carve c = carve(n, d, B);
     *bytes = c.rec_bytes;
     if (min_bytes) *min_bytes = c.min_bytes;
     return LPD_OK;
@@ -532,9 +551,9 @@ int lpd_nystrom_factor_to_host_workspace(int64_t n, int64_t d, int64_t B, int64_
 {
     if (!chunk_rows || !bytes) return LPD_ERR_NULL;
     if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
-    if (*chunk_rows <= 0) *chunk_rows = std::max<int64_t>(1, std::min<int64_t>(n, carve(n, B).rec_rows));
+    if (*chunk_rows <= 0) *chunk_rows = std::max<int64_t>(1, std::min<int64_t>(n, carve(n, d, B).rec_rows));
     if (*chunk_rows > kMaxDim) return LPD_ERR_SHAPE;
-    const StreamCarve sc = stream_carve(*chunk_rows, B);
+    const StreamCarve sc = stream_carve(*chunk_rows, d, B);
     *bytes = sc.bytes;
     return LPD_OK;
 }
@@ -549,7 +568,7 @@ int lpd_nystrom_factor_to_host(const float *X, int64_t n, int64_t d, int64_t ldx
     if (chunk_rows <= 0 || chunk_rows > kMaxDim) return LPD_ERR_SHAPE;
     if (n == 0 || B == 0) return LPD_OK;
     chunk_rows = std::min(chunk_rows, n);
-    const StreamCarve sc = stream_carve(chunk_rows, B);
+    const StreamCarve sc = stream_carve(chunk_rows, d, B);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < sc.bytes)
         return LPD_ERR_WORKSPACE;
     char *ws = static_cast<char *>(workspace);
@@ -598,7 +617,7 @@ int lpd_nystrom_factor_csr_workspace(int64_t n, int64_t d, int64_t B, int64_t nn
 {
     if (!chunk_rows || !bytes) return LPD_ERR_NULL;
     if (n < 0 || d < 0 || B < 0 || n > kMaxDim || d > kMaxDim || B > kMaxDim) return LPD_ERR_SHAPE;
-    if (*chunk_rows <= 0) *chunk_rows = std::max<int64_t>(1, std::min<int64_t>(n, carve(n, B).rec_rows));
+    if (*chunk_rows <= 0) *chunk_rows = std::max<int64_t>(1, std::min<int64_t>(n, carve(n, d, B).rec_rows));
     if (*chunk_rows > kMaxDim) return LPD_ERR_SHAPE;
     *bytes = csr_carve(*chunk_rows, d, B, csr_use_gather(n, d, nnz)).bytes;
     return LPD_OK;
@@ -709,7 +728,7 @@ int lpd_row_sqnorms(const float *G, int64_t n, int64_t r, int64_t ldg, float *gs
     if (n == 0) return LPD_OK;
     if (!gsq || (r > 0 && !G)) return LPD_ERR_NULL;
     if (ldg < r) return LPD_ERR_LD;
-    return launch_sqnorm(G, n, r, ldg, gsq, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? LPD_OK : LPD_ERR_HIP;
+    return launch_sqnorm(G, n, r, ldg, nullptr, gsq, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? LPD_OK : LPD_ERR_HIP;
 }
 
 int lpd_cd_solve_workspace(int64_t n_problems, int64_t total_rows, size_t *bytes)

@@ -93,9 +93,11 @@ __global__ __launch_bounds__(256) void margins_kernel(const float *__restrict__ 
     }
 }
 
+// cen (may be NULL): the row is taken relative to this point, s[i] = sum_k (X[i,k] - cen[k])^2; d floats,
+// 16-byte aligned.
 template <int LPR, bool VEC>
 __global__ __launch_bounds__(256) void sqnorm_kernel(const float *__restrict__ X, int64_t n, int d, int64_t ldx,
-                                                     float *__restrict__ out)
+                                                     const float *__restrict__ cen, float *__restrict__ out)
 {
     constexpr int GROUPS = 256 / LPR;
     const int sub = threadIdx.x % LPR;
@@ -107,15 +109,37 @@ __global__ __launch_bounds__(256) void sqnorm_kernel(const float *__restrict__ X
         float s0 = 0.f, s1 = 0.f;
         if (VEC) {
             for (int k = sub * 4; k < d4; k += LPR * 4) {
-                const rf32x4 v = *reinterpret_cast<const rf32x4 *>(x + k);
+                rf32x4 v = *reinterpret_cast<const rf32x4 *>(x + k);
+                if (cen) v -= *reinterpret_cast<const rf32x4 *>(cen + k);
                 s0 += v.x * v.x + v.y * v.y;
                 s1 += v.z * v.z + v.w * v.w;
             }
         }
-        for (int k = d4 + sub; k < d; k += LPR) s1 += x[k] * x[k];
+        for (int k = d4 + sub; k < d; k += LPR) {
+            const float v = cen ? x[k] - cen[k] : x[k];
+            s1 += v * v;
+        }
         const float s = group_sum<LPR>(s0 + s1);
         if (sub == 0) out[i] = s;
     }
+}
+
+// The origin the Gaussian kernel block works from: cen[k] = mean over a sample of the landmark rows of L[., k]
+// (every `step`-th row, `rows` of them).  Any point serves, a distance does not depend on the origin; one
+// inside the data keeps ||x - cen||^2 of the order of the distances.  A workgroup owns 64 features; its four
+// wavefronts take every fourth sampled row (coalesced) and meet in LDS.
+__global__ __launch_bounds__(256) void centre_kernel(const float *__restrict__ L, int64_t ldl, int d, int rows,
+                                                     int64_t step, float *__restrict__ cen)
+{
+    __shared__ float part[4][64];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int k = blockIdx.x * 64 + lane;
+    float s = 0.f;
+    if (k < d)
+        for (int i = wv; i < rows; i += 4) s += L[int64_t(i) * step * ldl + k];
+    part[wv][lane] = s;
+    __syncthreads();
+    if (wv == 0 && k < d) cen[k] = ((part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane])) / float(rows);
 }
 
 // M[i, q] = sum_j G[i, j] * Ws[q, j] for a handful of weight vectors at once (K <= 8): one pass over G

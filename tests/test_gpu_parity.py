@@ -74,7 +74,7 @@ def test_kernel_block_matches_oracle(lpd, oracle, dev, n, d, B, gamma, tile):
     X = torch.randn((n, d), generator=g).to(dev)
     L = torch.cat([X[: min(B, n) // 2].cpu(), torch.randn((B - min(B, n) // 2, d), generator=g)]).to(dev)
     Z = torch.full((n, B), float("nan"), dtype=torch.float32, device=dev)
-    ws = torch.empty(4 * (n + B) + 1024, dtype=torch.uint8, device=dev)
+    ws = torch.empty(4 * (n + B + d) + 3 * 256, dtype=torch.uint8, device=dev)     # three parts, each rounded up to 256
     lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, lpd.GEMM_TILES[tile])
     try:
         lpd.lpd_kernel_block(X, L, gamma, Z, ws)

@@ -72,8 +72,10 @@ typedef enum {
     LPD_ERR_LD = -3,        /* a leading dimension is smaller than the row      */
     LPD_ERR_WORKSPACE = -4, /* workspace missing, misaligned or too small       */
     LPD_ERR_HIP = -5,       /* a HIP runtime call or kernel launch failed       */
-    LPD_ERR_NUMERIC = -6    /* eigensolver did not converge / kernel matrix not
+    LPD_ERR_NUMERIC = -6,   /* eigensolver did not converge / kernel matrix not
                                positive (largest eigenvalue <= 0)               */
+    LPD_ERR_LIMIT = -7      /* lpd_predict_noalloc only: the shape needs more
+                               than its fixed scratch                           */
 } lpd_status;
 
 /* Library version, major * 100 + minor. */
@@ -352,6 +354,32 @@ int lpd_predict(const float *X, int64_t n, int64_t d, int64_t ldx,
                 const float *V, int64_t c, int64_t ldv,
                 float *F, int64_t ldf,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * lpd_predict for callers that may not allocate and have no workspace to pass:
+ * code that runs under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same result and same stream-ordered
+ * behaviour as lpd_predict, without the workspace: the row norms, the origin and
+ * the panel of the kernel block live in a fixed 32 MiB array in device memory
+ * that belongs to the library (one per GPU, present from the library's first
+ * use on that GPU until the process ends).  The call allocates nothing, on the
+ * host or on the device, and calls no allocating routine.
+ *
+ * Limit: the minimum workspace lpd_nystrom_factor_workspace(n, d, B) reports
+ * must not exceed 32 MiB = 33,554,432 bytes, i.e. roughly
+ * 4 n + 4 B + 4 d + 4 min(n, 256) (B + 16) <= 2^25; e.g. B <= 16,384 with up to
+ * 4 million points per call, B = 30,000 with up to 600,000.  Beyond it the call
+ * does nothing and returns LPD_ERR_LIMIT.  Nothing in the array has to start at
+ * zero; every call overwrites what it reads.
+ * All calls on one GPU share the array: calls that may overlap on one GPU (two
+ * streams, two host threads) race on it and give wrong scores; keep them on one
+ * stream, or order them with events.
+ * Errors: as lpd_predict (without LPD_ERR_WORKSPACE), and LPD_ERR_LIMIT.
+ */
+int lpd_predict_noalloc(const float *X, int64_t n, int64_t d, int64_t ldx,
+                        const float *L, int64_t B, int64_t ldl, float gamma,
+                        const float *V, int64_t c, int64_t ldv,
+                        float *F, int64_t ldf, void *hip_stream);
 
 /*
  * Squared norms of the rows of the factor, gsq[i] = sum_{j<r} G[i,j]^2: the

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <vector>
@@ -11,6 +12,12 @@
 #include "cd_solver.hip.h"
 #include "gemm_nt.hip.h"
 #include "rowops.hip.h"
+
+// Scratch of lpd_predict_noalloc: one array per GPU, held from the first use of the library on that GPU until
+// the process ends.  In host code the name is only a handle for hipGetSymbolAddress; kernels get the device
+// address that call returns (static_scratch below), never the name.
+constexpr size_t kStaticScratchBytes = size_t(32) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -265,6 +272,24 @@ int check_factor_args(const float *X, int64_t n, int64_t d, int64_t ldx, const f
         if (e__ != hipSuccess) { status = LPD_ERR_HIP; goto done; } \
     } while (0)
 
+// Device address of `scratch` on the current device, looked up once per device and kept.  Two threads that
+// meet here for the first time both look it up and store the same value.
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_addr[kMaxDevices];
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LPD_ERR_HIP;
+    void *ptr = g_scratch_addr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return LPD_ERR_HIP;
+        g_scratch_addr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return LPD_OK;
+}
+
 constexpr int64_t kSweepClassifiers = 32;   // up to here prediction consumes a panel by sweeps, above by MFMA
 
 // What follows a panel of the kernel block: Z (rows x B) times W^T into `out` (factor: out_cols = B, zero fill
@@ -498,6 +523,7 @@ const char *lpd_strerror(int status)
     case LPD_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
     case LPD_ERR_HIP: return "HIP runtime call or kernel launch failed";
     case LPD_ERR_NUMERIC: return "eigendecomposition failed or kernel matrix not positive";
+    case LPD_ERR_LIMIT: return "sizes need more than the fixed 32 MiB scratch of the allocation-free entry point";
     default: return "unknown status";
     }
 }
@@ -719,6 +745,23 @@ int lpd_predict(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
     if (c < 0 || c > B) return LPD_ERR_SHAPE;
     if (c == 0) return LPD_OK;
     return factor_impl(X, n, d, ldx, L, B, ldl, gamma, V, c, ldv, F, ldf, c == B ? B : c, workspace, workspace_bytes,
+                       static_cast<hipStream_t>(hip_stream), nullptr);
+}
+
+int lpd_predict_noalloc(const float *X, int64_t n, int64_t d, int64_t ldx, const float *L, int64_t B, int64_t ldl,
+                        float gamma, const float *V, int64_t c, int64_t ldv, float *F, int64_t ldf, void *hip_stream)
+{
+    if (c < 0 || c > B) return LPD_ERR_SHAPE;
+    const int64_t out_cols = c == B ? B : c;
+    int status = check_factor_args(X, n, d, ldx, L, B, ldl, V, c, ldv, F, std::max(ldf, B));
+    if (status == LPD_OK && ldf < out_cols) status = LPD_ERR_LD;
+    if (status != LPD_OK || c == 0 || n == 0 || B == 0) return status;
+    // the smallest workspace lpd_predict accepts for this shape must fit the fixed array
+    if (carve(n, d, B).min_bytes > kStaticScratchBytes) return LPD_ERR_LIMIT;
+    void *ws = nullptr;
+    status = static_scratch(&ws);
+    if (status != LPD_OK) return status;
+    return factor_impl(X, n, d, ldx, L, B, ldl, gamma, V, c, ldv, F, ldf, out_cols, ws, kStaticScratchBytes,
                        static_cast<hipStream_t>(hip_stream), nullptr);
 }
 

@@ -76,6 +76,8 @@ SIGNATURES = {
     "lpd_fold_weights": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, _vp, _i64, _vp]),
     "lpd_predict": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _i64, _vp, _i64,
                                    _vp, _sz, _vp]),
+    "lpd_predict_noalloc": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, ctypes.c_float, _vp, _i64, _i64, _vp,
+                                           _i64, _vp]),
     "lpd_row_sqnorms": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp]),
     "lpd_cd_solve_workspace": (ctypes.c_int, [_i64, _i64, ctypes.POINTER(_sz)]),
     "lpd_cd_solve": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp,
@@ -547,6 +549,24 @@ def lpd_predict(X, L, gamma: float, V, F=None, workspace=None) -> torch.Tensor:
     st = lib().lpd_predict(X.data_ptr(), n, d, _ld(X), L.data_ptr(), B, _ld(L), float(gamma), V.data_ptr(), c, _ld(V),
                            F.data_ptr(), _ld(F), workspace.data_ptr(), workspace.numel(), _stream(X.device))
     _check(st, "lpd_predict")
+    return F
+
+
+def lpd_predict_noalloc(X, L, gamma: float, V, F) -> torch.Tensor:
+    """lpd_predict without a workspace and without any allocation (F must be passed in): the scratch is a fixed
+    array inside the library, shared by all calls on the GPU; see include/lpd.h for the size limit."""
+    X = _dev_f32(X, "X", 2)
+    L = _dev_f32(L, "L", 2)
+    V = _dev_f32(V, "V", 2)
+    F = _dev_f32(F, "F", 2)
+    n, d = X.shape
+    B = L.shape[0]
+    c = V.shape[0]
+    if L.shape[1] != d or V.shape[1] != B or F.shape != (n, c):
+        raise ValueError("shape mismatch: X n x d, L B x d, V c x B, F n x c")
+    st = lib().lpd_predict_noalloc(X.data_ptr(), n, d, _ld(X), L.data_ptr(), B, _ld(L), float(gamma), V.data_ptr(), c,
+                                   _ld(V), F.data_ptr(), _ld(F), _stream(X.device))
+    _check(st, "lpd_predict_noalloc")
     return F
 
 

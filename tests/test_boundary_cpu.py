@@ -294,3 +294,18 @@ def test_csr_query_and_argument_errors(L):
     assert g(p, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 9, 8, p, 9, 4, None, 0, None) == -2         # c > B
     assert g(p, p, p, 4, 4, -1, p, 8, 4, 0.5, p, 3, 8, p, 2, 4, None, 0, None) == -3         # ldf < c
     assert L.lpd_set_option(3, 2) == 0 and L.lpd_set_option(3, 3) == -2 and L.lpd_set_option(3, 0) == 0
+
+
+def test_predict_noalloc_error_paths(L):
+    """The allocation-free entry point checks shapes and its fixed 32 MiB limit on the host, before any HIP call."""
+    p = ctypes.c_void_p(256)
+    f = L.lpd_predict_noalloc
+    assert f(p, 1000, 8, 8, p, 40000, 8, 0.5, p, 2, 40000, p, 2, None) == -7        # beyond the scratch
+    assert f(p, 4_500_000, 8, 8, p, 16384, 8, 0.5, p, 2, 16384, p, 2, None) == -7   # the norms alone: 18 MB + panel 17 MB
+    assert b"32 MiB" in L.lpd_strerror(-7)
+    assert f(p, 10, 8, 8, p, 16, 8, 0.5, p, 17, 16, p, 17, None) == -2              # more classifiers than landmarks
+    assert f(p, 10, 8, 7, p, 16, 8, 0.5, p, 2, 16, p, 2, None) == -3                # ldx < d
+    assert f(p, 10, 8, 8, p, 16, 8, 0.5, p, 2, 16, p, 1, None) == -3                # ldf < c
+    assert f(None, 10, 8, 8, p, 16, 8, 0.5, p, 2, 16, p, 2, None) == -1
+    assert f(p, 0, 8, 8, p, 16, 8, 0.5, p, 2, 16, p, 2, None) == 0                  # nothing to do
+    assert f(p, 10, 8, 8, p, 16, 8, 0.5, p, 0, 16, p, 1, None) == 0

@@ -86,7 +86,11 @@ const char *lpd_strerror(int status);
 
 /*
  * Process-wide tuning knobs (not part of the method; defaults are chosen per
- * shape).  Not synchronised: set them while no other call is in flight.
+ * shape).  The only state the library keeps besides the scratch of
+ * lpd_predict_noalloc.  Each is an atomic integer: it may be set at any time
+ * from any thread; a call that is running reads it once per kernel launch, so a
+ * change takes effect from the next launch on (results do not depend on them
+ * beyond rounding, see the tile-independence tests).
  *   LPD_OPT_GEMM_TILE  workgroup tile of the two MFMA products:
  *                      0 = choose by shape, 1 = 128x128, 2 = 256x128, 3 = 256x256
  *   LPD_OPT_GEMM_PIPELINE  main-loop schedule of the MFMA products: 1 (default) =
@@ -314,7 +318,9 @@ int lpd_margins(const float *G, int64_t n, int64_t r, int64_t ldg,
  * cross-validation folds need it (Section 4, "Shrinking" and
  * "Cross Validation"):  m[t] = sum_{j<r} G[rows[t], j] * w[j],  t < n_rows.
  *
- *   rows device in  n_rows int64 indices, each in [0, n)  (not checked on the device)
+ *   rows device in  n_rows int64 indices, each in [0, n).  The device checks them: an
+ *                   index outside [0, n) reads nothing out of bounds and gives m[t] = NaN.
+ * Errors: LPD_ERR_SHAPE also for n_rows > 0 with n = 0.
  */
 int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg,
                      const int64_t *rows, int64_t n_rows,
@@ -425,11 +431,19 @@ int lpd_cd_solve_workspace(int64_t n_problems, int64_t total_rows, size_t *bytes
  * started from a recomputed w.  shrink_k = 0
  * switches shrinking off, eta = 0 the interleaved re-checks.
  *
- *   G        device in   n x r (ldg), r <= 16384; 16-byte aligned rows take the fast loader
+ *   G        device in   n x r (ldg), 1 <= r <= 16384.  With a 16-byte aligned G and ldg a
+ *                        multiple of 4 rows are read 16 bytes at a time, also across column r
+ *                        when r is not a multiple of 4: every row, the last included, must be
+ *                        readable up to column 4 ceil(r / 4) (true for any matrix whose last
+ *                        row is allocated to its full ldg, as lpd_nystrom_factor's output is)
  *   gsq      device in   n, from lpd_row_sqnorms
  *   prob_off device in   n_problems + 1 offsets into rows / y / alpha; prob_off[0] = 0,
- *                        non-decreasing, prob_off[n_problems] = total_rows (not checked on the device)
- *   rows     device in   total_rows indices into G, each in [0, n) (not checked on the device)
+ *                        non-decreasing, prob_off[n_problems] = total_rows
+ *   rows     device in   total_rows indices into G, each in [0, n)
+ *                        The host cannot see these two arrays; the device clamps offsets to
+ *                        [0, total_rows] and indices to [0, n), so that wrong contents give
+ *                        wrong solutions of the problems concerned, never an access outside
+ *                        the arrays or G.
  *   y        device in   total_rows labels, +1 or -1
  *   C        device in   n_problems upper bounds
  *   alpha    device i/o  total_rows; start values (zeros, or a warm start) in, solution out
@@ -437,7 +451,8 @@ int lpd_cd_solve_workspace(int64_t n_problems, int64_t total_rows, size_t *bytes
  *   status   device out  n_problems records
  * One workgroup per problem; problems run concurrently.  Calls with the same
  * alpha / workspace must not overlap.
- * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE (incl. r > 16384, shrink_k > 255, eta outside [0,1)),
+ * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE (incl. r > 16384, r = 0 or n = 0 with rows listed,
+ * shrink_k > 255, eta outside [0,1)),
  * LPD_ERR_LD (ldg < r, ldw < r), LPD_ERR_WORKSPACE, LPD_ERR_HIP.
  */
 int lpd_cd_solve(const float *G, int64_t n, int64_t r, int64_t ldg, const float *gsq,

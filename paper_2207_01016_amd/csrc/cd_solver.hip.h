@@ -58,6 +58,7 @@ struct CdStatus {          // one per problem, mirrors lpd_cd_status
 
 struct CdArgs {
     const float *G; int64_t ldg; int r;
+    int64_t n;                      // rows of G: listed row indices are clamped to [0, n)
     const float *gsq;               // ||g_i||^2 per row of G
     const int64_t *prob_off;        // n_problems + 1 offsets into rows / y / alpha
     const int64_t *rows;            // concatenated row lists (visiting order)
@@ -137,9 +138,14 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
     const int p = blockIdx.x;
     const int gl = threadIdx.x;
     const int wave = gl >> 6;
-    const int64_t o0 = a.prob_off[p];
-    const int np = int(a.prob_off[p + 1] - o0);
+    // offsets and row indices come from the caller's device memory unchecked by the host: they are clamped
+    // here, so that no content of those arrays can take an access outside the lists or outside G (a problem
+    // with clamped entries solves something other than what the caller meant; its memory accesses stay legal)
+    const int64_t o0 = min(max(a.prob_off[p], int64_t(0)), a.total);
+    const int np = int(min(max(a.prob_off[p + 1] - o0, int64_t(0)), a.total - o0));
     const int64_t *rows = a.rows + o0;
+    const int64_t row_max = a.n - 1;
+    auto row_of = [&](int t) __attribute__((always_inline)) -> int64_t { return min(max(rows[t], int64_t(0)), row_max); };
     const float *y = a.y + o0;
     float *alpha = a.alpha + o0;
     uint8_t *cnt = a.cnt + o0;
@@ -244,7 +250,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
                     if (todo) {
                         const int j = __ffsll(todo) - 1;
                         todo &= todo - 1;
-                        load_row(g[u], rows[b0 + j]);
+                        load_row(g[u], row_of(b0 + j));
                         f[u] = __shfl(av, j, 64) * y[b0 + j];
                         ++used;
                     }
@@ -275,7 +281,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
 
     // one step on a removed variable (re-check) or a violation probe; slow path, no prefetch
     auto single = [&](int t, bool apply, float &viol_out) __attribute__((always_inline)) -> bool {
-        const int64_t row = rows[t];
+        const int64_t row = row_of(t);
         const float yt = y[t];
         const float at = ld_wg(&alpha[t]);
         const float q = a.gsq[row];
@@ -305,7 +311,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
             wg_sync();
             if (gl < nb) {
                 const int t = ld_wg(&lb[o_act + b0 + gl]);
-                const int64_t row = rows[t];
+                const int64_t row = row_of(t);
                 s_t[gl] = t;
                 s_row[gl] = row;
                 s_y[gl] = y[t];
@@ -405,7 +411,7 @@ __global__ __launch_bounds__(64 * WAVES) void cd_solve_kernel(CdArgs a)
                     if (at_ >= cap) at_ -= cap;
                     const int t = ld_wg(&lb[o_rem + at_]);
                     s_t[gl] = t;
-                    s_row[gl] = rows[t];
+                    s_row[gl] = row_of(t);
                     s_y[gl] = y[t];
                     s_alpha[gl] = ld_wg(&alpha[t]);
                 }

@@ -81,13 +81,16 @@ StreamCarve stream_carve(int64_t chunk_rows, int64_t d, int64_t B)
 
 enum TileId { TILE_AUTO = 0, TILE_128x128 = 1, TILE_256x128 = 2, TILE_256x256 = 3 };
 
-int g_pipe_option = 1;            // lpd_set_option(LPD_OPT_GEMM_PIPELINE, ...)
-int g_tile_option = TILE_AUTO;   // lpd_set_option(LPD_OPT_GEMM_TILE, ...)
-int g_csr_route = 0;              // lpd_set_option(LPD_OPT_CSR_ROUTE, ...): 0 by density, 1 dense panel, 2 gather
+// Tuning knobs of lpd_set_option.  Atomic, so that setting one while other threads are inside the library is
+// well defined: every launch reads the value once.
+std::atomic<int> g_pipe_option{1};            // LPD_OPT_GEMM_PIPELINE
+std::atomic<int> g_tile_option{TILE_AUTO};   // LPD_OPT_GEMM_TILE
+std::atomic<int> g_csr_route{0};              // LPD_OPT_CSR_ROUTE: 0 by density, 1 dense panel, 2 gather
 
 int tile_choice(const GemmArgs &a)
 {
-    if (g_tile_option != TILE_AUTO) return g_tile_option;
+    const int forced = g_tile_option.load(std::memory_order_relaxed);
+    if (forced != TILE_AUTO) return forced;
     // 256x256 tiles (8 wavefronts, one workgroup per CU) halve the L2 traffic per FLOP; they pay
     // off once the contraction is long enough to amortise their larger prologue and epilogue and
     // there are enough of them to give every CU at least one.  Measured cross-over: K about 2048.
@@ -119,7 +122,7 @@ hipError_t launch_tile(const GemmArgs &a, bool aligned, int epi, hipStream_t s)
 {
     // The pipelined schedule needs the aligned fast path and per-lane byte offsets inside one
     // tile strip that fit 32 bits.
-    const bool pipe = g_pipe_option != 0 && aligned && int64_t(BM) * a.lda * 4 < (int64_t(1) << 31) &&
+    const bool pipe = g_pipe_option.load(std::memory_order_relaxed) != 0 && aligned && int64_t(BM) * a.lda * 4 < (int64_t(1) << 31) &&
                       int64_t(BN) * a.ldb * 4 < (int64_t(1) << 31);
     if (epi == EPI_GAUSS) {
         if (pipe) return launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS, 1>(a, s);
@@ -181,8 +184,9 @@ hipError_t launch_centred_norms(const float *X, int64_t n, int64_t d, int64_t ld
     return launch_sqnorm(L, B, d, ldl, cen, nl, s);
 }
 
+// n_rows_G: rows of G, the bound a row list is checked against on the device (INDEXED only)
 template <int LPR, bool INDEXED, int ROWS>
-hipError_t launch_margins_lpr(const float *G, int64_t n_out, int r, int64_t ldg, const int64_t *rows,
+hipError_t launch_margins_lpr(const float *G, int64_t n_out, int r, int64_t ldg, const int64_t *rows, int64_t n_rows_G,
                               const float *w, float *m, int64_t ms, bool vec, hipStream_t s)
 {
     // A full sweep over long rows runs fastest with few rows open at once (about 128 MB of them): 512 workgroups
@@ -190,22 +194,22 @@ hipError_t launch_margins_lpr(const float *G, int64_t n_out, int r, int64_t ldg,
     // with 256.  Shorter rows and row lists (scattered rows) keep the large grid.
     const int64_t cap = (INDEXED || r < 8192) ? 4096 : std::max<int64_t>(256, (int64_t(4) << 20) / r);
     const unsigned grid = row_grid(n_out, 256 / LPR * ROWS, cap);
-    if (vec) hipLaunchKernelGGL((margins_kernel<LPR, true, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m, ms);
-    else hipLaunchKernelGGL((margins_kernel<LPR, false, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, w, m, ms);
+    if (vec) hipLaunchKernelGGL((margins_kernel<LPR, true, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, n_rows_G, w, m, ms);
+    else hipLaunchKernelGGL((margins_kernel<LPR, false, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, n_rows_G, w, m, ms);
     return hipGetLastError();
 }
 
 template <bool INDEXED>
-hipError_t launch_margins(const float *G, int64_t n_out, int64_t r, int64_t ldg, const int64_t *rows,
+hipError_t launch_margins(const float *G, int64_t n_out, int64_t r, int64_t ldg, const int64_t *rows, int64_t n_rows_G,
                           const float *w, float *m, hipStream_t s, int64_t ms = 1)
 {
     const bool vec = aligned16(G) && aligned16(w) && ldg % 4 == 0;
     const int ri = int(r);
-    if (r >= 1024) return launch_margins_lpr<64, INDEXED, 2>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
-    if (r >= 256) return launch_margins_lpr<64, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
-    if (r >= 128) return launch_margins_lpr<32, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
-    if (r >= 64) return launch_margins_lpr<16, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
-    return launch_margins_lpr<8, INDEXED, 1>(G, n_out, ri, ldg, rows, w, m, ms, vec, s);
+    if (r >= 1024) return launch_margins_lpr<64, INDEXED, 2>(G, n_out, ri, ldg, rows, n_rows_G, w, m, ms, vec, s);
+    if (r >= 256) return launch_margins_lpr<64, INDEXED, 1>(G, n_out, ri, ldg, rows, n_rows_G, w, m, ms, vec, s);
+    if (r >= 128) return launch_margins_lpr<32, INDEXED, 1>(G, n_out, ri, ldg, rows, n_rows_G, w, m, ms, vec, s);
+    if (r >= 64) return launch_margins_lpr<16, INDEXED, 1>(G, n_out, ri, ldg, rows, n_rows_G, w, m, ms, vec, s);
+    return launch_margins_lpr<8, INDEXED, 1>(G, n_out, ri, ldg, rows, n_rows_G, w, m, ms, vec, s);
 }
 
 // Up to 8 weight vectors in one pass over the rows (margins_multi_kernel); four rows per wavefront share
@@ -390,7 +394,8 @@ constexpr double kGatherDensity = 0.08;
 
 bool csr_use_gather(int64_t n, int64_t d, int64_t nnz)
 {
-    if (g_csr_route != 0) return g_csr_route == 2;
+    const int route = g_csr_route.load(std::memory_order_relaxed);
+    if (route != 0) return route == 2;
     return nnz >= 0 && n > 0 && d > 0 && double(nnz) < kGatherDensity * double(n) * double(d);
 }
 
@@ -531,15 +536,15 @@ const char *lpd_strerror(int status)
 int lpd_set_option(int option, int64_t value)
 {
     if (option == LPD_OPT_GEMM_TILE && value >= TILE_AUTO && value <= TILE_256x256) {
-        g_tile_option = int(value);
+        g_tile_option.store(int(value), std::memory_order_relaxed);
         return LPD_OK;
     }
     if (option == LPD_OPT_CSR_ROUTE && value >= 0 && value <= 2) {
-        g_csr_route = int(value);
+        g_csr_route.store(int(value), std::memory_order_relaxed);
         return LPD_OK;
     }
     if (option == LPD_OPT_GEMM_PIPELINE && (value == 0 || value == 1)) {
-        g_pipe_option = int(value);
+        g_pipe_option.store(int(value), std::memory_order_relaxed);
         return LPD_OK;
     }
     return LPD_ERR_SHAPE;
@@ -688,7 +693,7 @@ int lpd_margins(const float *G, int64_t n, int64_t r, int64_t ldg, const float *
     if (!m) return LPD_ERR_NULL;
     if (r > 0 && (!G || !w)) return LPD_ERR_NULL;
     if (ldg < r) return LPD_ERR_LD;
-    hipError_t e = launch_margins<false>(G, n, r, ldg, nullptr, w, m, static_cast<hipStream_t>(hip_stream));
+    hipError_t e = launch_margins<false>(G, n, r, ldg, nullptr, n, w, m, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LPD_OK : LPD_ERR_HIP;
 }
 
@@ -697,10 +702,11 @@ int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg, const in
 {
     if (n < 0 || r < 0 || n_rows < 0 || n > kMaxDim * 4 || r > kMaxDim || n_rows > kMaxDim * 4) return LPD_ERR_SHAPE;
     if (n_rows == 0) return LPD_OK;
+    if (n == 0) return LPD_ERR_SHAPE;        // rows listed, but G has none
     if (!m || !rows) return LPD_ERR_NULL;
     if (r > 0 && (!G || !w)) return LPD_ERR_NULL;
     if (ldg < r) return LPD_ERR_LD;
-    hipError_t e = launch_margins<true>(G, n_rows, r, ldg, rows, w, m, static_cast<hipStream_t>(hip_stream));
+    hipError_t e = launch_margins<true>(G, n_rows, r, ldg, rows, n, w, m, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LPD_OK : LPD_ERR_HIP;
 }
 
@@ -793,8 +799,11 @@ int lpd_cd_solve(const float *G, int64_t n, int64_t r, int64_t ldg, const float 
         !(eta >= 0.0f && eta < 1.0f) || !(eps >= 0.0f))
         return LPD_ERR_SHAPE;
     if (n_problems == 0) return LPD_OK;
+    // rows are read 16 bytes at a time from column 0 on: a factor without columns, or without rows, has
+    // nothing to read them from
+    if (total_rows > 0 && (r == 0 || n == 0)) return LPD_ERR_SHAPE;
     if (!prob_off || !C || !status || (r > 0 && !w)) return LPD_ERR_NULL;
-    if (total_rows > 0 && (!rows || !y || !alpha || !gsq || (r > 0 && !G))) return LPD_ERR_NULL;
+    if (total_rows > 0 && (!rows || !y || !alpha || !gsq || !G)) return LPD_ERR_NULL;
     if (ldg < r || ldw < r) return LPD_ERR_LD;
     size_t need = 0;
     lpd_cd_solve_workspace(n_problems, total_rows, &need);
@@ -802,7 +811,7 @@ int lpd_cd_solve(const float *G, int64_t n, int64_t r, int64_t ldg, const float 
         return LPD_ERR_WORKSPACE;
 
     CdArgs a{};
-    a.G = G; a.ldg = ldg; a.r = int(r); a.gsq = gsq;
+    a.G = G; a.ldg = ldg; a.r = int(r); a.n = n; a.gsq = gsq;
     a.prob_off = prob_off; a.rows = rows; a.y = y; a.C = C; a.alpha = alpha;
     a.w = w; a.ldw = ldw; a.status = reinterpret_cast<CdStatus *>(status);
     a.lists = static_cast<int32_t *>(workspace);

@@ -27,11 +27,13 @@ __device__ __forceinline__ float group_sum(float v)
 // ROWS: rows a lane group works on at once; they share each load of w, which is what lifts the
 // long-row sweep from 82 % to 89 % of HBM bandwidth (two rows; more rows lose it again to
 // register pressure).  A group past the end re-reads the last row and drops the result.
+// INDEXED: an index outside [0, n_rows_G) reads row 0 instead and yields NaN, so that no list can make the
+// kernel read outside G.
 template <int LPR, bool VEC, bool INDEXED, int ROWS>
 __global__ __launch_bounds__(256) void margins_kernel(const float *__restrict__ G, int64_t n_out, int r,
                                                       int64_t ldg, const int64_t *__restrict__ rows,
-                                                      const float *__restrict__ w, float *__restrict__ m,
-                                                      int64_t m_stride)
+                                                      int64_t n_rows_G, const float *__restrict__ w,
+                                                      float *__restrict__ m, int64_t m_stride)
 {
     constexpr int GROUPS = 256 / LPR;             // lane groups per workgroup
     const int sub = threadIdx.x % LPR;
@@ -41,10 +43,13 @@ __global__ __launch_bounds__(256) void margins_kernel(const float *__restrict__ 
 
     for (int64_t t0 = (int64_t(blockIdx.x) * GROUPS + grp) * ROWS; t0 < n_out; t0 += stride) {
         const float *g[ROWS];
+        bool bad[ROWS];
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
             const int64_t t = t0 + q < n_out ? t0 + q : n_out - 1;
-            const int64_t row = INDEXED ? rows[t] : t;
+            int64_t row = INDEXED ? rows[t] : t;
+            bad[q] = INDEXED && (row < 0 || row >= n_rows_G);
+            if (bad[q]) row = 0;
             g[q] = G + row * ldg;
         }
         float s[ROWS][4];
@@ -88,7 +93,7 @@ __global__ __launch_bounds__(256) void margins_kernel(const float *__restrict__ 
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
             const float tot = group_sum<LPR>((s[q][0] + s[q][1]) + (s[q][2] + s[q][3]));
-            if (sub == 0 && t0 + q < n_out) m[(t0 + q) * m_stride] = tot;
+            if (sub == 0 && t0 + q < n_out) m[(t0 + q) * m_stride] = bad[q] ? __builtin_nanf("") : tot;
         }
     }
 }

@@ -281,7 +281,7 @@ def lpd_nystrom_factor_to_host(X, L, gamma: float, W, G_host=None, chunk_rows: i
     return G_host
 
 
-def _csr_args(row_ptr, col_idx, values, d):
+def _csr_args(row_ptr, col_idx, values, d, validate=True):
     if not (row_ptr.is_cuda and row_ptr.dtype == torch.int64 and row_ptr.dim() == 1 and row_ptr.numel() >= 1):
         raise TypeError("row_ptr: expected a 1-D int64 device tensor with n + 1 entries")
     if not (col_idx.is_cuda and col_idx.dtype == torch.int32 and col_idx.dim() == 1):
@@ -290,11 +290,14 @@ def _csr_args(row_ptr, col_idx, values, d):
         raise TypeError("values: expected a float32 device tensor shaped like col_idx")
     row_ptr, col_idx, values = row_ptr.contiguous(), col_idx.contiguous(), values.contiguous()
     n = row_ptr.numel() - 1
-    # the structure is checked here, on the device, so that the kernels never see offsets outside the arrays
-    if int(row_ptr[0]) != 0 or int(row_ptr[-1]) != col_idx.numel() or (n and bool((row_ptr[1:] < row_ptr[:-1]).any())):
-        raise ValueError("row_ptr: expected non-decreasing offsets from 0 to the number of entries")
-    if col_idx.numel() and (int(col_idx.min()) < 0 or int(col_idx.max()) >= d):
-        raise ValueError("col_idx: column index outside [0, d)")
+    # the row offsets are trusted by the kernels: check them here unless the caller vouches for them
+    # (validate=False: no device-to-host synchronisation, the call only enqueues)
+    if validate:
+        if int(row_ptr[0]) != 0 or int(row_ptr[-1]) != col_idx.numel() or \
+                (n and bool((row_ptr[1:] < row_ptr[:-1]).any())):
+            raise ValueError("row_ptr: expected non-decreasing offsets from 0 to the number of entries")
+        if col_idx.numel() and (int(col_idx.min()) < 0 or int(col_idx.max()) >= d):
+            raise ValueError("col_idx: column index outside [0, d)")
     return row_ptr, col_idx, values, n
 
 
@@ -308,9 +311,11 @@ def lpd_nystrom_factor_csr_workspace(n: int, d: int, B: int, chunk_rows: int = 0
 
 
 def lpd_nystrom_factor_csr(row_ptr, col_idx, values, d: int, L, gamma: float, W, G=None, chunk_rows: int = 0,
-                           workspace=None, r: int | None = None) -> torch.Tensor:
-    """Step 1d for X in compressed-row form (device tensors). Enqueued on torch's current stream."""
-    row_ptr, col_idx, values, n = _csr_args(row_ptr, col_idx, values, d)
+                           workspace=None, r: int | None = None, validate: bool = True) -> torch.Tensor:
+    """Step 1d for X in compressed-row form (device tensors). Enqueued on torch's current stream.
+    validate=True reads the row offsets and the column range back first (a blocking check); pass False in a
+    hot loop or under graph capture once the structure is known to be sound."""
+    row_ptr, col_idx, values, n = _csr_args(row_ptr, col_idx, values, d, validate)
     L = _dev_f32(L, "L", 2)
     W = _dev_f32(W, "W", 2)
     B = L.shape[0]
@@ -335,9 +340,9 @@ def lpd_nystrom_factor_csr(row_ptr, col_idx, values, d: int, L, gamma: float, W,
 
 
 def lpd_kernel_block_csr(row_ptr, col_idx, values, d: int, L, gamma: float, Z=None, chunk_rows: int = 0,
-                         workspace=None) -> torch.Tensor:
-    """Z = K(X, L) for X in compressed-row form (device tensors)."""
-    row_ptr, col_idx, values, n = _csr_args(row_ptr, col_idx, values, d)
+                         workspace=None, validate: bool = True) -> torch.Tensor:
+    """Z = K(X, L) for X in compressed-row form (device tensors); validate as in lpd_nystrom_factor_csr."""
+    row_ptr, col_idx, values, n = _csr_args(row_ptr, col_idx, values, d, validate)
     L = _dev_f32(L, "L", 2)
     B = L.shape[0]
     if L.shape[1] != d:
@@ -357,9 +362,10 @@ def lpd_kernel_block_csr(row_ptr, col_idx, values, d: int, L, gamma: float, Z=No
 
 
 def lpd_predict_csr(row_ptr, col_idx, values, d: int, L, gamma: float, V, F=None, chunk_rows: int = 0,
-                    workspace=None) -> torch.Tensor:
-    """Scores F[i, j] = V[j] . K(x_i, L) for new points in compressed-row form (n x c)."""
-    row_ptr, col_idx, values, n = _csr_args(row_ptr, col_idx, values, d)
+                    workspace=None, validate: bool = True) -> torch.Tensor:
+    """Scores F[i, j] = V[j] . K(x_i, L) for new points in compressed-row form (n x c); validate as in
+    lpd_nystrom_factor_csr."""
+    row_ptr, col_idx, values, n = _csr_args(row_ptr, col_idx, values, d, validate)
     L = _dev_f32(L, "L", 2)
     V = _dev_f32(V, "V", 2)
     B, c = L.shape[0], V.shape[0]
@@ -413,15 +419,14 @@ def lpd_margins(G, w, m=None, r: int | None = None) -> torch.Tensor:
 
 
 def lpd_margins_rows(G, rows, w, m=None, r: int | None = None) -> torch.Tensor:
-    """Step 2a over a list of rows (int64 device tensor)."""
+    """Step 2a over a list of rows (int64 device tensor). Only enqueues: the kernel checks the indices itself
+    (an index outside [0, n) gives NaN), so the call can be recorded into a HIP graph."""
     G = _dev_f32(G, "G", 2)
     w = _dev_f32(w, "w", 1)
     if rows.dtype != torch.int64 or rows.dim() != 1 or not rows.is_cuda or (rows.numel() > 1 and rows.stride(0) != 1):
         raise TypeError("rows: expected a contiguous 1-D int64 device tensor")
     n = G.shape[0]
     k = rows.shape[0]
-    if k > 0 and (int(rows.min()) < 0 or int(rows.max()) >= n):   # the kernel does not bounds-check
-        raise IndexError("rows: index outside [0, n)")
     r = w.shape[0] if r is None else int(r)
     if r > w.shape[0] or r > G.shape[1]:
         raise ValueError("r exceeds w or the columns of G")
@@ -463,12 +468,18 @@ CD_STATUS_DTYPE = [("steps", "<i8"), ("epochs", "<i4"), ("converged", "<i4"), ("
 
 
 def lpd_cd_solve(G, gsq, prob_off, rows, y, C, alpha, w=None, eps: float = 1e-3, max_epochs: int = 1000,
-                 shrink_k: int = 5, eta: float = 0.05, r: int | None = None, workspace=None):
+                 shrink_k: int = 5, eta: float = 0.05, r: int | None = None, workspace=None, validate: bool = True,
+                 status=None):
     """Batch of dual coordinate-ascent problems on the rows of G (see include/lpd.h).
 
     prob_off: int64 device tensor of n_problems + 1 offsets; rows / y / alpha: concatenated per-problem lists
     (alpha is updated in place); C: float32 device tensor, one per problem.
-    Returns (alpha, w [n_problems x r], status as a numpy record array read back after a synchronise)."""
+    validate=True reads prob_off and the range of rows back and raises on inconsistent lists (blocking);
+    validate=False leaves them to the kernel, which clamps them so that no access leaves the arrays.
+    status: optional uint8 device tensor (n_problems x 32) for the result records; when given, the call only
+    enqueues and returns it as a device tensor (view it with CD_STATUS_DTYPE after a synchronise).
+    Returns (alpha, w [n_problems x r], status: numpy record array read back after a synchronise, or the
+    device tensor passed in)."""
     G = _dev_f32(G, "G", 2)
     gsq = _dev_f32(gsq, "gsq", 1)
     y = _dev_f32(y, "y", 1)
@@ -484,13 +495,13 @@ def lpd_cd_solve(G, gsq, prob_off, rows, y, C, alpha, w=None, eps: float = 1e-3,
     if r > G.shape[1] or prob_off.shape[0] != P + 1 or y.shape[0] != total or alpha.shape[0] != total or \
             gsq.shape[0] != n:
         raise ValueError("shape mismatch between G, gsq, prob_off, rows, y, C, alpha")
-    # the kernel trusts offsets and indices: check them here
-    if P > 0:
-        po = prob_off.cpu()
-        if int(po[0]) != 0 or int(po[-1]) != total or bool((po[1:] < po[:-1]).any()):
-            raise ValueError("prob_off must start at 0, be non-decreasing and end at len(rows)")
-    if total > 0 and (int(rows.min()) < 0 or int(rows.max()) >= n):
-        raise IndexError("rows: index outside [0, n)")
+    if validate:
+        if P > 0:
+            po = prob_off.cpu()
+            if int(po[0]) != 0 or int(po[-1]) != total or bool((po[1:] < po[:-1]).any()):
+                raise ValueError("prob_off must start at 0, be non-decreasing and end at len(rows)")
+        if total > 0 and (int(rows.min()) < 0 or int(rows.max()) >= n):
+            raise IndexError("rows: index outside [0, n)")
     if w is None:
         w = torch.empty((P, max(r, 1)), dtype=torch.float32, device=G.device)
     w = _dev_f32(w, "w", 2)
@@ -499,12 +510,18 @@ def lpd_cd_solve(G, gsq, prob_off, rows, y, C, alpha, w=None, eps: float = 1e-3,
     need = lpd_cd_solve_workspace(P, total)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=G.device)
-    status = torch.zeros((max(P, 1), 32), dtype=torch.uint8, device=G.device)
+    enqueue_only = status is not None
+    if status is None:
+        status = torch.zeros((max(P, 1), 32), dtype=torch.uint8, device=G.device)
+    elif status.dtype != torch.uint8 or not status.is_cuda or status.numel() < 32 * P or not status.is_contiguous():
+        raise TypeError("status: expected a contiguous uint8 device tensor of n_problems x 32 bytes")
     st = lib().lpd_cd_solve(G.data_ptr(), n, r, _ld(G), gsq.data_ptr(), P, prob_off.data_ptr(), total,
                             rows.data_ptr(), y.data_ptr(), C.data_ptr(), alpha.data_ptr(), w.data_ptr(), _ld(w),
                             status.data_ptr(), float(eps), int(max_epochs), int(shrink_k), float(eta),
                             workspace.data_ptr(), workspace.numel(), _stream(G.device))
     _check(st, "lpd_cd_solve")
+    if enqueue_only:
+        return alpha, w, status
     import numpy as np
     rec = np.frombuffer(status.cpu().numpy().tobytes(), dtype=np.dtype(CD_STATUS_DTYPE))[:P]
     return alpha, w, rec

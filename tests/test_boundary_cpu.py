@@ -150,6 +150,12 @@ def test_solver_and_predict_argument_errors(L):
     assert cd(p, 10, 8, 8, p, 1, p, 10, p, p, p, p, p, 8, p, 1e-3, 10, 300, 0.05, p, 4096, None) == -2  # k > 255
     assert cd(p, 10, 8, 8, p, 1, p, 10, p, p, p, p, p, 8, p, 1e-3, 10, 5, 1.0, p, 4096, None) == -2     # eta >= 1
     assert cd(p, 10, 20000, 20000, p, 1, p, 10, p, p, p, p, p, 20000, p, 1e-3, 10, 5, 0.05, p, 4096, None) == -2
+    # a factor without columns or without rows cannot be stepped over: refused on the host, no launch
+    assert cd(None, 10, 0, 0, p, 1, p, 10, p, p, p, p, None, 0, p, 1e-3, 10, 5, 0.05, p, 4096, None) == -2   # r = 0
+    assert cd(p, 10, 0, 8, p, 1, p, 10, p, p, p, p, p, 8, p, 1e-3, 10, 5, 0.05, p, 4096, None) == -2        # r = 0
+    assert cd(p, 0, 8, 8, p, 1, p, 10, p, p, p, p, p, 8, p, 1e-3, 10, 5, 0.05, p, 4096, None) == -2         # n = 0
+    assert cd(None, 10, 8, 8, p, 1, p, 10, p, p, p, p, p, 8, p, 1e-3, 10, 5, 0.05, p, 4096, None) == -1     # G NULL
+    assert L.lpd_margins_rows(p, 0, 8, 8, p, 5, p, p, None) == -2                    # rows listed, G has none
     assert L.lpd_row_sqnorms(p, 0, 8, 8, p, None) == 0
     assert L.lpd_row_sqnorms(p, 4, 8, 7, p, None) == -3
     assert L.lpd_row_sqnorms(p, 4, 8, 8, None, None) == -1

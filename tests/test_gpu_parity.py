@@ -293,8 +293,61 @@ def test_margins_unit_vector_and_rows(lpd, oracle, dev):
     assert torch.equal(mr, mall[rows])
     ref = oracle.margins(G[rows].cpu().numpy(), w.cpu().numpy())
     assert relfro(mr.cpu().numpy(), ref) <= TOL_M
-    with pytest.raises(IndexError):
-        lpd.lpd_margins_rows(G, torch.tensor([0, 1500], device=dev), w)
+    # indices outside [0, n) are caught on the device: NaN for that entry, nothing read out of bounds,
+    # the valid entries around it unaffected
+    bad = torch.tensor([0, 1500, 7, -1, 1499, 1 << 40], device=dev)
+    mb = lpd.lpd_margins_rows(G, bad, w)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.isnan(mb).cpu(), torch.tensor([False, True, False, True, False, True]))
+    assert torch.equal(mb[[0, 2, 4]], mall[[0, 7, 1499]])
+
+
+def test_row_list_sweep_and_solver_replay_from_a_hip_graph(lpd, oracle, dev):
+    """The row-list sweep and the solver take their index arrays from device memory and check them there, so the
+    binding only enqueues them: both can be recorded into a HIP graph and replayed."""
+    g = torch.Generator().manual_seed(123)
+    n, r = 4000, 520
+    G = (torch.randn((n, r), generator=g) / r ** 0.5).to(dev)
+    w = torch.randn(r, generator=g).to(dev)
+    rows = torch.randperm(n, generator=g)[:900].to(dev)
+    gsq = lpd.lpd_row_sqnorms(G)
+    prob_off = torch.tensor([0, 500, 900], device=dev)
+    y = torch.where(torch.randn(900, generator=g) > 0, 1.0, -1.0).to(dev)
+    C = torch.tensor([1.0, 0.5], device=dev)
+    ws = torch.empty(lpd.lpd_cd_solve_workspace(2, 900), dtype=torch.uint8, device=dev)
+
+    def run(m, alpha, wout, status):
+        lpd.lpd_margins_rows(G, rows, w, m)
+        alpha.copy_(alpha0)
+        lpd.lpd_cd_solve(G, gsq, prob_off, rows, y, C, alpha, wout, eps=1e-3, max_epochs=50, workspace=ws,
+                         validate=False, status=status)
+
+    alpha0 = torch.zeros(900, device=dev)
+    bufs0 = (torch.empty(900, device=dev), torch.empty(900, device=dev), torch.empty((2, r), device=dev),
+             torch.zeros((2, 32), dtype=torch.uint8, device=dev))
+    run(*bufs0)
+    torch.cuda.synchronize()
+    ref = oracle.margins(G[rows].cpu().numpy(), w.cpu().numpy())
+    assert relfro(bufs0[0].cpu().numpy(), ref) <= TOL_M
+    bufs1 = tuple(torch.zeros_like(b) for b in bufs0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(*bufs1)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(*bufs1)
+    for rep in range(3):
+        for b in bufs1[:3]:
+            b.fill_(float("nan"))
+        junk = (G @ G.T[:, :64]).sum()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(bufs1, bufs0)), rep
+        assert bool(torch.isfinite(junk))
 
 
 def test_margins_on_factor_output_tiny(lpd, wls, oracle, dev):

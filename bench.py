@@ -49,6 +49,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", default="auto", choices=["auto", "128x128", "256x128", "256x256"])
     ap.add_argument("--workspace-mult", type=float, default=1.0)
+    ap.add_argument("--panel-rows", type=int, default=0,
+                    help="factor: size the workspace for kernel-block panels of this many rows (a multiple of 256; "
+                         "0 = the library's recommendation)")
     ap.add_argument("--path", default="factor", choices=["factor", "solver", "predict", "stream", "whiten", "sparse"],
                     help="factor: Nystrom factor + margin sweep (default); solver: batched dual coordinate ascent "
                          "on G; predict: scores of new points; stream: the factor copied to pinned host memory as it is made; whiten: the one-off preparation "
@@ -533,8 +536,16 @@ def main():
     w = workloads.make_w(wl).to(dev)
     G = torch.empty((wl.n, wl.B), dtype=torch.float32, device=dev)
     m = torch.empty(wl.n, dtype=torch.float32, device=dev)
-    rec, _ = lpd.lpd_nystrom_factor_workspace(wl.n, wl.d, wl.B)
-    ws = lpd.alloc_workspace(wl.n, wl.d, wl.B, dev, int(rec * args.workspace_mult))
+    rec, mn = lpd.lpd_nystrom_factor_workspace(wl.n, wl.d, wl.B)
+    ws_bytes = int(rec * args.workspace_mult)
+    if args.panel_rows > 0:
+        # bytes per panel row from the two sizes the query reports (minimum: 256 rows; recommended: rec_rows rows)
+        ws = lpd.alloc_workspace(wl.n, wl.d, wl.B, dev, rec)
+        rec_rows = lpd.lpd_nystrom_factor_profiled(X, L, wl.gamma, W, G, ws, r=rank).panel_rows
+        del ws
+        row_bytes = (rec - mn) / max(rec_rows - 256, 1)
+        ws_bytes = int(mn + (args.panel_rows - 256 + 0.5) * row_bytes)
+    ws = lpd.alloc_workspace(wl.n, wl.d, wl.B, dev, ws_bytes)
     lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, lpd.GEMM_TILES[args.tile])
 
     def step(collect):

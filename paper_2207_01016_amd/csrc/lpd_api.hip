@@ -54,10 +54,14 @@ Carve carve(int64_t n, int64_t d, int64_t B)
     c.off_cen = c.off_nl + round_up(size_t(B) * 4, kAlign);
     c.off_z = c.off_cen + round_up(size_t(d) * 4, kAlign);
     c.min_rows = std::min<int64_t>(n, 256);
-    // recommended panel: about 64 Mi kernel values.  Rows = 64 Mi / B rounded to 256 makes the
-    // 256x256 tile count of a panel a multiple of the 256 CUs whenever B is a power of two
-    // (B >= 256), so the last round of workgroups of a launch is a full one.
-    int64_t rows = (int64_t(64) << 20) / std::max<int64_t>(B, 1);
+    // recommended panel: about 32 Mi kernel values = 128 MB, half of the 256 MB Infinity Cache, so that a panel
+    // written by the kernel-block launch can still be there when the whitening product reads it.  Rows =
+    // 32 Mi / B rounded to 256 makes the 256x256 tile count of a panel a multiple of the 256 CUs whenever B is a
+    // power of two (B >= 256): every round of workgroups of a launch is a full one (two rounds per launch).
+    // Measured, ms per step at 16 / 32 / 64 / 128 Mi values: 7562 / 7498 / 7476 / 7477 (n = 2,000,000, B = 16,384),
+    // 1509 / 1498 / 1497 (n = 1,280,000, B = 8,192; 32 Mi and up): flat from 32 Mi on, launches with fewer than 256
+    // tiles (below 16 Mi) leave compute units idle.
+    int64_t rows = (int64_t(32) << 20) / std::max<int64_t>(B, 1);
     rows = std::max<int64_t>(256, (rows + 128) / 256 * 256);
     c.rec_rows = std::min<int64_t>(rows, (n + 255) / 256 * 256);
     c.rec_rows = std::max<int64_t>(c.rec_rows, c.min_rows);

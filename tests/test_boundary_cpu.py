@@ -66,9 +66,9 @@ def test_workspace_query(L):
     assert rec.value % 256 == 0
     assert L.lpd_nystrom_factor_workspace(-1, 16, 128, ctypes.byref(rec), None) == -2
     assert L.lpd_nystrom_factor_workspace(10, 16, 128, None, None) == -1
-    # the recommended panel never exceeds about 64 Mi kernel values plus the norms
+    # the recommended panel never exceeds about 32 Mi kernel values (half the Infinity Cache) plus the norms
     assert L.lpd_nystrom_factor_workspace(2_000_000, 256, 16384, ctypes.byref(rec), ctypes.byref(mn)) == 0
-    assert rec.value < 4 * (2_000_000 + 16384 + (64 << 20) + 16384 * 300)
+    assert rec.value < 4 * (2_000_000 + 16384 + 256 + (32 << 20) + 16384 * 300)
 
 
 def test_factor_argument_errors(L):

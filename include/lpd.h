@@ -97,9 +97,12 @@ const char *lpd_strerror(int status);
  *                      software-pipelined across the barrier, 0 = plain load/compute/store
  *   LPD_OPT_CSR_ROUTE  route of the compressed-row entry points: 0 (default) = by density,
  *                      1 = dense panels, 2 = gather; set it before the workspace query
+ *   LPD_OPT_SMALL_PATH the factor for B <= 256 landmarks (and d <= 1024): 1 (default) = one
+ *                      launch per call, the kernel block stays in LDS; 0 = the panel schedule
  * Errors: LPD_ERR_SHAPE for an unknown option or value.
  */
-typedef enum { LPD_OPT_GEMM_TILE = 1, LPD_OPT_GEMM_PIPELINE = 2, LPD_OPT_CSR_ROUTE = 3 } lpd_option;
+typedef enum { LPD_OPT_GEMM_TILE = 1, LPD_OPT_GEMM_PIPELINE = 2, LPD_OPT_CSR_ROUTE = 3,
+               LPD_OPT_SMALL_PATH = 4 } lpd_option;
 int lpd_set_option(int option, int64_t value);
 
 /*
@@ -172,6 +175,8 @@ int lpd_nystrom_factor_workspace(int64_t n, int64_t d, int64_t B,
  * G[i, j] = 0 for r <= j < B, with Z[i,b] = exp(-gamma ||x_i - l_b||^2)
  * (Gaussian kernel of Section 5).  The n x B block Z is produced panel by
  * panel into the workspace and consumed at once; it never exists as a whole.
+ * With B <= 256 landmarks (and d <= 1024) the whole step is one kernel launch
+ * that keeps its rows of Z in LDS; the workspace is checked but not used.
  *
  *   X  device in   n x d, ldx          L  device in   B x d, ldl
  *   W  device in   r x B, ldw          G  device out  n x B, ldg
@@ -186,7 +191,10 @@ int lpd_nystrom_factor(const float *X, int64_t n, int64_t d, int64_t ldx,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Per-call device timing filled by lpd_nystrom_factor_profiled (milliseconds
- * summed over the launches of each kernel, from HIP events on `hip_stream`). */
+ * summed over the launches of each kernel, from HIP events on `hip_stream`).
+ * "norms" are the origin and the two row-norm kernels (3 launches).  The
+ * one-launch path for B <= 256 books its single launch under "whiten" and
+ * reports panel_rows = n. */
 typedef struct {
     int32_t launches_norms, launches_kernel_block, launches_whiten;
     int32_t panel_rows;

@@ -10,6 +10,7 @@
 
 #include "../../include/lpd.h"
 #include "cd_solver.hip.h"
+#include "fused_small.hip.h"
 #include "gemm_nt.hip.h"
 #include "rowops.hip.h"
 
@@ -90,6 +91,7 @@ enum TileId { TILE_AUTO = 0, TILE_128x128 = 1, TILE_256x128 = 2, TILE_256x256 = 
 std::atomic<int> g_pipe_option{1};            // LPD_OPT_GEMM_PIPELINE
 std::atomic<int> g_tile_option{TILE_AUTO};   // LPD_OPT_GEMM_TILE
 std::atomic<int> g_csr_route{0};              // LPD_OPT_CSR_ROUTE: 0 by density, 1 dense panel, 2 gather
+std::atomic<int> g_small_path{1};             // LPD_OPT_SMALL_PATH: 1 = one-launch factor for B <= 256, 0 = panel schedule
 
 int tile_choice(const GemmArgs &a)
 {
@@ -349,6 +351,27 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
     EventLog log;
     log.on = prof != nullptr;
 
+    // Few landmarks: the whole of step 1d in one launch (fused_small.hip.h); the workspace is not touched.
+    if (out_cols == B && B <= SM_MAXB && d <= SM_MAXD && g_small_path.load(std::memory_order_relaxed) != 0) {
+        SmallArgs a{};
+        a.X = X; a.L = L; a.W = W; a.G = G;
+        a.ldx = ldx; a.ldl = ldl; a.ldw = ldw; a.ldg = ldg;
+        a.n = int(n); a.d = int(d); a.B = int(B); a.r = int(r);
+        a.cen_rows = int(std::min<int64_t>(B, 32));
+        a.cen_step = int(B / a.cen_rows);
+        a.scale = -gamma * 1.44269504088896340736f;
+        const bool vec = d % 4 == 0 && B % 4 == 0 && ldx % 4 == 0 && ldl % 4 == 0 && aligned16(X) && aligned16(L) &&
+                         (r == 0 || (ldw % 4 == 0 && aligned16(W)));
+        const dim3 grid(unsigned((n + SM_TM - 1) / SM_TM));
+        LPD_HIP(log.begin(2, s));
+        if (vec) hipLaunchKernelGGL((nystrom_small_kernel<true>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((nystrom_small_kernel<false>), grid, dim3(256), 0, s, a);
+        LPD_HIP(hipGetLastError());
+        LPD_HIP(log.end(s));
+        panel = n;
+        goto readout;
+    }
+
     LPD_HIP(log.begin(0, s));
     LPD_HIP(launch_centred_norms(X, n, d, ldx, L, B, ldl, cen, nx, nl, s));
     LPD_HIP(log.end(s));
@@ -371,13 +394,14 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
         LPD_HIP(log.end(s));
     }
 
+readout:
     if (prof) {
         LPD_HIP(hipStreamSynchronize(s));
         prof->panel_rows = int32_t(panel);
         for (auto &sp : log.spans) {
             float ms = 0.f;
             LPD_HIP(hipEventElapsedTime(&ms, sp.a, sp.b));
-            if (sp.kind == 0) { prof->ms_norms += ms; prof->launches_norms += 2; }
+            if (sp.kind == 0) { prof->ms_norms += ms; prof->launches_norms += 3; }
             else if (sp.kind == 1) { prof->ms_kernel_block += ms; prof->launches_kernel_block += 1; }
             else { prof->ms_whiten += ms; prof->launches_whiten += 1; }
         }
@@ -545,6 +569,10 @@ int lpd_set_option(int option, int64_t value)
     }
     if (option == LPD_OPT_CSR_ROUTE && value >= 0 && value <= 2) {
         g_csr_route.store(int(value), std::memory_order_relaxed);
+        return LPD_OK;
+    }
+    if (option == LPD_OPT_SMALL_PATH && (value == 0 || value == 1)) {
+        g_small_path.store(int(value), std::memory_order_relaxed);
         return LPD_OK;
     }
     if (option == LPD_OPT_GEMM_PIPELINE && (value == 0 || value == 1)) {

@@ -199,15 +199,20 @@ def test_factor_is_deterministic_and_tile_independent(lpd, wls, dev):
 
 
 def test_factor_profiled_matches_plain(lpd, wls, dev):
-    wl = wls.WORKLOADS["small"].with_shape(n=5000, B=256)
-    X, idx, L, W, eig, rank = _prepare(lpd, wls, wl, dev)
-    G1 = _factor(lpd, X, L, wl.gamma, W, rank)
-    G2 = torch.empty_like(G1)
-    ws = lpd.alloc_workspace(wl.n, wl.d, wl.B, dev)
-    prof = lpd.lpd_nystrom_factor_profiled(X, L, wl.gamma, W.to(dev), G2, ws, r=rank)
-    assert torch.equal(G1, G2)
-    assert prof.launches_whiten == prof.launches_kernel_block >= 1
-    assert prof.ms_whiten > 0 and prof.ms_kernel_block > 0
+    for B in (320, 256):
+        wl = wls.WORKLOADS["small"].with_shape(n=5000, B=B)
+        X, idx, L, W, eig, rank = _prepare(lpd, wls, wl, dev)
+        G1 = _factor(lpd, X, L, wl.gamma, W, rank)
+        G2 = torch.empty_like(G1)
+        ws = lpd.alloc_workspace(wl.n, wl.d, wl.B, dev)
+        prof = lpd.lpd_nystrom_factor_profiled(X, L, wl.gamma, W.to(dev), G2, ws, r=rank)
+        assert torch.equal(G1, G2)
+        if B > 256:     # panel schedule: one kernel-block launch per whitening launch
+            assert prof.launches_whiten == prof.launches_kernel_block >= 1 and prof.launches_norms == 3
+            assert prof.ms_whiten > 0 and prof.ms_kernel_block > 0
+        else:           # one launch does it all and is booked under the whitening product
+            assert (prof.launches_whiten, prof.launches_kernel_block, prof.launches_norms) == (1, 0, 0)
+            assert prof.ms_whiten > 0 and prof.panel_rows == wl.n
 
 
 @pytest.mark.parametrize("chunk_rows,pinned,pad", [
@@ -244,6 +249,45 @@ def test_streaming_factor_zero_fills_dropped_components(lpd, wls, dev):
     lpd.lpd_nystrom_factor_to_host(X, L, wl.gamma, W.to(dev), host, chunk_rows=1024, r=r)
     assert torch.equal(host[:, r:], torch.zeros((wl.n, wl.B - r)))
     assert relfro(host.numpy(), G_dev.numpy()) <= 1e-6
+
+
+@pytest.mark.parametrize("n,d,B,r,gamma", [
+    (2000, 16, 128, 128, 1.0 / 16),     # the tiny workload's shape
+    (1, 7, 1, 1, 0.3),
+    (33, 19, 31, 31, 0.1),              # nothing a multiple of 4: element-wise loads
+    (700, 1024, 256, 256, 1.0 / 1024),  # the largest shape the one-launch kernel takes
+    (257, 64, 200, 137, 1.0 / 64),      # rank below B: zero-filled columns
+    (100, 12, 64, 0, 0.2),              # no component kept
+    (95, 0, 40, 40, 0.5),               # no features: all points coincide, Z = 1
+    (300, 20, 96, 96, 0.0),             # gamma = 0: Z = 1
+    (64, 33, 255, 255, 1.5),            # gamma dist ~ 100: kernel values underflow for most pairs
+])
+def test_one_launch_factor_for_few_landmarks(lpd, oracle, dev, n, d, B, r, gamma):
+    """B <= 256: step 1d as one kernel with its rows of Z in LDS, against the oracle and against the panel
+    schedule, on the shapes that bound it."""
+    g = torch.Generator().manual_seed(n * 7 + d * 3 + B)
+    X = 3.0 + torch.randn((n, d), generator=g)                       # an offset: the kernel shifts its origin
+    L = torch.cat([X[: min(n, B) // 2], 3.0 + torch.randn((B - min(n, B) // 2, d), generator=g)])
+    W = torch.randn((B, B), generator=g) / B ** 0.5
+    Xd, Ld, Wd = X.to(dev), L.to(dev), W.to(dev)
+    ws = lpd.alloc_workspace(n, d, B, dev)
+    out = []
+    for small in (1, 0):
+        G = torch.full((n, B + 3), float("nan"), device=dev)         # padded rows: ldg > B, not a multiple of 4
+        lpd.lpd_set_option(lpd.LPD_OPT_SMALL_PATH, small)
+        try:
+            lpd.lpd_nystrom_factor(Xd, Ld, gamma, Wd, G[:, :B], ws, r=r)
+            torch.cuda.synchronize()
+        finally:
+            lpd.lpd_set_option(lpd.LPD_OPT_SMALL_PATH, 1)
+        assert torch.isnan(G[:, B:]).all()
+        out.append(G[:, :B].cpu().numpy())
+    ref = oracle.nystrom_factor(X.numpy(), L.numpy(), gamma, W.numpy(), r=r)
+    for Gh in out:
+        assert np.all(np.isfinite(Gh)) and not Gh[:, r:].any()
+        if r:
+            assert relfro(Gh[:, :r], ref) <= TOL_G
+    assert relfro(out[0], out[1]) <= 2e-5 or r == 0
 
 
 def test_factor_zero_sizes(lpd, dev):

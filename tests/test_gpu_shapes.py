@@ -45,6 +45,15 @@ def test_factor_sweep_predict_on_awkward_shapes(oracle, n, d, B, r, pads, tile, 
     lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, lpd.GEMM_TILES[tile])
     try:
         lpd.lpd_nystrom_factor(X, L, gamma, W, G, ws, r=r)
+        G_panels = None
+        if B <= 256:
+            # few landmarks take the one-launch kernel; the panel schedule must give the same factor
+            G_panels = torch.full((n, B), float("nan"), device=dev)
+            lpd.lpd_set_option(lpd.LPD_OPT_SMALL_PATH, 0)
+            try:
+                lpd.lpd_nystrom_factor(X, L, gamma, W, G_panels, ws, r=r)
+            finally:
+                lpd.lpd_set_option(lpd.LPD_OPT_SMALL_PATH, 1)
         w = torch.randn(r, generator=g).to(dev)
         m = lpd.lpd_margins(G, w, r=r)
         c = int(1 + case % 5) if case % 2 else min(B, 33 + case)
@@ -58,6 +67,10 @@ def test_factor_sweep_predict_on_awkward_shapes(oracle, n, d, B, r, pads, tile, 
     Gh = G.cpu().numpy()
     assert relfro(Gh[:, :r], ref) <= 1e-4
     assert not Gh[:, r:].any()                                       # zero fill past r
+    if G_panels is not None:
+        Gp = G_panels.cpu().numpy()
+        assert relfro(Gp[:, :r], ref) <= 1e-4 and not Gp[:, r:].any()
+        assert relfro(Gh, Gp) <= 2e-5
     if pg:
         assert torch.isnan(Gf[:, B:]).all()                          # padding untouched
     assert relfro(m.cpu().numpy(), oracle.margins(np.ascontiguousarray(Gh), w.cpu().numpy(), r=r)) <= 1e-5

@@ -27,14 +27,23 @@ if ROOT not in sys.path:
 FP32_MFMA_PEAK_TFLOPS = 157.3   # 256 CU x 256 FLOP/clk x 2.4 GHz
 HBM_PEAK_GBPS = 8000.0
 
-# HBM bytes per whitening-product launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/), keyed by workload; None where not collected.
-MEASURED_TRAFFIC = {
-    # profiles/factor_and_sweep_cnn_hbm_traffic.txt: FETCH_SIZE 1.5676e6 KiB x 2.0 + WRITE_SIZE 2.6089e5 KiB x 1.0
-    "cnn": 1.5676e6 * 1024 * 2.0 + 2.6089e5 * 1024 * 1.0,
-    # profiles/factor_and_sweep_highrank_hbm_traffic.txt: FETCH_SIZE 3.1444e6 KiB x 2.0 + WRITE_SIZE 2.6176e5 KiB x 1.0
-    "highrank": 3.1444e6 * 1024 * 2.0 + 2.6176e5 * 1024 * 1.0,
-}
+
+
+def measured_traffic(workload, panel_rows):
+    """HBM-side bytes per launch of the dominant kernel and of the sweep, as the rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE runs recorded them in profiles/factor_and_sweep_<workload>_hbm_traffic.txt (the line starting with
+    '#@').  (None, None) when there is no such record or it was taken with another panel size."""
+    path = os.path.join(ROOT, "profiles", f"factor_and_sweep_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("#@"):
+                kv = dict(item.split("=", 1) for item in line[2:].split())
+                if int(kv.get("panel_rows", -1)) != int(panel_rows):
+                    return None, None
+                return float(kv["dominant_bytes_per_launch"]), float(kv["sweep_bytes_per_launch"])
+    except (OSError, ValueError, KeyError):
+        pass
+    return None, None
 
 
 def parse_args():
@@ -52,10 +61,13 @@ def parse_args():
     ap.add_argument("--panel-rows", type=int, default=0,
                     help="factor: size the workspace for kernel-block panels of this many rows (a multiple of 256; "
                          "0 = the library's recommendation)")
-    ap.add_argument("--path", default="factor", choices=["factor", "solver", "predict", "stream", "whiten", "sparse"],
+    ap.add_argument("--path", default="factor", choices=["factor", "solver", "predict", "stream", "whiten", "sparse",
+                                                         "calibrate"],
                     help="factor: Nystrom factor + margin sweep (default); solver: batched dual coordinate ascent "
                          "on G; predict: scores of new points; stream: the factor copied to pinned host memory as it is made; whiten: the one-off preparation "
-                         "(steps 1a-1c) on the device; sparse: the factor from X in compressed-row form")
+                         "(steps 1a-1c) on the device; sparse: the factor from X in compressed-row form; calibrate: a "
+                         "plain 1 GiB device-to-device copy, the known traffic the FETCH_SIZE / WRITE_SIZE counters "
+                         "are scaled by")
     ap.add_argument("--classifiers", type=int, default=10, help="predict: number of classifiers scored at once")
     ap.add_argument("--whiten", default="device", choices=["device", "host"],
                     help="steps 1a-1c (one-off preparation, outside the timed region): lpd_whiten on the GPU, or the "
@@ -70,7 +82,7 @@ def parse_args():
     args = ap.parse_args()
     if args.workload is None:
         args.workload = {"factor": "highrank", "predict": "cnn", "whiten": "cnn", "stream": "digit", "sparse": "digit",
-                         "solver": "small"}[args.path]
+                         "solver": "small", "calibrate": "tiny"}[args.path]
     return args
 
 
@@ -487,6 +499,24 @@ def bench_sparse(args):
     print(json.dumps(out))
 
 
+def bench_calibrate(args):
+    """A copy of known size for scaling the traffic counters: 1 GiB read, 1 GiB written, args.steps times."""
+    import torch
+    dev = torch.device("cuda:0")
+    n = 1 << 28
+    src = torch.ones(n, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    print(json.dumps({"metric": "copy_GBps", "value": 2.0 * 4 * n / sec / 1e9, "unit": "GB/s", "n_gpus": 1,
+                      "steps": args.steps, "bytes_read_per_copy": 4 * n, "bytes_written_per_copy": 4 * n,
+                      "kib_per_copy_each_way": 4 * n // 1024}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -515,6 +545,9 @@ def main():
         return
     if args.path == "sparse":
         bench_sparse(args)
+        return
+    if args.path == "calibrate":
+        bench_calibrate(args)
         return
     dev = torch.device("cuda:0")
     wl = workloads.WORKLOADS[args.workload]
@@ -614,6 +647,8 @@ def main():
     sweep_bytes = 4.0 * wl.n * rank
     sweep_gbps = sweep_bytes * steps / (ms_sweep * 1e-3) / 1e9
 
+    panel_rows = records[0][0].panel_rows if records else None
+    traffic_dominant, traffic_sweep = measured_traffic(wl.name, panel_rows)
     out = {
         "metric": "nystrom_factor_plus_margin_sweep_rows_per_s",
         "value": wl.n * steps / elapsed,
@@ -628,7 +663,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic" + (" (random W: tuning run, not a valid measurement)" if args.random_w else ""),
         "config": {"workload": wl.name, "n": wl.n, "d": wl.d, "B": wl.B, "rank": rank, "gamma": wl.gamma,
-                   "panel_rows": records[0][0].panel_rows if records else None, "gemm_tile": args.tile,
+                   "panel_rows": panel_rows, "gemm_tile": args.tile,
                    "choice": "largest of BASELINE.json's five configurations (all fit one GPU, its metric names none)"
                              if wl.name == "highrank" else "selected with --workload"},
         "factor": {"ms_per_step": ms_factor / steps, "rows_per_s": wl.n * steps / (ms_factor * 1e-3),
@@ -644,10 +679,10 @@ def main():
                      "achieved": whiten_tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": whiten_tflops / FP32_MFMA_PEAK_TFLOPS,
                      "flop_per_launch": flop_whiten_launch, "avg_launch_ms": ms_whiten / max(launches, 1),
-                     "launches": launches, "traffic": MEASURED_TRAFFIC.get(wl.name)},
+                     "launches": launches, "traffic": traffic_dominant},
         "roofline_sweep": {"kernel": "margins_kernel", "bound": "hbm", "achieved": sweep_gbps, "peak": HBM_PEAK_GBPS,
                            "unit": "GB/s", "frac": sweep_gbps / HBM_PEAK_GBPS, "bytes_per_launch": sweep_bytes,
-                           "avg_launch_ms": ms_sweep / steps, "traffic": None},
+                           "avg_launch_ms": ms_sweep / steps, "traffic": traffic_sweep},
     }
 
     if not args.no_cpu_baseline:

@@ -99,10 +99,13 @@ const char *lpd_strerror(int status);
  *                      1 = dense panels, 2 = gather; set it before the workspace query
  *   LPD_OPT_SMALL_PATH the factor for B <= 256 landmarks (and d <= 1024): 1 (default) = one
  *                      launch per call, the kernel block stays in LDS; 0 = the panel schedule
+ *   LPD_OPT_WHITEN_DC  lpd_whiten for B >= 512: 1 (default) = the tridiagonal problem is torn in two,
+ *                      the halves solved concurrently and merged on the device; 0 = one QL
+ *                      iteration over the whole matrix
  * Errors: LPD_ERR_SHAPE for an unknown option or value.
  */
 typedef enum { LPD_OPT_GEMM_TILE = 1, LPD_OPT_GEMM_PIPELINE = 2, LPD_OPT_CSR_ROUTE = 3,
-               LPD_OPT_SMALL_PATH = 4 } lpd_option;
+               LPD_OPT_SMALL_PATH = 4, LPD_OPT_WHITEN_DC = 5 } lpd_option;
 int lpd_set_option(int option, int64_t value);
 
 /*

@@ -13,6 +13,7 @@
 #include "fused_small.hip.h"
 #include "gemm_nt.hip.h"
 #include "rowops.hip.h"
+#include "whiten_internal.h"
 
 // Scratch of lpd_predict_noalloc: one array per GPU, held from the first use of the library on that GPU until
 // the process ends.  In host code the name is only a handle for hipGetSymbolAddress; kernels get the device
@@ -569,6 +570,10 @@ int lpd_set_option(int option, int64_t value)
     }
     if (option == LPD_OPT_CSR_ROUTE && value >= 0 && value <= 2) {
         g_csr_route.store(int(value), std::memory_order_relaxed);
+        return LPD_OK;
+    }
+    if (option == LPD_OPT_WHITEN_DC && (value == 0 || value == 1)) {
+        lpd_host::set_divide_and_conquer(int(value));
         return LPD_OK;
     }
     if (option == LPD_OPT_SMALL_PATH && (value == 0 || value == 1)) {

@@ -19,11 +19,15 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
+#include <numeric>
+#include <thread>
 #include <vector>
 
 #include "../../include/lpd.h"
@@ -582,6 +586,246 @@ __global__ __launch_bounds__(64 * RW) void rot_kernel(double *__restrict__ Zt, i
     }
 }
 
+// ---------------------------------------------------------------- step 1b, divide and conquer: one merge
+//
+// The tridiagonal matrix is torn at row m into two halves plus a rank-one term (Cuppen):
+//     T = diag(T1', T2') + rho u u^T,   rho = |e_{m-1}|,  u = e_{m-1} + sign(e_{m-1}) e_m,
+// T1', T2' being the halves with rho taken off the two diagonal entries next to the tear.  The halves are
+// solved by the QL iteration as before (two host threads, rotations applied to their own rows of Zt), which
+// leaves Zt = diag(Z1, Z2)^T Q^T and the problem D + rho z z^T with D the eigenvalues of the halves and
+// z = diag(Z1, Z2)^T u.  Its eigenpairs are found here, on the device:
+//   * z = Zt (Q u), where Q u = row m-1 + sign row m of Q^T is saved before the rotations start;
+//   * deflation (host, O(n log n)): components with rho |z_i| below tolerance keep their eigenpair; two close
+//     eigenvalues are rotated so that one of them gets a zero component (dc_rot_rows_kernel);
+//   * the k remaining eigenvalues are the roots of the secular equation 1 + rho sum_i z_i^2 / (d_i - x) = 0,
+//     one per interval between neighbouring d_i: one wavefront per root, measured from the nearer pole so that
+//     the differences d_i - x keep full relative accuracy (dc_secular_kernel);
+//   * the components are recomputed from the roots (Gu and Eisenstat: zhat_i^2 = prod_j (x_j - d_i) /
+//     prod_{j != i} (d_j - d_i)), which makes the eigenvectors u_j = (zhat_i / (d_i - x_j))_i orthogonal to
+//     working precision whatever the accuracy of the roots (dc_zhat_kernel, dc_colnorm_kernel, dc_fill_u_kernel);
+//   * rows of Zt <- U^T (rows of Zt): a double-precision matrix product (dgemm_tn_kernel).
+
+// uq[c] = Zt[m-1, c] + sgn * Zt[m, c]
+__global__ __launch_bounds__(256) void dc_save_u_kernel(const double *__restrict__ Zt, int n, int m, double sgn,
+                                                        double *__restrict__ uq)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c < n) uq[c] = Zt[int64_t(m - 1) * n + c] + sgn * Zt[int64_t(m) * n + c];
+}
+
+// z[r] = Zt[r, :] . uq for rows r0 <= r < r1, one wavefront per row
+__global__ __launch_bounds__(256) void dc_gemv_kernel(const double *__restrict__ Zt, int n, int r0, int r1,
+                                                      const double *__restrict__ uq, double *__restrict__ z)
+{
+    const int lane = threadIdx.x & 63;
+    const int r = r0 + blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= r1) return;
+    const double *row = Zt + int64_t(r) * n;
+    double s0 = 0.0, s1 = 0.0;
+    int c = lane;
+    for (; c + 64 < n; c += 128) { s0 += row[c] * uq[c]; s1 += row[c + 64] * uq[c + 64]; }
+    if (c < n) s0 += row[c] * uq[c];
+    s0 = wave_sum(s0 + s1);
+    if (lane == 0) z[r] = s0;
+}
+
+// The deflating rotations, in order: rows a = ra[t], b = rb[t]:  a <- c a + s b,  b <- c b - s a.
+// One thread per column; consecutive rotations share a row, so the chain is walked by each thread alone.
+__global__ __launch_bounds__(256) void dc_rot_rows_kernel(double *__restrict__ Zt, int n, int nrot,
+                                                          const int *__restrict__ ra, const int *__restrict__ rb,
+                                                          const double *__restrict__ cs)
+{
+    const int q = blockIdx.x * 256 + threadIdx.x;
+    if (q >= n) return;
+    for (int t = 0; t < nrot; ++t) {
+        const double c = cs[2 * t], sn = cs[2 * t + 1];
+        double *pa = Zt + int64_t(ra[t]) * n + q, *pb = Zt + int64_t(rb[t]) * n + q;
+        const double a = *pa, b = *pb;
+        *pa = c * a + sn * b;
+        *pb = c * b - sn * a;
+    }
+}
+
+// Root j of 1 + rho sum_i z_i^2 / (d_i - x) = 0 in (d_j, d_{j+1}) (the last one in (d_{k-1}, d_{k-1} + rho |z|^2]),
+// d ascending.  One wavefront per root.  x = d_org + mu with org the nearer of the two poles (decided by the
+// sign of the function at the midpoint), so f(mu) = R(mu) - a / mu with a = rho z_org^2 and R the sum over the
+// other poles, smooth and increasing on the bracket.  Newton steps on f, kept inside a bracket that the sign of
+// f narrows every iteration; a step that leaves the bracket is replaced by the fixed point a / R(mu), which
+// lands next to a root that hugs its pole, or by the midpoint.
+__global__ __launch_bounds__(64) void dc_secular_kernel(int k, const double *__restrict__ d, const double *__restrict__ z,
+                                                        double rho, double znorm2, double *__restrict__ mu_out,
+                                                        int *__restrict__ org_out)
+{
+    const int j = blockIdx.x, lane = threadIdx.x;
+    const double eps = 2.220446049250313e-16;
+    const bool last = j == k - 1;
+    const double gap = last ? rho * znorm2 : d[j + 1] - d[j];
+    // value, derivative and magnitude of f at mu measured from pole `org`
+    auto eval = [&](int org, double mu, double &f, double &fp, double &mag, double &R) {
+        const double dorg = d[org];
+        double sr = 0.0, sp = 0.0, sm = 0.0;
+        for (int i = lane; i < k; i += 64) {
+            if (i == org) continue;
+            const double zi = z[i];
+            const double t = zi / ((d[i] - dorg) - mu);
+            const double term = zi * t;
+            sr += term;
+            sp += t * t;
+            sm += fabs(term);
+        }
+        sr = wave_sum(sr); sp = wave_sum(sp); sm = wave_sum(sm);
+        const double a = rho * z[org] * z[org];
+        R = 1.0 + rho * sr;
+        f = R - a / mu;
+        fp = rho * sp + a / (mu * mu);
+        mag = 1.0 + rho * sm + fabs(a / mu);
+    };
+    int org = j;
+    double lo = 0.0, hi = last ? gap : 0.5 * gap;      // f(lo+) = -inf, f(hi) >= 0 when the root lies in the left half
+    double f, fp, mag, R;
+    if (!last) {
+        eval(j, 0.5 * gap, f, fp, mag, R);
+        if (f < 0.0) { org = j + 1; lo = -0.5 * gap; hi = 0.0; }    // root in the right half: measure from d_{j+1}
+    }
+    const double a = rho * z[org] * z[org];
+    double mu = 0.5 * (lo + hi);
+    for (int it = 0; it < 400; ++it) {
+        eval(org, mu, f, fp, mag, R);
+        if (fabs(f) <= 8.0 * eps * mag) break;
+        if (f > 0.0) hi = mu; else lo = mu;
+        if (hi - lo <= 2.0 * eps * fmax(fabs(lo), fabs(hi))) { mu = (f > 0.0) ? lo + 0.5 * (hi - lo) : mu; break; }
+        double next = mu - f / fp;
+        if (!(next > lo && next < hi)) {
+            const double fix = a / R;                    // root of R(mu) - a / x = 0 with R frozen
+            next = (fix > lo && fix < hi) ? fix : 0.5 * (lo + hi);
+        }
+        if (next == mu) break;
+        mu = next;
+    }
+    if (lane == 0) { mu_out[j] = mu; org_out[j] = org; }
+}
+
+// d_i - x_j with x_j = d[org_j] + mu_j
+__device__ __forceinline__ double dc_delta(const double *__restrict__ d, const double *__restrict__ mu,
+                                           const int *__restrict__ org, int i, int j)
+{
+    return (d[i] - d[org[j]]) - mu[j];
+}
+
+// zhat_i = sign(z_i) sqrt(| (d_i - x_i) prod_{j != i} (d_i - x_j) / (d_i - d_j) |); one wavefront per i, each lane a
+// contiguous run of j so that neighbouring ratios (which interlace) meet in the same partial product.
+__global__ __launch_bounds__(64) void dc_zhat_kernel(int k, const double *__restrict__ d, const double *__restrict__ z,
+                                                     const double *__restrict__ mu, const int *__restrict__ org,
+                                                     double *__restrict__ zhat)
+{
+    const int i = blockIdx.x, lane = threadIdx.x;
+    const int per = (k + 63) / 64;
+    const int j0 = lane * per, j1 = min(k, j0 + per);
+    double prod = 1.0;
+    for (int j = j0; j < j1; ++j) {
+        const double num = dc_delta(d, mu, org, i, j);
+        prod *= (j == i) ? num : num / (d[i] - d[j]);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) prod *= __shfl_xor(prod, off, 64);
+    if (lane == 0) zhat[i] = copysign(sqrt(fabs(prod)), z[i]);
+}
+
+// 1 / || (zhat_i / (d_i - x_j))_i ||, one wavefront per j
+__global__ __launch_bounds__(64) void dc_colnorm_kernel(int k, const double *__restrict__ d, const double *__restrict__ zhat,
+                                                        const double *__restrict__ mu, const int *__restrict__ org,
+                                                        double *__restrict__ inv_norm)
+{
+    const int j = blockIdx.x, lane = threadIdx.x;
+    double s = 0.0;
+    for (int i = lane; i < k; i += 64) {
+        const double v = zhat[i] / dc_delta(d, mu, org, i, j);
+        s += v * v;
+    }
+    s = wave_sum(s);
+    if (lane == 0) inv_norm[j] = 1.0 / sqrt(s);
+}
+
+// U[i, j] = zhat_i / (d_i - x_j) / norm_j, row-major k x k
+__global__ __launch_bounds__(256) void dc_fill_u_kernel(int k, const double *__restrict__ d, const double *__restrict__ zhat,
+                                                        const double *__restrict__ mu, const int *__restrict__ org,
+                                                        const double *__restrict__ inv_norm, double *__restrict__ U)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x, i = blockIdx.y;
+    if (j < k) U[int64_t(i) * k + j] = zhat[i] / dc_delta(d, mu, org, i, j) * inv_norm[j];
+}
+
+// T[i, :] = Zt[rows[i], :]
+__global__ __launch_bounds__(256) void dc_gather_kernel(const double *__restrict__ Zt, int n, const int *__restrict__ rows,
+                                                        double *__restrict__ T)
+{
+    const int i = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
+    if (c < n) T[int64_t(i) * n + c] = Zt[int64_t(rows[i]) * n + c];
+}
+
+// Zt[rows[j], c] = sum_i U[i, j] T[i, c]  (j < k, c < n, i < k): C = U^T T in double precision.  The contraction
+// index is the row index of both operands, so a slice of 8 rows of U and of T is two sets of contiguous runs:
+// 128 x 128 tile per workgroup, 8 x 8 per thread as 2-wide pieces 32 apart (conflict-free 16-byte LDS reads),
+// next slice fetched into registers while the current one is multiplied from LDS.
+__global__ __launch_bounds__(256) void dgemm_tn_kernel(const double *__restrict__ U, int k, const double *__restrict__ T,
+                                                       int n, const int *__restrict__ rows, double *__restrict__ Zt)
+{
+    constexpr int BT = 128, BK = 8;
+    __shared__ __attribute__((aligned(16))) double As[BK][BT], Bs[BK][BT];
+    const int j0 = blockIdx.y * BT, c0 = blockIdx.x * BT;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    // loader: thread -> (slice row lr, 4 consecutive columns lc)
+    const int lr = threadIdx.x >> 5, lc = (threadIdx.x & 31) * 4;
+    double acc[8][8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[p][q] = 0.0;
+    double ra[4], rb[4];
+    auto fetch = [&](int i0) {
+        const int i = i0 + lr;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            ra[e] = (i < k && j0 + lc + e < k) ? U[int64_t(i) * k + j0 + lc + e] : 0.0;
+            rb[e] = (i < k && c0 + lc + e < n) ? T[int64_t(i) * n + c0 + lc + e] : 0.0;
+        }
+    };
+    fetch(0);
+    for (int i0 = 0; i0 < k; i0 += BK) {
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { As[lr][lc + e] = ra[e]; Bs[lr][lc + e] = rb[e]; }
+        __syncthreads();
+        if (i0 + BK < k) fetch(i0 + BK);
+#pragma unroll
+        for (int kk = 0; kk < BK; ++kk) {
+            double a[8], b[8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const d2 av = *reinterpret_cast<const d2 *>(&As[kk][q * 32 + ty * 2]);
+                const d2 bv = *reinterpret_cast<const d2 *>(&Bs[kk][q * 32 + tx * 2]);
+                a[2 * q] = av.x; a[2 * q + 1] = av.y;
+                b[2 * q] = bv.x; b[2 * q + 1] = bv.y;
+            }
+#pragma unroll
+            for (int p = 0; p < 8; ++p)
+#pragma unroll
+                for (int q = 0; q < 8; ++q) acc[p][q] += a[p] * b[q];
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const int j = j0 + (p >> 1) * 32 + ty * 2 + (p & 1);
+        if (j >= k) continue;
+        double *out = Zt + int64_t(rows[j]) * n;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int c = c0 + (q >> 1) * 32 + tx * 2 + (q & 1);
+            if (c < n) out[c] = acc[p][q];
+        }
+    }
+}
+
 // ---------------------------------------------------------------- step 1c
 
 // Row j of W from eigenvector row ord[j] of Zt: scaled by 1/sqrt(lambda), sign chosen so that the entry
@@ -628,8 +872,17 @@ __global__ __launch_bounds__(256) void finish_kernel(const double *__restrict__ 
 
 struct DevCarve {
     size_t off_A, off_Zt, off_vec, off_panel, off_P, off_T, off_cs, off_tab, off_ord, off_lam, bytes;
-    size_t cs_doubles;     // capacity of ONE of the two rotation buffers, header included
+    size_t off_cs2, off_tab2, off_G, off_dc, off_uq;   // further QL instances, gathered rows, vectors of the merges
+    size_t cs_doubles;     // capacity of ONE of the rotation buffers, header included
+    size_t cs_bytes, tab_bytes;
 };
+
+constexpr int kDcMin = 512;      // matrices from this size on are torn apart and merged on the device
+constexpr int kMaxLeaves = 8;    // pieces the tridiagonal problem is torn into at most
+std::atomic<int> g_dc_enabled{1};
+
+// Depth of the tearing: 2^levels leaves.
+inline int dc_levels(int64_t n) { return n >= 8192 ? 3 : n >= 2048 ? 2 : n >= kDcMin ? 1 : 0; }
 
 DevCarve dev_carve(int64_t n)
 {
@@ -645,10 +898,21 @@ DevCarve dev_carve(int64_t n)
     c.off_P = o; o += round_up(nchunks * NB * NB * 8, kAlign);
     c.off_T = o; o += round_up(size_t(NB) * NB * 8, kAlign);
     c.cs_doubles = ROT_HDR + size_t(KSW) * 2 * size_t(std::max<int64_t>(n, 1));
-    c.off_cs = o; o += 2 * round_up(c.cs_doubles * 8, kAlign);
-    c.off_tab = o; o += round_up((size_t(n) + 2 * KSW + 2 * CH) * KSW * 2 * 8, kAlign);
+    c.cs_bytes = round_up(c.cs_doubles * 8, kAlign);
+    c.off_cs = o; o += 2 * c.cs_bytes;
+    c.tab_bytes = round_up((size_t(n) + 2 * KSW + 2 * CH) * KSW * 2 * 8, kAlign);
+    c.off_tab = o; o += c.tab_bytes;
     c.off_ord = o; o += round_up(size_t(n) * 4, kAlign);
     c.off_lam = o; o += vec;
+    // divide and conquer (n >= kDcMin): buffers of the further QL instances, the gathered rows of Zt (n x n),
+    // fourteen vectors (z, d, z kept, mu, zhat, 1/norm, rotation pairs (2), origin, rows, rotation rows (2), spare)
+    // and one saved vector Q u per tear
+    const size_t extra = size_t((1 << dc_levels(n)) - 1);
+    c.off_cs2 = o; o += extra * 2 * c.cs_bytes;
+    c.off_tab2 = o; o += extra * c.tab_bytes;
+    c.off_G = o; o += n >= kDcMin ? nn : 0;
+    c.off_dc = o; o += 14 * vec;
+    c.off_uq = o; o += extra * vec;
     c.bytes = o;
     return c;
 }
@@ -664,7 +928,223 @@ bool verbose()
         if ((call) != hipSuccess) { status = LPD_ERR_HIP; goto done; } \
     } while (0)
 
+// Page-locked staging and events of lpd_whiten: made at its first call (and when a larger matrix comes
+// along), kept until the process ends, so that repeated calls (one per kernel parameter of a grid search)
+// allocate nothing.  One call at a time uses it: lpd_whiten holds `mu` while it runs.
+struct Staging {
+    std::mutex mu;
+    int64_t n_cap = 0;
+    size_t cs_doubles = 0;
+    double *cs_h[2 * kMaxLeaves] = {};        // rotation batches: two per QL instance
+    hipEvent_t cs_free[2 * kMaxLeaves] = {};
+    hipEvent_t tri_done = nullptr;
+    double *dge_h = nullptr;                                  // 3 n doubles: tridiagonal matrix; order and eigenvalues
+    double *dc_h = nullptr;                                   // 8 n doubles: vectors of the merge
+    bool reserve(int64_t n, size_t cs_d)
+    {
+        if (n <= n_cap) return true;
+        for (int b = 0; b < 2 * kMaxLeaves; ++b) if (cs_h[b]) { (void)hipHostFree(cs_h[b]); cs_h[b] = nullptr; }
+        if (dge_h) { (void)hipHostFree(dge_h); dge_h = nullptr; }
+        if (dc_h) { (void)hipHostFree(dc_h); dc_h = nullptr; }
+        n_cap = 0;
+        for (int b = 0; b < 2 * (1 << dc_levels(n)); ++b)
+            if (hipHostMalloc(reinterpret_cast<void **>(&cs_h[b]), cs_d * 8, hipHostMallocDefault) != hipSuccess) return false;
+        if (hipHostMalloc(reinterpret_cast<void **>(&dge_h), size_t(n) * 8 * 3, hipHostMallocDefault) != hipSuccess) return false;
+        if (hipHostMalloc(reinterpret_cast<void **>(&dc_h), size_t(n) * 8 * 8, hipHostMallocDefault) != hipSuccess) return false;
+        for (int b = 0; b < 2 * kMaxLeaves; ++b)
+            if (!cs_free[b] && hipEventCreateWithFlags(&cs_free[b], hipEventDisableTiming) != hipSuccess) return false;
+        if (!tri_done && hipEventCreateWithFlags(&tri_done, hipEventDisableTiming) != hipSuccess) return false;
+        n_cap = n;
+        cs_doubles = cs_d;
+        return true;
+    }
+};
+Staging g_staging;
+
+// One QL iteration on rows row0 .. row0 + sz - 1 of the tridiagonal problem: the host finds the rotations,
+// the device applies them to those rows of Zt, 16 sweeps per pass, two batches in flight.
+struct QlRun {
+    int n = 0, row0 = 0, sz = 0;
+    double *Zt = nullptr;
+    hipStream_t s = nullptr;
+    double *cs_h[2] = {nullptr, nullptr};
+    hipEvent_t cs_free[2] = {nullptr, nullptr};
+    double *cs_d[2] = {nullptr, nullptr};
+    double *tab_d = nullptr;
+    size_t cs_doubles = 0;
+    int device = 0;
+    bool talk = false;
+    int64_t nbatch = 0;
+    int hip_fail = 0;        // 1: a HIP call failed, 2: a batch did not fit what it was promised
+    bool ok = false;
+
+    void run(double *dg, double *e)
+    {
+        if (hipSetDevice(device) != hipSuccess) { hip_fail = 1; return; }
+        // the QL iteration writes its rotations straight into the page-locked buffer of the batch, behind
+        // the header; the buffer is free once the copy queued from it two batches ago has run
+        auto buffer = [&]() -> double * {
+            const int b = int(nbatch & 1);
+            if (hip_fail || hipEventSynchronize(cs_free[b]) != hipSuccess) { hip_fail = hip_fail ? hip_fail : 1; return nullptr; }
+            return cs_h[b] + ROT_HDR;
+        };
+        auto apply = [&](const std::vector<lpd_host::Sweep> &sw, const double *cs, size_t ncs) {
+            if (hip_fail || sw.empty()) return;
+            const int b = int(nbatch & 1);
+            ++nbatch;
+            long long *hdr = reinterpret_cast<long long *>(cs_h[b]);
+            int imin = sz, imax = 0;
+            if (cs != cs_h[b] + ROT_HDR) { hip_fail = 2; return; }
+            for (int k = 0; k < KSW; ++k) { hdr[k] = 1; hdr[KSW + k] = 0; hdr[2 * KSW + k] = 0; }
+            for (size_t k = 0; k < sw.size() && k < size_t(KSW); ++k) {
+                hdr[k] = sw[k].lo + row0;
+                hdr[KSW + k] = sw[k].hi + row0;
+                hdr[2 * KSW + k] = (long long)sw[k].off;
+                imin = std::min(imin, int(sw[k].lo));
+                imax = std::max(imax, int(sw[k].hi));
+            }
+            if (ROT_HDR + ncs > cs_doubles || sw.size() > size_t(KSW) || imax + 1 >= sz || imin < 0 || imin > imax) {
+                hip_fail = 2;
+                return;
+            }
+            if (hipMemcpyAsync(cs_d[b], cs_h[b], (ROT_HDR + ncs) * 8, hipMemcpyHostToDevice, s) != hipSuccess ||
+                hipEventRecord(cs_free[b], s) != hipSuccess) { hip_fail = 1; return; }
+            const int top = imax + 1 + row0, bottom = imin + row0;
+            const int nsteps = (top - bottom) + 2 * KSW;            // t = 0 .. t_last
+            const int nchunks = (nsteps + CH - 1) / CH;
+            const int tab_steps = (nchunks + 1) * CH;               // the later waves read RW - 1 steps further
+            hipLaunchKernelGGL(rot_table_kernel, dim3((tab_steps * KSW + 255) / 256), dim3(256), 0, s,
+                               reinterpret_cast<const long long *>(cs_d[b]), cs_d[b] + ROT_HDR, top, tab_steps, tab_d);
+            hipLaunchKernelGGL(rot_kernel, dim3((n + 63) / 64), dim3(64 * RW), 0, s, Zt, n, bottom, top, nchunks, tab_d);
+            if (hipGetLastError() != hipSuccess) hip_fail = 1;
+        };
+        int last_decile = -1;
+        auto prog = [&](int64_t l) {
+            const int dec = int(l * 10 / std::max(sz, 1));
+            if (talk && dec != last_decile) {
+                last_decile = dec;
+                std::fprintf(stderr, "[lpd_whiten B=%d] QL iteration on rows %d..%d: %d%%\n", n, row0, row0 + sz - 1, dec * 10);
+                std::fflush(stderr);
+            }
+        };
+        ok = lpd_host::tridiag_ql(dg, e, sz, KSW, buffer, apply, prog);
+    }
+};
+
+// Pointers into the workspace that the merge uses.
+struct DcBuffers {
+    double *Zt, *U, *G;                 // n x n each; U overlays the matrix that held the reflectors
+    double *z, *dk, *zk, *mu, *zhat, *inv_norm, *rotcs;
+    int *org, *rows, *ra, *rb;
+};
+
+// One tear of the tridiagonal matrix: rows r0 .. r0 + sz - 1 fall into [r0, m) and [m, r0 + sz).
+struct Tear { int r0, sz, m; double rho, sgn; double *uq; };
+
+// The merge of the two solved halves of a tear (see the kernels above).  dg: eigenvalues by row of Zt, those of
+// the halves on entry, those of the block on exit.  stage: 8 n doubles of page-locked memory.
+int dc_merge(int n, const Tear &tr, std::vector<double> &dg, const DcBuffers &b, double *stage, hipStream_t s, bool talk)
+{
+    const int r0 = tr.r0, r1 = tr.r0 + tr.sz;
+    double rho = tr.rho;
+    const double eps = 2.220446049250313e-16;
+    double *z_h = stage, *dk_h = stage + n, *zk_h = stage + 2 * size_t(n), *rot_h = stage + 3 * size_t(n),
+           *mu_h = stage + 5 * size_t(n);
+    int *rows_h = reinterpret_cast<int *>(stage + 6 * size_t(n)), *ra_h = rows_h + n, *rb_h = ra_h + n, *org_h = rb_h + n;
+
+    hipLaunchKernelGGL(dc_gemv_kernel, dim3((tr.sz + 3) / 4), dim3(256), 0, s, b.Zt, n, r0, r1, tr.uq, b.z);
+    if (hipGetLastError() != hipSuccess ||
+        hipMemcpyAsync(z_h + r0, b.z + r0, size_t(tr.sz) * 8, hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return LPD_ERR_HIP;
+
+    // z has norm sqrt(2) (one unit row of each half): scale it to 1 and rho with it
+    double zz = 0.0;
+    for (int i = r0; i < r1; ++i) zz += z_h[i] * z_h[i];
+    if (!(zz > 0.0) || !std::isfinite(zz)) return LPD_ERR_NUMERIC;
+    const double zs = 1.0 / std::sqrt(zz);
+    for (int i = r0; i < r1; ++i) z_h[i] *= zs;
+    rho *= zz;
+
+    double dmax = 0.0, zmax = 0.0;
+    for (int i = r0; i < r1; ++i) { dmax = std::max(dmax, std::fabs(dg[size_t(i)])); zmax = std::max(zmax, std::fabs(z_h[i])); }
+    const double tol = 8.0 * eps * std::max(dmax, zmax);
+    if (rho * zmax <= tol) return LPD_OK;           // the halves do not see each other: nothing to merge
+
+    std::vector<int> perm(size_t(tr.sz), 0);
+    std::iota(perm.begin(), perm.end(), r0);
+    std::stable_sort(perm.begin(), perm.end(), [&](int a, int c) { return dg[size_t(a)] < dg[size_t(c)]; });
+    int k = 0, nrot = 0, pj = -1;
+    for (int idx = 0; idx < tr.sz; ++idx) {
+        const int i = perm[size_t(idx)];
+        if (rho * std::fabs(z_h[i]) <= tol) continue;        // its eigenpair stands as it is
+        if (pj < 0) { pj = i; continue; }
+        double sn = z_h[pj], c = z_h[i];
+        const double tau = std::hypot(c, sn);
+        const double t = dg[size_t(i)] - dg[size_t(pj)];
+        c /= tau;
+        sn = -sn / tau;
+        if (std::fabs(t * c * sn) <= tol) {
+            // two eigenvalues too close to tell apart: rotate their vectors so that pj carries no component
+            z_h[i] = tau;
+            z_h[pj] = 0.0;
+            ra_h[nrot] = pj; rb_h[nrot] = i;
+            rot_h[2 * nrot] = c; rot_h[2 * nrot + 1] = sn;
+            ++nrot;
+            const double dp = dg[size_t(pj)], di = dg[size_t(i)];
+            dg[size_t(pj)] = dp * c * c + di * sn * sn;
+            dg[size_t(i)] = dp * sn * sn + di * c * c;
+        } else {
+            rows_h[k++] = pj;
+        }
+        pj = i;
+    }
+    if (pj >= 0) rows_h[k++] = pj;
+    double zn2 = 0.0;
+    for (int i = 0; i < k; ++i) { dk_h[i] = dg[size_t(rows_h[i])]; zk_h[i] = z_h[rows_h[i]]; zn2 += zk_h[i] * zk_h[i]; }
+    for (int i = 1; i < k; ++i)
+        if (!(dk_h[i] > dk_h[i - 1])) return LPD_ERR_NUMERIC;    // cannot happen: equal values deflate
+    if (talk) {
+        std::fprintf(stderr, "[lpd_whiten B=%d] merge of rows %d..%d: %d of %d eigenvalues from the secular equation, "
+                     "%d deflating rotations\n", n, r0, r1 - 1, k, tr.sz, nrot);
+        std::fflush(stderr);
+    }
+    if (k == 0) return LPD_OK;
+
+    if (hipMemcpyAsync(b.dk, dk_h, size_t(k) * 8, hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipMemcpyAsync(b.zk, zk_h, size_t(k) * 8, hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipMemcpyAsync(b.rows, rows_h, size_t(k) * 4, hipMemcpyHostToDevice, s) != hipSuccess)
+        return LPD_ERR_HIP;
+    if (nrot > 0) {
+        if (hipMemcpyAsync(b.ra, ra_h, size_t(nrot) * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(b.rb, rb_h, size_t(nrot) * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(b.rotcs, rot_h, size_t(nrot) * 16, hipMemcpyHostToDevice, s) != hipSuccess)
+            return LPD_ERR_HIP;
+        hipLaunchKernelGGL(dc_rot_rows_kernel, dim3((n + 255) / 256), dim3(256), 0, s, b.Zt, n, nrot, b.ra, b.rb, b.rotcs);
+    }
+    hipLaunchKernelGGL(dc_secular_kernel, dim3(k), dim3(64), 0, s, k, b.dk, b.zk, rho, zn2, b.mu, b.org);
+    hipLaunchKernelGGL(dc_zhat_kernel, dim3(k), dim3(64), 0, s, k, b.dk, b.zk, b.mu, b.org, b.zhat);
+    hipLaunchKernelGGL(dc_colnorm_kernel, dim3(k), dim3(64), 0, s, k, b.dk, b.zhat, b.mu, b.org, b.inv_norm);
+    hipLaunchKernelGGL(dc_fill_u_kernel, dim3((k + 255) / 256, k), dim3(256), 0, s, k, b.dk, b.zhat, b.mu, b.org,
+                       b.inv_norm, b.U);
+    hipLaunchKernelGGL(dc_gather_kernel, dim3((n + 255) / 256, k), dim3(256), 0, s, b.Zt, n, b.rows, b.G);
+    hipLaunchKernelGGL(dgemm_tn_kernel, dim3((n + 127) / 128, (k + 127) / 128), dim3(256), 0, s, b.U, k, b.G, n, b.rows, b.Zt);
+    if (hipGetLastError() != hipSuccess ||
+        hipMemcpyAsync(mu_h, b.mu, size_t(k) * 8, hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipMemcpyAsync(org_h, b.org, size_t(k) * 4, hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return LPD_ERR_HIP;
+    for (int j = 0; j < k; ++j) {
+        const double lam = dk_h[org_h[j]] + mu_h[j];
+        if (!std::isfinite(lam)) return LPD_ERR_NUMERIC;
+        dg[size_t(rows_h[j])] = lam;
+    }
+    return LPD_OK;
+}
+
 }  // namespace
+
+void lpd_host::set_divide_and_conquer(int on) { g_dc_enabled.store(on ? 1 : 0, std::memory_order_relaxed); }
 
 extern "C" int lpd_whiten_workspace(int64_t B, size_t *bytes)
 {
@@ -726,22 +1206,37 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
     if (phase_seconds)
         for (int k = 0; k < 5; ++k) phase_seconds[k] = 0.0;
 
-    // page-locked staging: rotation batches (two in flight), the tridiagonal matrix, order and eigenvalues
-    double *cs_h[2] = {nullptr, nullptr};
+    // page-locked staging (rotation batches, the tridiagonal matrix, order and eigenvalues, the vectors of the
+    // merge) and events: the process-wide set, made at the first call; held for the duration of this one
+    std::lock_guard<std::mutex> staging_lock(g_staging.mu);
     double *dge_h = nullptr;
-    hipEvent_t cs_free[2] = {nullptr, nullptr}, tri_done = nullptr;
+    hipEvent_t tri_done = nullptr;
     std::vector<double> dg(size_t(n), 0.0), e(size_t(n), 0.0);
     std::vector<int64_t> ord;
-    bool ql_ok = true;
-    int hip_fail = 0;
+    std::vector<Tear> tears;                  // children before parents
+    std::vector<std::pair<int, int>> leaves;  // (first row, rows)
+    QlRun ql[kMaxLeaves];
+    int device = 0;
     int64_t r = 0;
+    const int levels = g_dc_enabled.load(std::memory_order_relaxed) != 0 ? dc_levels(n) : 0;
+    const int nleaves = 1 << levels;
 
-    LPD_HIP(hipHostMalloc(reinterpret_cast<void **>(&cs_h[0]), cv.cs_doubles * 8, hipHostMallocDefault));
-    LPD_HIP(hipHostMalloc(reinterpret_cast<void **>(&cs_h[1]), cv.cs_doubles * 8, hipHostMallocDefault));
-    LPD_HIP(hipHostMalloc(reinterpret_cast<void **>(&dge_h), size_t(n) * 8 * 3, hipHostMallocDefault));
-    LPD_HIP(hipEventCreateWithFlags(&cs_free[0], hipEventDisableTiming));
-    LPD_HIP(hipEventCreateWithFlags(&cs_free[1], hipEventDisableTiming));
-    LPD_HIP(hipEventCreateWithFlags(&tri_done, hipEventDisableTiming));
+    if (!g_staging.reserve(n, cv.cs_doubles)) { status = LPD_ERR_HIP; goto done; }
+    dge_h = g_staging.dge_h;
+    tri_done = g_staging.tri_done;
+    LPD_HIP(hipGetDevice(&device));
+    for (int q = 0; q < nleaves; ++q) {
+        ql[q].n = n; ql[q].Zt = Zt; ql[q].s = s; ql[q].device = device; ql[q].talk = talk;
+        ql[q].cs_doubles = cv.cs_doubles;
+        for (int b = 0; b < 2; ++b) {
+            // an event that was never recorded counts as complete; one left over from an earlier call has long run
+            ql[q].cs_h[b] = g_staging.cs_h[2 * q + b];
+            ql[q].cs_free[b] = g_staging.cs_free[2 * q + b];
+            ql[q].cs_d[b] = reinterpret_cast<double *>(
+                ws + (q == 0 ? cv.off_cs + size_t(b) * cv.cs_bytes : cv.off_cs2 + size_t(2 * (q - 1) + b) * cv.cs_bytes));
+        }
+        ql[q].tab_d = reinterpret_cast<double *>(ws + (q == 0 ? cv.off_tab : cv.off_tab2 + size_t(q - 1) * cv.tab_bytes));
+    }
 
     say("landmark kernel matrix");
     {
@@ -814,59 +1309,74 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
     if (n == 1) e[0] = 0.0;
 
     say("QL iteration (host) with rotation passes (device)");
-    {
-        int64_t nbatch = 0;
-        // the QL iteration writes its rotations straight into the page-locked buffer of the batch, behind
-        // the header; the buffer is free once the copy queued from it two batches ago has run
-        auto buffer = [&]() -> double * {
-            const int b = int(nbatch & 1);
-            if (hip_fail || hipEventSynchronize(cs_free[b]) != hipSuccess) { hip_fail = hip_fail ? hip_fail : 1; return nullptr; }
-            return cs_h[b] + ROT_HDR;
-        };
-        auto apply = [&](const std::vector<lpd_host::Sweep> &sw, const double *cs, size_t ncs) {
-            if (hip_fail || sw.empty()) return;
-            const int b = int(nbatch & 1);
-            ++nbatch;
-            long long *hdr = reinterpret_cast<long long *>(cs_h[b]);
-            int imin = n, imax = 0;
-            if (cs != cs_h[b] + ROT_HDR) { hip_fail = 2; return; }
-            for (int k = 0; k < KSW; ++k) { hdr[k] = 1; hdr[KSW + k] = 0; hdr[2 * KSW + k] = 0; }
-            for (size_t k = 0; k < sw.size() && k < size_t(KSW); ++k) {
-                hdr[k] = sw[k].lo;
-                hdr[KSW + k] = sw[k].hi;
-                hdr[2 * KSW + k] = (long long)sw[k].off;
-                imin = std::min(imin, int(sw[k].lo));
-                imax = std::max(imax, int(sw[k].hi));
+    if (levels == 0) {
+        ql[0].row0 = 0; ql[0].sz = n;
+        ql[0].run(dg.data(), e.data());
+        if (ql[0].hip_fail) { status = ql[0].hip_fail == 1 ? LPD_ERR_HIP : LPD_ERR_NUMERIC; goto done; }
+        if (!ql[0].ok) { status = LPD_ERR_NUMERIC; goto done; }
+    } else {
+        // Tear the matrix into 2^levels leaves.  A tear at row m takes rho = |e_{m-1}| off the two diagonal entries
+        // next to it and cuts the coupling; what it removed returns in its merge as rho u u^T with
+        // u = e_{m-1} + sign e_m.  Q u = row (m - 1) + sign * row m of Q^T is saved now, before any rotation.
+        {
+            struct Span { int r0, sz, level; };
+            std::vector<Span> stack{{0, n, levels}};
+            std::vector<Tear> pre;                                    // parents before children
+            while (!stack.empty()) {
+                const Span sp = stack.back();
+                stack.pop_back();
+                if (sp.level == 0) { leaves.push_back({sp.r0, sp.sz}); continue; }
+                const int m = sp.r0 + sp.sz / 2;
+                Tear t{sp.r0, sp.sz, m, std::fabs(e[size_t(m) - 1]), e[size_t(m) - 1] < 0.0 ? -1.0 : 1.0, nullptr};
+                pre.push_back(t);
+                stack.push_back({m, sp.r0 + sp.sz - m, sp.level - 1});
+                stack.push_back({sp.r0, m - sp.r0, sp.level - 1});
             }
-            if (ROT_HDR + ncs > cv.cs_doubles || sw.size() > size_t(KSW) || imax + 1 >= n || imin < 0 || imin > imax) {
-                hip_fail = 2;
-                return;
+            std::sort(leaves.begin(), leaves.end());
+            tears.assign(pre.rbegin(), pre.rend());                   // every parent now comes after its children
+        }
+        for (size_t t = 0; t < tears.size(); ++t) {
+            Tear &tr = tears[t];
+            tr.uq = reinterpret_cast<double *>(ws + cv.off_uq + t * vec);
+            dg[size_t(tr.m) - 1] -= tr.rho;
+            dg[size_t(tr.m)] -= tr.rho;
+            e[size_t(tr.m) - 1] = 0.0;
+            hipLaunchKernelGGL(dc_save_u_kernel, dim3((n + 255) / 256), dim3(256), 0, s, Zt, n, tr.m, tr.sgn, tr.uq);
+        }
+        LPD_HIP(hipGetLastError());
+        // one QL iteration per leaf, each on its own host thread and its own rows of dg, e and Zt
+        {
+            std::vector<std::thread> workers;
+            for (int q = 0; q < nleaves; ++q) {
+                ql[q].row0 = leaves[size_t(q)].first;
+                ql[q].sz = leaves[size_t(q)].second;
             }
-            if (hipMemcpyAsync(cs_d[b], cs_h[b], (ROT_HDR + ncs) * 8, hipMemcpyHostToDevice, s) != hipSuccess ||
-                hipEventRecord(cs_free[b], s) != hipSuccess) { hip_fail = 1; return; }
-            const int top = imax + 1;
-            const int nsteps = (top - imin) + 2 * KSW;              // t = 0 .. t_last
-            const int nchunks = (nsteps + CH - 1) / CH;
-            const int tab_steps = (nchunks + 1) * CH;               // the later waves read RW - 1 steps further
-            hipLaunchKernelGGL(rot_table_kernel, dim3((tab_steps * KSW + 255) / 256), dim3(256), 0, s,
-                               reinterpret_cast<const long long *>(cs_d[b]), cs_d[b] + ROT_HDR, top, tab_steps, tab_d);
-            hipLaunchKernelGGL(rot_kernel, dim3((n + 63) / 64), dim3(64 * RW), 0, s, Zt, n, imin, top, nchunks,
-                               tab_d);
-            if (hipGetLastError() != hipSuccess) hip_fail = 1;
-        };
-        int last_decile = -1;
-        auto prog = [&](int64_t l) {
-            const int dec = int(l * 10 / n);
-            if (talk && dec != last_decile) {
-                last_decile = dec;
-                std::fprintf(stderr, "[lpd_whiten B=%d] QL iteration %d%%\n", n, dec * 10);
-                std::fflush(stderr);
+            for (int q = 1; q < nleaves; ++q)
+                workers.emplace_back([&, q]() { ql[q].run(dg.data() + ql[q].row0, e.data() + ql[q].row0); });
+            ql[0].run(dg.data() + ql[0].row0, e.data() + ql[0].row0);
+            for (auto &w : workers) w.join();
+        }
+        for (int q = 0; q < nleaves; ++q) {
+            if (ql[q].hip_fail) { status = ql[q].hip_fail == 1 ? LPD_ERR_HIP : LPD_ERR_NUMERIC; goto done; }
+            if (!ql[q].ok) { status = LPD_ERR_NUMERIC; goto done; }
+        }
+        {
+            auto dcv = [&](int k) { return ws + cv.off_dc + size_t(k) * vec; };
+            DcBuffers bufs;
+            bufs.Zt = Zt; bufs.U = A; bufs.G = reinterpret_cast<double *>(ws + cv.off_G);
+            bufs.z = reinterpret_cast<double *>(dcv(1));
+            bufs.dk = reinterpret_cast<double *>(dcv(2)); bufs.zk = reinterpret_cast<double *>(dcv(3));
+            bufs.mu = reinterpret_cast<double *>(dcv(4)); bufs.zhat = reinterpret_cast<double *>(dcv(5));
+            bufs.inv_norm = reinterpret_cast<double *>(dcv(6)); bufs.rotcs = reinterpret_cast<double *>(dcv(7));   // 2 n doubles
+            bufs.org = reinterpret_cast<int *>(dcv(9)); bufs.rows = reinterpret_cast<int *>(dcv(10));
+            bufs.ra = reinterpret_cast<int *>(dcv(11)); bufs.rb = reinterpret_cast<int *>(dcv(12));
+            for (const Tear &tr : tears) {
+                if (!(tr.rho > 0.0)) continue;              // the halves were never coupled
+                status = dc_merge(n, tr, dg, bufs, g_staging.dc_h, s, talk);
+                if (status != LPD_OK) goto done;
             }
-        };
-        ql_ok = lpd_host::tridiag_ql(dg.data(), e.data(), n, KSW, buffer, apply, prog);
+        }
     }
-    if (hip_fail) { status = hip_fail == 1 ? LPD_ERR_HIP : LPD_ERR_NUMERIC; goto done; }
-    if (!ql_ok) { status = LPD_ERR_NUMERIC; goto done; }
 
     say("ordering and scaling");
     r = lpd_host::order_and_clip(dg.data(), n, clip_ratio, ord, eig_host);
@@ -886,11 +1396,5 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
     say("done");
 done:
     if (hipStreamSynchronize(s) != hipSuccess && status == LPD_OK) status = LPD_ERR_HIP;
-    for (int b = 0; b < 2; ++b) {
-        if (cs_free[b]) (void)hipEventDestroy(cs_free[b]);
-        if (cs_h[b]) (void)hipHostFree(cs_h[b]);
-    }
-    if (tri_done) (void)hipEventDestroy(tri_done);
-    if (dge_h) (void)hipHostFree(dge_h);
     return status;
 }

@@ -31,4 +31,8 @@ bool tridiag_ql(double *dg, double *e, int64_t n, int batch, const RotationBuffe
 int64_t order_and_clip(const double *dg, int64_t n, double clip_ratio, std::vector<int64_t> &ord,
                        double *eig_sorted);
 
+// Switch of the device routine: 1 (default) = matrices of 512 rows and more are torn in two, the halves solved
+// by two concurrent QL iterations and merged on the device; 0 = one QL iteration over the whole matrix.
+void set_divide_and_conquer(int on);
+
 }  // namespace lpd_host

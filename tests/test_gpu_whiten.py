@@ -164,3 +164,51 @@ def test_whiten_digit_workload_at_full_landmark_count(lpd, oracle, dev):
     Wd = W.double()
     P = Wd @ torch.from_numpy(K).to(dev) @ Wd.T
     assert float((P - torch.eye(wl.B, dtype=torch.float64, device=dev)).norm()) <= 2e-6 * wl.B
+
+
+@pytest.mark.parametrize("name,B", [("highrank", 1030), ("small", 2100), ("digit", 600)])
+def test_torn_and_whole_problem_agree(lpd, oracle, dev, name, B):
+    """From 512 landmarks on the tridiagonal problem is torn into 2 (4 from 2,048 on) leaves that are solved
+    side by side and merged on the device.  Both ways must give the oracle's eigenvalues, the same rank, and
+    the same basis-independent W^T W; the rows agree up to rotations within (near-)repeated eigenvalues."""
+    from paper_2207_01016_amd import workloads
+    wl = workloads.WORKLOADS[name].with_shape(n=max(2 * B, 1000), B=B)
+    X = workloads.make_X(wl)
+    Lm = X[workloads.landmark_indices(wl)].contiguous()
+    out = {}
+    for dc in (1, 0):
+        lpd.lpd_set_option(lpd.LPD_OPT_WHITEN_DC, dc)
+        try:
+            out[dc] = lpd.lpd_whiten(Lm.to(dev), wl.gamma)
+        finally:
+            lpd.lpd_set_option(lpd.LPD_OPT_WHITEN_DC, 1)
+    Wo, eo, ro, K = oracle.whiten(Lm.numpy(), wl.gamma, method="lapack")
+    for dc in (1, 0):
+        W, eig, rank = out[dc]
+        assert rank == ro
+        assert np.max(np.abs(eig.numpy() - eo)) <= 1e-10 * eo[0], dc
+        Wd = W.double().cpu().numpy()[:rank]
+        assert np.linalg.norm(Wd @ K @ Wd.T - np.eye(rank)) <= 2e-6 * B, dc
+    A1, A0 = out[1][0].double()[:ro], out[0][0].double()[:ro]
+    G1, G0 = A1.T @ A1, A0.T @ A0
+    assert float((G1 - G0).norm() / G0.norm()) <= 1e-5
+
+
+def test_whiten_8192_landmarks_three_levels_of_tearing(lpd, dev):
+    """8,192 landmarks of the cnn-shaped workload: eight leaves, seven merges.  Checked against a library
+    eigenvalue routine on the device (double precision) and by W K W^T = I."""
+    from paper_2207_01016_amd import workloads
+    wl = workloads.WORKLOADS["cnn"].with_rows(32768)
+    X = workloads.make_X(wl, dev)
+    Lm = X[workloads.landmark_indices(wl).to(dev)].contiguous()
+    W, eig, rank = lpd.lpd_whiten(Lm, wl.gamma)
+    assert rank == wl.B
+    Ld = Lm.double()
+    sq = (Ld * Ld).sum(1)
+    K = torch.exp(-wl.gamma * (sq[:, None] + sq[None, :] - 2.0 * Ld @ Ld.T).clamp_(min=0.0))
+    K.fill_diagonal_(1.0)
+    ref = torch.linalg.eigvalsh(K).flip(0).cpu().numpy()
+    assert np.max(np.abs(eig.numpy() - ref)) <= 1e-9 * ref[0]
+    Wd = W.double()
+    P = Wd @ K @ Wd.T
+    assert float((P - torch.eye(wl.B, dtype=torch.float64, device=dev)).norm()) <= 2e-6 * wl.B

@@ -102,10 +102,12 @@ const char *lpd_strerror(int status);
  *   LPD_OPT_WHITEN_DC  lpd_whiten for B >= 512: 1 (default) = the tridiagonal problem is torn in two,
  *                      the halves solved concurrently and merged on the device; 0 = one QL
  *                      iteration over the whole matrix
+ *   LPD_OPT_WHITEN_UPPER  lpd_whiten's reduction to tridiagonal form: 1 (default) = reads and updates the
+ *                      upper triangle of the trailing matrix only, 0 = the whole symmetric matrix
  * Errors: LPD_ERR_SHAPE for an unknown option or value.
  */
 typedef enum { LPD_OPT_GEMM_TILE = 1, LPD_OPT_GEMM_PIPELINE = 2, LPD_OPT_CSR_ROUTE = 3,
-               LPD_OPT_SMALL_PATH = 4, LPD_OPT_WHITEN_DC = 5 } lpd_option;
+               LPD_OPT_SMALL_PATH = 4, LPD_OPT_WHITEN_DC = 5, LPD_OPT_WHITEN_UPPER = 6 } lpd_option;
 int lpd_set_option(int option, int64_t value);
 
 /*

@@ -572,6 +572,10 @@ int lpd_set_option(int option, int64_t value)
         g_csr_route.store(int(value), std::memory_order_relaxed);
         return LPD_OK;
     }
+    if (option == LPD_OPT_WHITEN_UPPER && (value == 0 || value == 1)) {
+        lpd_host::set_upper_triangle_pass(int(value));
+        return LPD_OK;
+    }
     if (option == LPD_OPT_WHITEN_DC && (value == 0 || value == 1)) {
         lpd_host::set_divide_and_conquer(int(value));
         return LPD_OK;

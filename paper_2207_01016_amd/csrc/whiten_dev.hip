@@ -230,6 +230,140 @@ __global__ __launch_bounds__(256) void symv_kernel(const double *__restrict__ A,
     }
 }
 
+// The same product from the UPPER triangle alone: the trailing matrix is symmetric, so an element A[a, c],
+// c > a, serves row a (times v[c]) and row c (times v[a]) in one read, and the pass reads half the bytes.
+// Work item = a strip of 64 rows (16 per wavefront) times a segment of 2048 columns, walked in chunks of 128
+// columns; a lane holds 2 columns of the chunk and 16 row sums.  Row sums of a segment go to
+// rowpart[segment][row]; the column sums of a chunk are combined over the four wavefronts in LDS and go to
+// colpart[strip][column]; yfix_kernel adds both up in a fixed order (no atomics: the result does not depend
+// on the order in which workgroups finish).  Elements left of the diagonal are read with their chunk and
+// masked; they are never meant: the panel update (syr2k_kernel) maintains the upper triangle only.
+// blockIdx.y >= n_strips: the panel dots, as in symv_kernel.
+constexpr int SY_ROWS = 64, SY_WR = 16, SY_CH = 128, SY_NCH = 8, SY_SEG = SY_CH * SY_NCH;
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void symv_upper_kernel(const double *__restrict__ A, int n, int j, int n_strips,
+                                                         const double *__restrict__ v, double *__restrict__ rowpart,
+                                                         double *__restrict__ colpart, const double *__restrict__ Vp,
+                                                         const double *__restrict__ Wp, double *__restrict__ coef)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: row addresses stay scalar
+    if (int(blockIdx.y) >= n_strips) {
+        if (blockIdx.x != 0) return;
+        __shared__ double red[16];
+        const int k = blockIdx.y - n_strips;
+        const double *vk = Vp + int64_t(k) * n, *wk = Wp + int64_t(k) * n;
+        double sa = 0.0, sb = 0.0;
+        for (int c = j + 1 + threadIdx.x; c < n; c += 256) {
+            const double vc = v[c];
+            sa += wk[c] * vc;
+            sb += vk[c] * vc;
+        }
+        sa = block_sum(sa, red);
+        sb = block_sum(sb, red);
+        if (threadIdx.x == 0) { coef[2 * k] = sa; coef[2 * k + 1] = sb; }
+        return;
+    }
+    __shared__ double cpart[4][SY_SEG];
+    const int strip = (j + 1) / SY_ROWS + blockIdx.y;          // absolute strip: rows 64 strip .. 64 strip + 63
+    const int c_first = (strip * SY_ROWS) & ~(SY_CH - 1);      // chunk that holds the strip's first diagonal element
+    const int seg0 = c_first + blockIdx.x * SY_SEG;
+    if (seg0 >= n) return;
+    const int a_base = strip * SY_ROWS + wave * SY_WR;
+    // Rows outside (j, n) are read from a row inside it and carry no weight: every lane issues the same 16 loads
+    // per chunk with no branch between them, so they are all in flight together.
+    double racc[SY_WR], va[SY_WR];
+    const double *rowp[SY_WR];
+#pragma unroll
+    for (int q = 0; q < SY_WR; ++q) {
+        const int a = a_base + q;
+        const bool live = a > j && a < n;
+        racc[q] = 0.0;
+        va[q] = live ? v[a] : 0.0;
+        rowp[q] = A + int64_t(min(max(a, j + 1), n - 1)) * n;
+    }
+    // one chunk at a time (not unrolled: 16 row loads of 16 bytes per lane are in flight per chunk, more would
+    // not fit the register file); a wavefront parks its column sums in its own LDS row, no barrier until the end
+#pragma unroll 1
+    for (int ch = 0; ch < SY_NCH; ++ch) {
+        const int c = seg0 + ch * SY_CH + 2 * lane;
+        const int cl = VEC ? min(c, n - 2) : min(c, n - 1);     // a column inside the row for lanes past its end
+        const double v0 = (c > j && c < n) ? v[c] : 0.0;
+        const double v1 = (c + 1 > j && c + 1 < n) ? v[c + 1] : 0.0;
+        double x0[SY_WR], x1[SY_WR];
+#pragma unroll
+        for (int q = 0; q < SY_WR; ++q) {
+            if (VEC) {
+                const d2 x = __builtin_nontemporal_load(reinterpret_cast<const d2 *>(rowp[q] + cl));
+                x0[q] = x.x; x1[q] = x.y;
+            } else {
+                x0[q] = __builtin_nontemporal_load(rowp[q] + cl);
+                x1[q] = __builtin_nontemporal_load(rowp[q] + min(cl + 1, n - 1));
+            }
+        }
+        double c0 = 0.0, c1 = 0.0;
+#pragma unroll
+        for (int q = 0; q < SY_WR; ++q) {
+            const int a = a_base + q;
+            // elements left of the diagonal and past the end of the row count as zero
+            const double e0 = (c >= a && c < n) ? x0[q] : 0.0;
+            const double e1 = (c + 1 >= a && c + 1 < n) ? x1[q] : 0.0;
+            racc[q] += e0 * v0 + e1 * v1;
+            c0 += (c > a) ? e0 * va[q] : 0.0;
+            c1 += (c + 1 > a) ? e1 * va[q] : 0.0;
+        }
+        cpart[wave][ch * SY_CH + 2 * lane] = c0;
+        cpart[wave][ch * SY_CH + 2 * lane + 1] = c1;
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < SY_SEG; t += 256)
+        if (seg0 + t < n)
+            colpart[int64_t(blockIdx.y) * n + seg0 + t] = (cpart[0][t] + cpart[1][t]) + (cpart[2][t] + cpart[3][t]);
+#pragma unroll
+    for (int q = 0; q < SY_WR; ++q) {
+        const int a = a_base + q;
+        const double r = wave_sum(racc[q]);
+        if (lane == 0 && a > j && a < n) rowpart[int64_t(blockIdx.x) * n + a] = r;
+    }
+}
+
+// y[c] = sum over the segments of row c's strip of rowpart + sum over the strips up to row c's of colpart
+//        - sum_{k<i} (v_k[c] a_k + w_k[c] b_k)          for c > j   (a_k = coef[2k], b_k = coef[2k+1])
+__global__ __launch_bounds__(256) void yfix_kernel(int n, int j, int i, const double *__restrict__ rowpart,
+                                                   const double *__restrict__ colpart, const double *__restrict__ Vp,
+                                                   const double *__restrict__ Wp, const double *__restrict__ coef,
+                                                   double *__restrict__ y)
+{
+    // 64 columns per workgroup; the strips (up to n / 64 of them) are dealt round-robin to its four wavefronts,
+    // four sums in flight each, and met in LDS in a fixed order
+    __shared__ double part[4][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int c = j + 1 + blockIdx.x * 64 + lane;
+    const int cc = min(c, n - 1);
+    const int s_first = (j + 1) / SY_ROWS;
+    const int strip = cc / SY_ROWS;
+    const int nst = strip - s_first + 1;                  // strips that hold column sums for this column
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    int st = w;
+    for (; st + 12 < nst; st += 16) {
+        a0 += colpart[int64_t(st) * n + cc];
+        a1 += colpart[int64_t(st + 4) * n + cc];
+        a2 += colpart[int64_t(st + 8) * n + cc];
+        a3 += colpart[int64_t(st + 12) * n + cc];
+    }
+    for (; st < nst; st += 4) a0 += colpart[int64_t(st) * n + cc];
+    part[w][lane] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    if (w != 0 || c >= n) return;
+    double v = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+    const int c_first = (strip * SY_ROWS) & ~(SY_CH - 1);
+    const int nseg = (n - c_first + SY_SEG - 1) / SY_SEG;
+    for (int g = 0; g < nseg; ++g) v += rowpart[int64_t(g) * n + c];
+    for (int k = 0; k < i; ++k) v -= Vp[int64_t(k) * n + c] * coef[2 * k] + Wp[int64_t(k) * n + c] * coef[2 * k + 1];
+    y[c] = v;
+}
+
 // y[c] -= sum_{k<i} (v_k[c] a_k + w_k[c] b_k) for c > j, with a_k = coef[2k], b_k = coef[2k+1].
 __global__ __launch_bounds__(256) void pfix_kernel(int n, int j, int i, const double *__restrict__ Vp,
                                                    const double *__restrict__ Wp, const double *__restrict__ coef,
@@ -258,10 +392,13 @@ __global__ __launch_bounds__(1024) void w_kernel(int n, int j, const double *__r
 
 // End of a panel of nb columns: A[a, c] -= sum_k (v_k[a] w_k[c] + w_k[a] v_k[c]) for a, c >= jn.
 // 64 x 64 tile per workgroup, 4 x 4 elements per thread, the four 64-long slices of the panel in LDS.
+// upper_only: tiles strictly below the diagonal are left alone (the upper-triangle pass never reads them).
 __global__ __launch_bounds__(256) void syr2k_kernel(double *__restrict__ A, int n, int jn, int nb,
-                                                    const double *__restrict__ Vp, const double *__restrict__ Wp)
+                                                    const double *__restrict__ Vp, const double *__restrict__ Wp,
+                                                    int upper_only)
 {
     __shared__ double va[NBT][64], wa[NBT][64], vc[NBT][64], wc[NBT][64];
+    if (upper_only && blockIdx.y > blockIdx.x) return;
     const int a0 = jn + blockIdx.y * 64, c0 = jn + blockIdx.x * 64;
     for (int e = threadIdx.x; e < NBT * 64; e += 256) {
         const int k = e >> 6, t = e & 63;
@@ -873,6 +1010,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const double *__restrict__ 
 struct DevCarve {
     size_t off_A, off_Zt, off_vec, off_panel, off_P, off_T, off_cs, off_tab, off_ord, off_lam, bytes;
     size_t off_cs2, off_tab2, off_G, off_dc, off_uq;   // further QL instances, gathered rows, vectors of the merges
+    size_t off_rowpart, off_colpart;                   // partial sums of the upper-triangle pass
     size_t cs_doubles;     // capacity of ONE of the rotation buffers, header included
     size_t cs_bytes, tab_bytes;
 };
@@ -880,6 +1018,7 @@ struct DevCarve {
 constexpr int kDcMin = 512;      // matrices from this size on are torn apart and merged on the device
 constexpr int kMaxLeaves = 8;    // pieces the tridiagonal problem is torn into at most
 std::atomic<int> g_dc_enabled{1};
+std::atomic<int> g_upper_pass{1};   // 1: the reduction reads and maintains the upper triangle only
 
 // Depth of the tearing: 2^levels leaves.
 inline int dc_levels(int64_t n) { return n >= 8192 ? 3 : n >= 2048 ? 2 : n >= kDcMin ? 1 : 0; }
@@ -913,6 +1052,8 @@ DevCarve dev_carve(int64_t n)
     c.off_G = o; o += n >= kDcMin ? nn : 0;
     c.off_dc = o; o += 14 * vec;
     c.off_uq = o; o += extra * vec;
+    c.off_rowpart = o; o += (size_t(n) / SY_SEG + 2) * vec;
+    c.off_colpart = o; o += (size_t(n) / SY_ROWS + 2) * vec;
     c.bytes = o;
     return c;
 }
@@ -1145,6 +1286,7 @@ int dc_merge(int n, const Tear &tr, std::vector<double> &dg, const DcBuffers &b,
 }  // namespace
 
 void lpd_host::set_divide_and_conquer(int on) { g_dc_enabled.store(on ? 1 : 0, std::memory_order_relaxed); }
+void lpd_host::set_upper_triangle_pass(int on) { g_upper_pass.store(on ? 1 : 0, std::memory_order_relaxed); }
 
 extern "C" int lpd_whiten_workspace(int64_t B, size_t *bytes)
 {
@@ -1248,6 +1390,9 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
     say("tridiagonalisation");
     {
         const bool even = n % 2 == 0;
+        const bool upper = g_upper_pass.load(std::memory_order_relaxed) != 0;
+        double *rowpart = reinterpret_cast<double *>(ws + cv.off_rowpart);
+        double *colpart = reinterpret_cast<double *>(ws + cv.off_colpart);
         for (int j0 = 0; j0 + 2 < n; j0 += NBT) {
             const int nb = std::min(NBT, n - 2 - j0);
             for (int i = 0; i < nb; ++i) {
@@ -1256,20 +1401,35 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
                 hipLaunchKernelGGL(rowfix_kernel, dim3((n - j + 255) / 256), dim3(256), 0, s, A, n, j, i, Vp, Wp, xrow);
                 hipLaunchKernelGGL(hh_kernel, dim3(1), dim3(1024), 0, s, A, n, j, xrow, vi, dg_d, e_d, tau_d);
                 const int rows = n - j - 1;
-                const int row_blocks = std::min(512, even ? ((rows + 1) / 2 + 3) / 4 : (rows + 3) / 4);
-                if (even)
-                    hipLaunchKernelGGL((symv_kernel<true>), dim3(row_blocks + i), dim3(256), 0, s, A, n, j, row_blocks,
-                                       vi, y, Vp, Wp, coef);
-                else
-                    hipLaunchKernelGGL((symv_kernel<false>), dim3(row_blocks + i), dim3(256), 0, s, A, n, j, row_blocks,
-                                       vi, y, Vp, Wp, coef);
-                if (i > 0)
-                    hipLaunchKernelGGL(pfix_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, n, j, i, Vp, Wp, coef, y);
+                if (upper) {
+                    const int s_first = (j + 1) / SY_ROWS;
+                    const int n_strips = (n - 1) / SY_ROWS - s_first + 1;
+                    const int c_first = (s_first * SY_ROWS) & ~(SY_CH - 1);
+                    const int nseg = (n - c_first + SY_SEG - 1) / SY_SEG;
+                    if (even)
+                        hipLaunchKernelGGL((symv_upper_kernel<true>), dim3(nseg, n_strips + i), dim3(256), 0, s, A, n, j,
+                                           n_strips, vi, rowpart, colpart, Vp, Wp, coef);
+                    else
+                        hipLaunchKernelGGL((symv_upper_kernel<false>), dim3(nseg, n_strips + i), dim3(256), 0, s, A, n, j,
+                                           n_strips, vi, rowpart, colpart, Vp, Wp, coef);
+                    hipLaunchKernelGGL(yfix_kernel, dim3((rows + 63) / 64), dim3(256), 0, s, n, j, i, rowpart, colpart, Vp,
+                                       Wp, coef, y);
+                } else {
+                    const int row_blocks = std::min(512, even ? ((rows + 1) / 2 + 3) / 4 : (rows + 3) / 4);
+                    if (even)
+                        hipLaunchKernelGGL((symv_kernel<true>), dim3(row_blocks + i), dim3(256), 0, s, A, n, j, row_blocks,
+                                           vi, y, Vp, Wp, coef);
+                    else
+                        hipLaunchKernelGGL((symv_kernel<false>), dim3(row_blocks + i), dim3(256), 0, s, A, n, j, row_blocks,
+                                           vi, y, Vp, Wp, coef);
+                    if (i > 0)
+                        hipLaunchKernelGGL(pfix_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, n, j, i, Vp, Wp, coef, y);
+                }
                 hipLaunchKernelGGL(w_kernel, dim3(1), dim3(1024), 0, s, n, j, tau_d, vi, y, wi);
             }
             const int jn = j0 + nb;
             const int tiles = (n - jn + 63) / 64;
-            hipLaunchKernelGGL(syr2k_kernel, dim3(tiles, tiles), dim3(256), 0, s, A, n, jn, nb, Vp, Wp);
+            hipLaunchKernelGGL(syr2k_kernel, dim3(tiles, tiles), dim3(256), 0, s, A, n, jn, nb, Vp, Wp, upper ? 1 : 0);
             LPD_HIP(hipGetLastError());
         }
         if (n >= 2) {

@@ -34,5 +34,8 @@ int64_t order_and_clip(const double *dg, int64_t n, double clip_ratio, std::vect
 // Switch of the device routine: 1 (default) = matrices of 512 rows and more are torn in two, the halves solved
 // by two concurrent QL iterations and merged on the device; 0 = one QL iteration over the whole matrix.
 void set_divide_and_conquer(int on);
+// 1 (default) = the Householder reduction reads and maintains the upper triangle of the trailing matrix only
+// (half the bytes per column); 0 = the whole symmetric matrix.
+void set_upper_triangle_pass(int on);
 
 }  // namespace lpd_host

@@ -212,3 +212,29 @@ def test_whiten_8192_landmarks_three_levels_of_tearing(lpd, dev):
     Wd = W.double()
     P = Wd @ K @ Wd.T
     assert float((P - torch.eye(wl.B, dtype=torch.float64, device=dev)).norm()) <= 2e-6 * wl.B
+
+
+@pytest.mark.parametrize("B", [333, 1030, 2050])
+def test_upper_triangle_reduction_matches_full_matrix_reduction(lpd, dev, B):
+    """The reduction to tridiagonal form reads the upper triangle of the symmetric trailing matrix only (each
+    element serves its row and its column).  The same decomposition must come out as from the pass over the
+    whole matrix: eigenvalues to rounding, W^T W to fp32 rounding (odd and even sizes: both loaders)."""
+    from paper_2207_01016_amd import workloads
+    wl = workloads.WORKLOADS["highrank"].with_shape(n=max(2 * B, 1000), B=B)
+    X = workloads.make_X(wl)
+    Lm = X[workloads.landmark_indices(wl)].contiguous().to(dev)
+    out = {}
+    for upper in (1, 0):
+        lpd.lpd_set_option(lpd.LPD_OPT_WHITEN_UPPER, upper)
+        try:
+            out[upper] = lpd.lpd_whiten(Lm, wl.gamma)
+        finally:
+            lpd.lpd_set_option(lpd.LPD_OPT_WHITEN_UPPER, 1)
+    (W1, e1, r1), (W0, e0, r0) = out[1], out[0]
+    assert r1 == r0 == B
+    assert float((e1 - e0).abs().max()) <= 1e-11 * float(e0[0])
+    G1, G0 = W1.double().T @ W1.double(), W0.double().T @ W0.double()
+    assert float((G1 - G0).norm() / G0.norm()) <= 1e-5
+    # and it is deterministic: no atomics, fixed order of the partial sums
+    W2, e2, r2 = lpd.lpd_whiten(Lm, wl.gamma)
+    assert torch.equal(W2, W1) and torch.equal(e2, e1)

@@ -102,12 +102,15 @@ const char *lpd_strerror(int status);
  *   LPD_OPT_WHITEN_DC  lpd_whiten for B >= 512: 1 (default) = the tridiagonal problem is torn in two,
  *                      the halves solved concurrently and merged on the device; 0 = one QL
  *                      iteration over the whole matrix
+ *   LPD_OPT_SWEEP_GRID workgroups of a full margin sweep: 0 (default) = chosen by the row length,
+ *                      1..65536 = that many (each takes rows in a grid-stride loop)
  *   LPD_OPT_WHITEN_UPPER  lpd_whiten's reduction to tridiagonal form: 1 (default) = reads and updates the
  *                      upper triangle of the trailing matrix only, 0 = the whole symmetric matrix
  * Errors: LPD_ERR_SHAPE for an unknown option or value.
  */
 typedef enum { LPD_OPT_GEMM_TILE = 1, LPD_OPT_GEMM_PIPELINE = 2, LPD_OPT_CSR_ROUTE = 3,
-               LPD_OPT_SMALL_PATH = 4, LPD_OPT_WHITEN_DC = 5, LPD_OPT_WHITEN_UPPER = 6 } lpd_option;
+               LPD_OPT_SMALL_PATH = 4, LPD_OPT_WHITEN_DC = 5, LPD_OPT_WHITEN_UPPER = 6,
+               LPD_OPT_SWEEP_GRID = 7 } lpd_option;
 int lpd_set_option(int option, int64_t value);
 
 /*
@@ -139,23 +142,32 @@ int lpd_whiten_host(const float *L_host, int64_t B, int64_t d, int64_t ldl,
  * lpd_whiten_host (same definition, same ordering, clipping and sign rule),
  * computed in double precision by HIP kernels: kernel matrix of the landmarks,
  * Householder reduction to tridiagonal form, accumulation of the reflectors,
- * application of the QL plane rotations, scaling to W.  Only the scalar QL
- * iteration on the tridiagonal matrix (O(B^2)) runs on the host, overlapped
- * with the device.  Eigenvectors of a repeated eigenvalue may differ from the
- * host routine's by a rotation within their eigenspace.
+ * eigendecomposition of the tridiagonal matrix, scaling to W.  From 512
+ * landmarks on the tridiagonal matrix is torn into 2, 4 or 8 pieces (from 512 /
+ * 2,048 / 8,192 landmarks); each piece is solved by a QL iteration whose scalar
+ * recurrence runs on a host thread of its own while the device applies its
+ * plane rotations, and the pieces are merged on the device (secular equation,
+ * deflation, a double-precision matrix product).  Eigenvectors of a repeated
+ * eigenvalue may differ from the host routine's by a rotation within their
+ * eigenspace.  The result is deterministic (no atomics anywhere).
  *
  *   L          device in   B x d floats, ldl
  *   W          device out  B x B floats, ldw; rows >= *rank are zero
  *   eig_host   host out    B doubles, descending; may be NULL
  *   rank       host out
  *   workspace  device, 256-byte aligned, at least lpd_whiten_workspace(B) bytes
- *              (two B x B double matrices and some vectors)
+ *              (two B x B double matrices, a third from 512 landmarks on, and
+ *              vectors: 6.6 GB at B = 16,384)
  *   phase_seconds  host out, may be NULL: 5 doubles, wall time of the kernel
  *              matrix, the tridiagonalisation, the reflector accumulation, the
- *              QL iteration with its rotation passes, and the final scaling.
+ *              eigendecomposition of the tridiagonal matrix (QL iterations with
+ *              their rotation passes, and the merges), and the final scaling.
  *              Asking for them drains the stream between phases.
- * The call BLOCKS until W is complete.  It allocates page-locked host staging
- * (a few MB) and events for its duration, no device memory.  B <= 46340.
+ * The call BLOCKS until W is complete.  It allocates no device memory.  At its
+ * first call in a process (and again only for a larger B) it allocates
+ * page-locked host staging (64 bytes per landmark plus up to 16 rotation buffers
+ * of 256 B bytes each) and 17 events, which it keeps until the process ends; calls
+ * from several threads are serialised on that staging.  B <= 46340.
  * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE, LPD_ERR_LD, LPD_ERR_WORKSPACE,
  * LPD_ERR_HIP, LPD_ERR_NUMERIC (QL did not converge, or no positive eigenvalue).
  */

@@ -92,6 +92,7 @@ enum TileId { TILE_AUTO = 0, TILE_128x128 = 1, TILE_256x128 = 2, TILE_256x256 = 
 std::atomic<int> g_pipe_option{1};            // LPD_OPT_GEMM_PIPELINE
 std::atomic<int> g_tile_option{TILE_AUTO};   // LPD_OPT_GEMM_TILE
 std::atomic<int> g_csr_route{0};              // LPD_OPT_CSR_ROUTE: 0 by density, 1 dense panel, 2 gather
+std::atomic<int> g_sweep_grid{0};             // LPD_OPT_SWEEP_GRID: 0 = by row length, else the number of workgroups of a full sweep
 std::atomic<int> g_small_path{1};             // LPD_OPT_SMALL_PATH: 1 = one-launch factor for B <= 256, 0 = panel schedule
 
 int tile_choice(const GemmArgs &a)
@@ -199,7 +200,9 @@ hipError_t launch_margins_lpr(const float *G, int64_t n_out, int r, int64_t ldg,
     // A full sweep over long rows runs fastest with few rows open at once (about 128 MB of them): 512 workgroups
     // at 32 KB per row, one per CU at 64 KB.  Measured at 16,384 columns: 6.7 TB/s with 4,096 workgroups, 7.2 TB/s
     // with 256.  Shorter rows and row lists (scattered rows) keep the large grid.
-    const int64_t cap = (INDEXED || r < 8192) ? 4096 : std::max<int64_t>(256, (int64_t(4) << 20) / r);
+    const int forced = g_sweep_grid.load(std::memory_order_relaxed);
+    const int64_t cap = (forced > 0 && !INDEXED) ? forced
+                        : (INDEXED || r < 8192) ? 4096 : std::max<int64_t>(256, (int64_t(4) << 20) / r);
     const unsigned grid = row_grid(n_out, 256 / LPR * ROWS, cap);
     if (vec) hipLaunchKernelGGL((margins_kernel<LPR, true, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, n_rows_G, w, m, ms);
     else hipLaunchKernelGGL((margins_kernel<LPR, false, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, n_rows_G, w, m, ms);
@@ -570,6 +573,10 @@ int lpd_set_option(int option, int64_t value)
     }
     if (option == LPD_OPT_CSR_ROUTE && value >= 0 && value <= 2) {
         g_csr_route.store(int(value), std::memory_order_relaxed);
+        return LPD_OK;
+    }
+    if (option == LPD_OPT_SWEEP_GRID && value >= 0 && value <= 65536) {
+        g_sweep_grid.store(int(value), std::memory_order_relaxed);
         return LPD_OK;
     }
     if (option == LPD_OPT_WHITEN_UPPER && (value == 0 || value == 1)) {

@@ -284,7 +284,8 @@ __global__ __launch_bounds__(256) void symv_upper_kernel(const double *__restric
         rowp[q] = A + int64_t(min(max(a, j + 1), n - 1)) * n;
     }
     // one chunk at a time (not unrolled: 16 row loads of 16 bytes per lane are in flight per chunk, more would
-    // not fit the register file); a wavefront parks its column sums in its own LDS row, no barrier until the end
+    // not fit the register file; requesting the next chunk before summing the current one was tried and costs
+    // more in occupancy than it gains); a wavefront parks its column sums in its own LDS row, no barrier until the end
 #pragma unroll 1
     for (int ch = 0; ch < SY_NCH; ++ch) {
         const int c = seg0 + ch * SY_CH + 2 * lane;
@@ -520,91 +521,133 @@ __global__ __launch_bounds__(NB * NB) void panel_t_kernel(const double *__restri
     T[threadIdx.x] = ts[threadIdx.x / NB][threadIdx.x % NB];
 }
 
-// Rows r0.. of Zt times the panel: row <- row (I - V T^T V^T), 16 rows per workgroup.  Both passes over the
-// columns fetch the next 64-column slice into registers while the current one is worked on from LDS.
-__global__ __launch_bounds__(256) void panel_apply_kernel(double *__restrict__ Zt, int n, const double *__restrict__ A,
-                                                          int k0, int nb, const double *__restrict__ T, int r0)
-{
-    constexpr int RB = 16, CC = 64;
-    constexpr int ZPT = RB * CC / 256, VPT = NB * CC / 256;     // elements per thread of a slice: 4 and 8
-    __shared__ double zs[RB][CC + 1], vs[NB][CC + 1], ys[RB][NB + 1], y2[RB][NB + 1], ts[NB][NB + 1];
-    const int rbase = r0 + blockIdx.x * RB;
-    const int cfirst = k0 + 1;
-    for (int e = threadIdx.x; e < NB * NB; e += 256) ts[e / NB][e % NB] = T[e];
-    double zreg[ZPT], vreg[VPT];
-    auto fetch_z = [&](int cb) {
-#pragma unroll
-        for (int q = 0; q < ZPT; ++q) {
-            const int e = threadIdx.x + q * 256, r = e / CC, c = e % CC;
-            zreg[q] = (rbase + r < n && cb + c < n) ? Zt[int64_t(rbase + r) * n + cb + c] : 0.0;
-        }
-    };
-    auto fetch_v = [&](int cb) {
-#pragma unroll
-        for (int q = 0; q < VPT; ++q) {
-            const int e = threadIdx.x + q * 256, t = e / CC, c = e % CC;
-            vreg[q] = panel_v(A, n, k0, nb, t, cb + c);
-        }
-    };
-    auto put_z = [&]() {
-#pragma unroll
-        for (int q = 0; q < ZPT; ++q) { const int e = threadIdx.x + q * 256; zs[e / CC][e % CC] = zreg[q]; }
-    };
-    auto put_v = [&]() {
-#pragma unroll
-        for (int q = 0; q < VPT; ++q) { const int e = threadIdx.x + q * 256; vs[e / CC][e % CC] = vreg[q]; }
-    };
+// Rows r0.. of Zt times the panel: row <- row (I - V T^T V^T), in three kernels so that each streams Zt once with
+// tiles large enough to pay for the panel vectors they load:
+//   panel_y_kernel       Ypart[ks][r][t] = sum over the ks-th quarter of the columns of Zt[r][c] v_t[c]
+//                        (64 rows x 32 reflectors per workgroup, 4 x 2 per thread, 32-column slices through LDS)
+//   panel_y2_kernel      Y2[r][t] = sum_{u >= t} (sum_ks Ypart[ks][r][u]) T[t][u]
+//   panel_update_kernel  Zt[r][c] -= sum_t Y2[r][t] v_t[c]   (64 x 128 tile per workgroup, 8 x 4 per thread)
+constexpr int PA_RB = 64, PA_KS = 4;
 
-    // Y[rr][t] = sum_c Zt[rbase+rr][c] v_t[c]; thread (rr, tq) owns t = tq and tq + 16
-    const int rr = threadIdx.x >> 4, tq = threadIdx.x & 15;
-    double ya = 0.0, yb = 0.0;
-    fetch_z(cfirst);
-    fetch_v(cfirst);
-    for (int cb = cfirst; cb < n; cb += CC) {
+__global__ __launch_bounds__(256) void panel_y_kernel(const double *__restrict__ Zt, int n, const double *__restrict__ A,
+                                                      int k0, int nb, int r0, int nrows, double *__restrict__ Ypart)
+{
+    constexpr int CC = 32;
+    __shared__ double zs[PA_RB][CC + 1], vs[NB][CC + 1];
+    const int rbase = r0 + blockIdx.x * PA_RB;
+    const int cfirst = k0 + 1;
+    const int nch = (n - cfirst + CC - 1) / CC;
+    const int ch0 = int(int64_t(blockIdx.y) * nch / PA_KS), ch1 = int(int64_t(blockIdx.y + 1) * nch / PA_KS);
+    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;         // rows 4 ty .. 4 ty + 3, reflectors tx and tx + 16
+    double acc[4][2] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
+    double zreg[8], vreg[4];
+    auto fetch = [&](int ch) {
+        const int cb = cfirst + ch * CC;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int e = threadIdx.x + q * 256, r = e / CC, c = e % CC;
+            zreg[q] = (ch < ch1 && rbase + r < n && cb + c < n) ? Zt[int64_t(rbase + r) * n + cb + c] : 0.0;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = threadIdx.x + q * 256, t = e / CC, c = e % CC;
+            vreg[q] = ch < ch1 ? panel_v(A, n, k0, nb, t, cb + c) : 0.0;
+        }
+    };
+    fetch(ch0);
+    for (int ch = ch0; ch < ch1; ++ch) {
         __syncthreads();
-        put_z();
-        put_v();
+#pragma unroll
+        for (int q = 0; q < 8; ++q) { const int e = threadIdx.x + q * 256; zs[e / CC][e % CC] = zreg[q]; }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { const int e = threadIdx.x + q * 256; vs[e / CC][e % CC] = vreg[q]; }
         __syncthreads();
-        fetch_z(cb + CC);          // past the last column the guards turn the fetch into zeros
-        fetch_v(cb + CC);
+        fetch(ch + 1);
 #pragma unroll 8
         for (int c = 0; c < CC; ++c) {
-            const double z = zs[rr][c];
-            ya += z * vs[tq][c];
-            yb += z * vs[tq + 16][c];
+            const double va = vs[tx][c], vb = vs[tx + 16][c];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const double z = zs[ty * 4 + p][c];
+                acc[p][0] += z * va;
+                acc[p][1] += z * vb;
+            }
         }
     }
-    ys[rr][tq] = ya;
-    ys[rr][tq + 16] = yb;
-    __syncthreads();
-    // Y2[rr][t] = sum_{u >= t} Y[rr][u] T[t][u]
-    for (int e = threadIdx.x; e < RB * NB; e += 256) {
-        const int r = e / NB, t = e % NB;
-        double s = 0.0;
-        for (int u = t; u < NB; ++u) s += ys[r][u] * ts[t][u];
-        y2[r][t] = s;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int r = rbase - r0 + ty * 4 + p;
+        if (r < nrows) {
+            double *out = Ypart + (int64_t(blockIdx.y) * nrows + r) * NB;
+            out[tx] = acc[p][0];
+            out[tx + 16] = acc[p][1];
+        }
     }
-    // Zt[r][c] -= sum_t Y2[r][t] v_t[c]
-    fetch_z(cfirst);
-    fetch_v(cfirst);
-    for (int cb = cfirst; cb < n; cb += CC) {
-        __syncthreads();
-        put_v();
-        double zcur[ZPT];
+}
+
+__global__ __launch_bounds__(256) void panel_y2_kernel(const double *__restrict__ Ypart, int nrows,
+                                                       const double *__restrict__ T, double *__restrict__ Y2)
+{
+    __shared__ double ts[NB][NB + 1];
+    for (int e = threadIdx.x; e < NB * NB; e += 256) ts[e / NB][e % NB] = T[e];
+    __syncthreads();
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    const int r = idx / NB, t = idx % NB;
+    if (r >= nrows) return;
+    double s = 0.0;
+    for (int u = t; u < NB; ++u) {
+        double yu = 0.0;
 #pragma unroll
-        for (int q = 0; q < ZPT; ++q) zcur[q] = zreg[q];
-        __syncthreads();
-        fetch_z(cb + CC);
-        fetch_v(cb + CC);
+        for (int ks = 0; ks < PA_KS; ++ks) yu += Ypart[(int64_t(ks) * nrows + r) * NB + u];
+        s += yu * ts[t][u];
+    }
+    Y2[int64_t(r) * NB + t] = s;
+}
+
+__global__ __launch_bounds__(256) void panel_update_kernel(double *__restrict__ Zt, int n, const double *__restrict__ A,
+                                                           int k0, int nb, int r0, int nrows, const double *__restrict__ Y2)
+{
+    constexpr int CT = 128;
+    __shared__ __attribute__((aligned(16))) double y2s[PA_RB][NB + 1], vs[NB][CT];
+    const int rbase = r0 + blockIdx.x * PA_RB;
+    const int cb = k0 + 1 + blockIdx.y * CT;
+    for (int e = threadIdx.x; e < PA_RB * NB; e += 256) {
+        const int r = e / NB, t = e % NB;
+        y2s[r][t] = (rbase - r0 + r < nrows) ? Y2[int64_t(rbase - r0 + r) * NB + t] : 0.0;
+    }
+    for (int e = threadIdx.x; e < NB * CT; e += 256) {
+        const int t = e / CT, c = e % CT;
+        vs[t][c] = panel_v(A, n, k0, nb, t, cb + c);
+    }
+    __syncthreads();
+    const int ty = threadIdx.x >> 5, tx = threadIdx.x & 31;         // rows 8 ty .. 8 ty + 7, columns 4 tx .. 4 tx + 3
+    double acc[8][4];
 #pragma unroll
-        for (int q = 0; q < ZPT; ++q) {
-            const int e = threadIdx.x + q * 256, r = e / CC, c = e % CC;
-            if (rbase + r < n && cb + c < n) {
-                double s = 0.0;
-#pragma unroll 8
-                for (int t = 0; t < NB; ++t) s += y2[r][t] * vs[t][c];
-                Zt[int64_t(rbase + r) * n + cb + c] = zcur[q] - s;
-            }
+    for (int p = 0; p < 8; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[p][q] = 0.0;
+#pragma unroll 4
+    for (int t = 0; t < NB; ++t) {
+        const d2 va = *reinterpret_cast<const d2 *>(&vs[t][tx * 4]);
+        const d2 vb = *reinterpret_cast<const d2 *>(&vs[t][tx * 4 + 2]);
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const double y = y2s[ty * 8 + p][t];
+            acc[p][0] += y * va.x;
+            acc[p][1] += y * va.y;
+            acc[p][2] += y * vb.x;
+            acc[p][3] += y * vb.y;
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const int r = rbase + ty * 8 + p;
+        if (r >= n) continue;
+        double *row = Zt + int64_t(r) * n;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = cb + tx * 4 + q;
+            if (c < n) row[c] -= acc[p][q];
         }
     }
 }
@@ -1011,6 +1054,7 @@ struct DevCarve {
     size_t off_A, off_Zt, off_vec, off_panel, off_P, off_T, off_cs, off_tab, off_ord, off_lam, bytes;
     size_t off_cs2, off_tab2, off_G, off_dc, off_uq;   // further QL instances, gathered rows, vectors of the merges
     size_t off_rowpart, off_colpart;                   // partial sums of the upper-triangle pass
+    size_t off_Y;                                      // Y parts and Y2 of the reflector accumulation
     size_t cs_doubles;     // capacity of ONE of the rotation buffers, header included
     size_t cs_bytes, tab_bytes;
 };
@@ -1054,6 +1098,7 @@ DevCarve dev_carve(int64_t n)
     c.off_uq = o; o += extra * vec;
     c.off_rowpart = o; o += (size_t(n) / SY_SEG + 2) * vec;
     c.off_colpart = o; o += (size_t(n) / SY_ROWS + 2) * vec;
+    c.off_Y = o; o += round_up(size_t(5) * size_t(std::max<int64_t>(n, 1)) * 32 * 8, kAlign);
     c.bytes = o;
     return c;
 }
@@ -1446,6 +1491,8 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
     say("accumulation of the reflectors");
     // Q^T into Zt while the host starts on the tridiagonal matrix
     {
+        double *Ypart = reinterpret_cast<double *>(ws + cv.off_Y);
+        double *Y2 = Ypart + size_t(PA_KS) * size_t(n) * NB;
         hipLaunchKernelGGL(identity_kernel, dim3(2048), dim3(256), 0, s, Zt, n);
         const int nref = n - 2;
         const int npanel = nref > 0 ? (nref + NB - 1) / NB : 0;
@@ -1457,8 +1504,12 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
             hipLaunchKernelGGL(panel_t_kernel, dim3(1), dim3(NB * NB), 0, s, P, nchunks, k0, nb, tau_d, T);
             // rows up to k0 are still unit vectors with nothing in the columns this panel touches
             const int r0 = k0 + 1;
-            const int nblk = (n - r0 + 15) / 16;
-            hipLaunchKernelGGL(panel_apply_kernel, dim3(nblk), dim3(256), 0, s, Zt, n, A, k0, nb, T, r0);
+            const int nrows = n - r0;
+            const int nblk = (nrows + PA_RB - 1) / PA_RB;
+            hipLaunchKernelGGL(panel_y_kernel, dim3(nblk, PA_KS), dim3(256), 0, s, Zt, n, A, k0, nb, r0, nrows, Ypart);
+            hipLaunchKernelGGL(panel_y2_kernel, dim3((nrows * NB + 255) / 256), dim3(256), 0, s, Ypart, nrows, T, Y2);
+            hipLaunchKernelGGL(panel_update_kernel, dim3(nblk, (nrows + 127) / 128), dim3(256), 0, s, Zt, n, A, k0, nb, r0,
+                               nrows, Y2);
         }
         LPD_HIP(hipGetLastError());
     }

@@ -53,8 +53,9 @@ struct GemmArgs {
 constexpr int GEMM_BK = 16;
 constexpr int GEMM_LDK = GEMM_BK + 4;
 
+// two stages of operand tiles, then the BM + BN squared norms of the tile's rows and columns (EPI_GAUSS)
 template <int BM, int BN>
-constexpr size_t gemm_lds_bytes() { return size_t(2) * (BM + BN) * GEMM_LDK * sizeof(float); }
+constexpr size_t gemm_lds_bytes() { return (size_t(2) * (BM + BN) * GEMM_LDK + (BM + BN)) * sizeof(float); }
 
 template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI, int PIPE>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
@@ -162,6 +163,14 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
         for (int q = 0; q < PB; ++q)
             *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) = EPI == EPI_GAUSS ? rb[q] - rc : rb[q];
     };
+
+    // The squared norms the epilogue needs go to LDS now, so that after the main loop nothing waits for
+    // global memory: a load there would also wait for every store issued before it (one counter orders both).
+    float *nas = lds + 2 * STAGE, *nbs = nas + BM;
+    if (EPI == EPI_GAUSS) {
+        for (int e = tid; e < BM + BN; e += NT)
+            nas[e] = e < BM ? p.na[min(m0 + e, p.M - 1)] : p.nb[min(n0 + e - BM, p.N - 1)];
+    }
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -341,25 +350,50 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
     // ---- epilogue: accumulator register v of lane l is C[8*(v/4) + 4*(l/32) + v%4][l%32]
     const int col_in = lane & 31;
     const int row_in = (lane >> 5) * 4;
+    if (EPI == EPI_GAUSS) __syncthreads();      // the norms in LDS (no barrier lies behind when K = 0)
+    auto finish = [&](float accv, float nav, float nbv) __attribute__((always_inline)) -> float {
+        if (EPI != EPI_GAUSS) return accv;
+        const float dist = fmaxf(nav + nbv - 2.0f * accv, 0.0f);
+        return __builtin_amdgcn_exp2f(p.scale * dist);
+    };
+    if (m0 + BM <= p.M && n0 + BN <= p.N) {
+        // interior tile: no bounds to check, one row pointer per group of four rows
+        float nbv[TN];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int cc = n0 + wn * WN + j * 32 + col_in;
-        if (cc >= p.n_store) continue;
-        const bool live = cc < p.N;
-        float nbv = 0.0f;
-        if (EPI == EPI_GAUSS) nbv = live ? p.nb[cc] : 0.0f;
+        for (int j = 0; j < TN; ++j) nbv[j] = EPI == EPI_GAUSS ? nbs[wn * WN + j * 32 + col_in] : 0.0f;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rr = m0 + wm * WM + i * 32 + 8 * (v >> 2) + row_in + (v & 3);
-                if (rr >= p.M) continue;
-                float out = acc[i][j][v];
-                if (EPI == EPI_GAUSS) {
-                    const float dist = fmaxf(p.na[rr] + nbv - 2.0f * out, 0.0f);
-                    out = __builtin_amdgcn_exp2f(p.scale * dist);
+            for (int g = 0; g < 4; ++g) {
+                const int rl = wm * WM + i * 32 + 8 * g + row_in;      // row within the tile, a multiple of 4
+                f32x4 nav = {0.f, 0.f, 0.f, 0.f};
+                if (EPI == EPI_GAUSS) nav = *reinterpret_cast<const f32x4 *>(&nas[rl]);
+                float *crow = p.C + int64_t(m0 + rl) * p.ldc + (n0 + wn * WN + col_in);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        crow[int64_t(e) * p.ldc + j * 32] = finish(acc[i][j][4 * g + e], nav[e], nbv[j]);
                 }
-                p.C[int64_t(rr) * p.ldc + cc] = live ? out : 0.0f;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int cl = wn * WN + j * 32 + col_in;
+            const int cc = n0 + cl;
+            if (cc >= p.n_store) continue;
+            const bool live = cc < p.N;
+            const float nbv = EPI == EPI_GAUSS ? nbs[cl] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int rl = wm * WM + i * 32 + 8 * (v >> 2) + row_in + (v & 3);
+                    if (m0 + rl >= p.M) continue;
+                    const float out = finish(acc[i][j][v], EPI == EPI_GAUSS ? nas[rl] : 0.0f, nbv);
+                    p.C[int64_t(m0 + rl) * p.ldc + cc] = live ? out : 0.0f;
+                }
             }
         }
     }

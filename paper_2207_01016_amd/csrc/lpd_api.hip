@@ -95,15 +95,37 @@ std::atomic<int> g_csr_route{0};              // LPD_OPT_CSR_ROUTE: 0 by density
 std::atomic<int> g_sweep_grid{0};             // LPD_OPT_SWEEP_GRID: 0 = by row length, else the number of workgroups of a full sweep
 std::atomic<int> g_small_path{1};             // LPD_OPT_SMALL_PATH: 1 = one-launch factor for B <= 256, 0 = panel schedule
 
-int tile_choice(const GemmArgs &a)
+// Estimated duration of a launch with BM x BN tiles, in units of (CUs x tile elements): a CU holds `per_cu`
+// workgroups (registers: 3 of the 128x128 tile, 2 of the 256x128 tile of the plain product, else 1), a launch
+// runs in rounds of 256 x per_cu tiles, and a last round that leaves CUs with fewer workgroups than they can
+// hold goes faster, though not in proportion (a lone 4-wavefront workgroup cannot keep a CU's MFMA pipes
+// full).  `speed` is the measured main-loop advantage of the larger tiles (less LDS and L2 traffic per FLOP).
+double launch_cost(const GemmArgs &a, int bm, int bn, int per_cu, double speed)
+{
+    const int64_t tiles = int64_t((a.M + bm - 1) / bm) * ((a.n_store + bn - 1) / bn);
+    const int64_t slots = int64_t(256) * per_cu;
+    const int64_t rem = tiles % slots;
+    double rounds = double(tiles / slots);
+    if (rem > 0) {
+        const int64_t deep = (rem + 255) / 256;          // workgroups on the fullest CU in the last round
+        static const double part3[4] = {0.0, 0.45, 0.75, 1.0}, part2[3] = {0.0, 0.6, 1.0};
+        rounds += per_cu == 3 ? part3[deep] : per_cu == 2 ? part2[deep] : 1.0;
+    }
+    return rounds * double(slots) * bm * bn / speed;
+}
+
+int tile_choice(const GemmArgs &a, int epi)
 {
     const int forced = g_tile_option.load(std::memory_order_relaxed);
     if (forced != TILE_AUTO) return forced;
-    // 256x256 tiles (8 wavefronts, one workgroup per CU) halve the L2 traffic per FLOP; they pay
-    // off once the contraction is long enough to amortise their larger prologue and epilogue and
-    // there are enough of them to give every CU at least one.  Measured cross-over: K about 2048.
-    const int64_t big = int64_t((a.M + 255) / 256) * ((a.n_store + 255) / 256);
-    return (big >= 256 && a.K >= 2048) ? TILE_256x256 : TILE_128x128;
+    // Larger tiles run the main loop a few per cent faster at any contraction length (measured, both
+    // products, K from 128 to 16,384); what decides is how evenly the tile count fills the chip.
+    const bool gauss = epi == EPI_GAUSS;
+    const double c1 = launch_cost(a, 128, 128, 3, 1.0);
+    const double c2 = launch_cost(a, 256, 128, gauss ? 1 : 2, 1.03);
+    const double c3 = launch_cost(a, 256, 256, 1, gauss ? 1.07 : 1.04);
+    if (c3 <= c1 && c3 <= c2) return TILE_256x256;
+    return c2 <= c1 ? TILE_256x128 : TILE_128x128;
 }
 
 template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI, int PIPE>
@@ -145,7 +167,7 @@ hipError_t launch_tile(const GemmArgs &a, bool aligned, int epi, hipStream_t s)
 hipError_t launch_gemm(const GemmArgs &a, int epi, hipStream_t s)
 {
     const bool aligned = aligned16(a.A) && aligned16(a.B) && a.lda % 4 == 0 && a.ldb % 4 == 0 && a.K % 4 == 0;
-    switch (tile_choice(a)) {
+    switch (tile_choice(a, epi)) {
     case TILE_256x256: return launch_tile<256, 256, 4, 2>(a, aligned, epi, s);
     case TILE_256x128: return launch_tile<256, 128, 4, 2>(a, aligned, epi, s);
     default: return launch_tile<128, 128, 2, 2>(a, aligned, epi, s);

@@ -93,8 +93,10 @@ const char *lpd_strerror(int status);
  * beyond rounding, see the tile-independence tests).
  *   LPD_OPT_GEMM_TILE  workgroup tile of the two MFMA products:
  *                      0 = choose by shape, 1 = 128x128, 2 = 256x128, 3 = 256x256
- *   LPD_OPT_GEMM_PIPELINE  main-loop schedule of the MFMA products: 1 (default) =
- *                      software-pipelined across the barrier, 0 = plain load/compute/store
+ *   LPD_OPT_GEMM_PIPELINE  main-loop schedule of the MFMA products: 0 = plain load/compute/store,
+ *                      1 = software-pipelined across the barrier, 2 (default) = as 1, and the
+ *                      whitening product keeps two k-tiles in flight from memory instead of one
+ *                      (all three visit k in the same order: identical results)
  *   LPD_OPT_CSR_ROUTE  route of the compressed-row entry points: 0 (default) = by density,
  *                      1 = dense panels, 2 = gather; set it before the workspace query
  *   LPD_OPT_SMALL_PATH the factor for B <= 256 landmarks (and d <= 1024): 1 (default) = one

@@ -25,6 +25,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace lpd {
 
@@ -121,7 +122,12 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
 
     // rc: the four centre values of this thread's k columns (all its rows share them).  They are loaded with
     // the tile and subtracted on the way into LDS, so that nothing waits for a global load before it must.
-    f32x4 ra[PA], rb[PB], rc = {0.f, 0.f, 0.f, 0.f};
+    constexpr int NSET = PIPE == 2 ? 2 : 1;        // register sets of staged tiles (see the pipelined schedule)
+    f32x4 ra_[NSET][PA], rb_[NSET][PB], rc_[NSET];
+    f32x4(&ra)[PA] = ra_[0];
+    f32x4(&rb)[PB] = rb_[0];
+    f32x4 &rc = rc_[0];
+    rc = f32x4{0.f, 0.f, 0.f, 0.f};
     auto gload = [&](int k0) {
         const int k = k0 + lch * 4;
         if (ALIGNED) {
@@ -236,6 +242,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
         // Buffer (kt+1)&1 is overwritten in phase A of iteration kt; its previous tile kt-1 was last
         // read before the barrier of iteration kt-1, and each wavefront drains its LDS reads before a
         // barrier.  A partial last tile (K % 16 != 0) is handled after the loop by the plain schedule.
+        static_assert(PIPE == 1 || PIPE == 2, "schedules: 0 plain, 1 pipelined, 2 pipelined with two staged tiles");
         static_assert(BK == 16, "the pipelined schedule assumes two chunks per tile");
         static_assert(ALIGNED, "the pipelined schedule is for the 16-byte aligned fast path");
         constexpr int MEMOPS = TM + TN + PA + PB + (EPI == EPI_GAUSS ? 1 : 0);   // + the load of the centre values
@@ -252,14 +259,28 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
 #pragma unroll
             for (int q = 0; q < PB; ++q)
                 ob[q] = uint32_t(min(lrow + q * RPP, p.N - 1 - n0)) * uint32_t(p.ldb) * 4u + lch * 16u;
-            auto gload_full = [&](int tile) {
+            auto gload_full = [&](int tile, auto S) {
+                constexpr int st = decltype(S)::value;
                 const char *pa = baseA + size_t(tile) * (BK * 4);
                 const char *pb = baseB + size_t(tile) * (BK * 4);
 #pragma unroll
-                for (int q = 0; q < PA; ++q) ra[q] = *reinterpret_cast<const f32x4 *>(pa + oa[q]);
+                for (int q = 0; q < PA; ++q) ra_[st][q] = *reinterpret_cast<const f32x4 *>(pa + oa[q]);
 #pragma unroll
-                for (int q = 0; q < PB; ++q) rb[q] = *reinterpret_cast<const f32x4 *>(pb + ob[q]);
-                if (EPI == EPI_GAUSS) rc = *reinterpret_cast<const f32x4 *>(p.cen + tile * BK + lch * 4);
+                for (int q = 0; q < PB; ++q) rb_[st][q] = *reinterpret_cast<const f32x4 *>(pb + ob[q]);
+                if (EPI == EPI_GAUSS) rc_[st] = *reinterpret_cast<const f32x4 *>(p.cen + tile * BK + lch * 4);
+            };
+            auto lstore_set = [&](int buf, auto S) {
+                constexpr int st = decltype(S)::value;
+                float *As = lds + buf * STAGE;
+                float *Bs = As + BM * LDK;
+#pragma unroll
+                for (int q = 0; q < PA; ++q)
+                    *reinterpret_cast<f32x4 *>(&As[(lrow + q * RPP) * LDK + lch * 4]) =
+                        EPI == EPI_GAUSS ? ra_[st][q] - rc_[st] : ra_[st][q];
+#pragma unroll
+                for (int q = 0; q < PB; ++q)
+                    *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) =
+                        EPI == EPI_GAUSS ? rb_[st][q] - rc_[st] : rb_[st][q];
             };
             f32x4 a0[TM], b0[TN], a1[TM], b1[TN];
             auto fetch = [&](f32x4(&a)[TM], f32x4(&b)[TN], int buf, int kc) {
@@ -280,19 +301,15 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                         for (int j = 0; j < TN; ++j)
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[j][t], acc[i][j], 0, 0, 0);
             };
-
-            gload_full(0);
-            lstore(0);
-            gload_full(min(1, nfull - 1));
-            __syncthreads();
-            fetch(a0, b0, 0, 0);
-
-            for (int kt = 0; kt < nfull; ++kt) {
+            // One k-tile.  Register set S holds tile kt+1 on entry and is refilled with tile kt+1+NSET, so with
+            // two sets (PIPE == 2) a global load has a whole iteration and a half to arrive instead of half of
+            // one: what streams from HBM rather than from L2 (W of many landmarks) then never holds up phase A.
+            auto step = [&](int kt, auto S) {
                 const int cur = kt & 1;
                 // ---- phase A
                 fetch(a1, b1, cur, 1);
                 mma(a0, b0);
-                lstore(cur ^ 1);
+                lstore_set(cur ^ 1, S);
 #pragma unroll
                 for (int g = 0; g < TM + TN; ++g) {
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
@@ -305,7 +322,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                 }
                 __syncthreads();
                 // ---- phase B
-                gload_full(min(kt + 2, nfull - 1));
+                gload_full(min(kt + 1 + NSET, nfull - 1), S);
                 fetch(a0, b0, cur ^ 1, 0);
                 mma(a1, b1);
 #pragma unroll
@@ -318,6 +335,30 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0);
                 }
+            };
+            using S0 = std::integral_constant<int, 0>;
+            using S1 = std::integral_constant<int, NSET - 1>;
+
+            gload_full(0, S0{});
+            lstore_set(0, S0{});
+            if constexpr (NSET == 2) {
+                gload_full(min(1, nfull - 1), S1{});
+                gload_full(min(2, nfull - 1), S0{});
+            } else {
+                gload_full(min(1, nfull - 1), S0{});
+            }
+            __syncthreads();
+            fetch(a0, b0, 0, 0);
+
+            if constexpr (NSET == 2) {
+                int kt = 0;
+                for (; kt + 1 < nfull; kt += 2) {
+                    step(kt, S1{});
+                    step(kt + 1, S0{});
+                }
+                if (kt < nfull) step(kt, S1{});
+            } else {
+                for (int kt = 0; kt < nfull; ++kt) step(kt, S0{});
             }
             __syncthreads();
         }

@@ -89,7 +89,7 @@ enum TileId { TILE_AUTO = 0, TILE_128x128 = 1, TILE_256x128 = 2, TILE_256x256 = 
 
 // Tuning knobs of lpd_set_option.  Atomic, so that setting one while other threads are inside the library is
 // well defined: every launch reads the value once.
-std::atomic<int> g_pipe_option{1};            // LPD_OPT_GEMM_PIPELINE
+std::atomic<int> g_pipe_option{2};            // LPD_OPT_GEMM_PIPELINE
 std::atomic<int> g_tile_option{TILE_AUTO};   // LPD_OPT_GEMM_TILE
 std::atomic<int> g_csr_route{0};              // LPD_OPT_CSR_ROUTE: 0 by density, 1 dense panel, 2 gather
 std::atomic<int> g_sweep_grid{0};             // LPD_OPT_SWEEP_GRID: 0 = by row length, else the number of workgroups of a full sweep
@@ -152,12 +152,19 @@ hipError_t launch_tile(const GemmArgs &a, bool aligned, int epi, hipStream_t s)
 {
     // The pipelined schedule needs the aligned fast path and per-lane byte offsets inside one
     // tile strip that fit 32 bits.
-    const bool pipe = g_pipe_option.load(std::memory_order_relaxed) != 0 && aligned && int64_t(BM) * a.lda * 4 < (int64_t(1) << 31) &&
+    const int opt = g_pipe_option.load(std::memory_order_relaxed);
+    const bool pipe = opt != 0 && aligned && int64_t(BM) * a.lda * 4 < (int64_t(1) << 31) &&
                       int64_t(BN) * a.ldb * 4 < (int64_t(1) << 31);
     if (epi == EPI_GAUSS) {
+        // (two staged tiles cost this variant, which also carries the origin, wavefronts per SIMD or spills)
         if (pipe) return launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS, 1>(a, s);
         return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS, 0>(a, s)
                        : launch_one<BM, BN, WGM, WGN, false, EPI_GAUSS, 0>(a, s);
+    }
+    // two staged tiles: +1.5 % on the 256x256 tile at any K, more on the 128x128 tile at K about 1,000; the
+    // 256x128 tile would lose a wavefront per SIMD to the extra registers
+    if constexpr (!(BM == 256 && BN == 128)) {
+        if (pipe && opt == 2) return launch_one<BM, BN, WGM, WGN, true, EPI_STORE, 2>(a, s);
     }
     if (pipe) return launch_one<BM, BN, WGM, WGN, true, EPI_STORE, 1>(a, s);
     return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_STORE, 0>(a, s)
@@ -613,7 +620,7 @@ int lpd_set_option(int option, int64_t value)
         g_small_path.store(int(value), std::memory_order_relaxed);
         return LPD_OK;
     }
-    if (option == LPD_OPT_GEMM_PIPELINE && (value == 0 || value == 1)) {
+    if (option == LPD_OPT_GEMM_PIPELINE && value >= 0 && value <= 2) {
         g_pipe_option.store(int(value), std::memory_order_relaxed);
         return LPD_OK;
     }

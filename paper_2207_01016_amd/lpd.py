@@ -141,6 +141,7 @@ LPD_OPT_WHITEN_DC = 5
 LPD_OPT_WHITEN_UPPER = 6
 LPD_OPT_SWEEP_GRID = 7
 CSR_ROUTES = {"auto": 0, "dense": 1, "gather": 2}
+GEMM_PIPELINE_DEFAULT = 2
 GEMM_TILES = {"auto": 0, "128x128": 1, "256x128": 2, "256x256": 3}
 
 

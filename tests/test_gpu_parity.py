@@ -251,6 +251,38 @@ def test_streaming_factor_zero_fills_dropped_components(lpd, wls, dev):
     assert relfro(host.numpy(), G_dev.numpy()) <= 1e-6
 
 
+@pytest.mark.parametrize("tile", ["128x128", "256x128", "256x256"])
+@pytest.mark.parametrize("n,d,B", [
+    (700, 16, 272),        # one k-tile in the kernel block, 17 in the whitening product (odd: the peeled last step)
+    (300, 48, 288),        # 3 and 18 k-tiles (even)
+    (513, 36, 340),        # a partial last k-tile in both products
+    (260, 32, 260),        # 2 k-tiles and a partial one
+])
+def test_main_loop_schedules_agree_bit_for_bit(lpd, oracle, dev, n, d, B, tile):
+    """The plain schedule, the pipelined one and the one with two staged tiles visit k in the same order."""
+    g = torch.Generator().manual_seed(31 + n + B)
+    X = torch.randn((n, d), generator=g).to(dev)
+    L = torch.randn((B, d), generator=g).to(dev)
+    W = (torch.randn((B, B), generator=g) / B ** 0.5).to(dev)
+    gamma = 0.5 / d
+    ws = lpd.alloc_workspace(n, d, B, dev)
+    out = []
+    lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, lpd.GEMM_TILES[tile])
+    try:
+        for schedule in (0, 1, 2):
+            lpd.lpd_set_option(lpd.LPD_OPT_GEMM_PIPELINE, schedule)
+            G = torch.full((n, B), float("nan"), device=dev)
+            lpd.lpd_nystrom_factor(X, L, gamma, W, G, ws)
+            torch.cuda.synchronize()
+            out.append(G.cpu().numpy())
+    finally:
+        lpd.lpd_set_option(lpd.LPD_OPT_GEMM_PIPELINE, lpd.GEMM_PIPELINE_DEFAULT)
+        lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, 0)
+    ref = oracle.nystrom_factor(X.cpu().numpy(), L.cpu().numpy(), gamma, W.cpu().numpy())
+    assert relfro(out[0], ref) <= 1e-4
+    assert np.array_equal(out[0], out[1]) and np.array_equal(out[0], out[2])
+
+
 @pytest.mark.parametrize("n,d,B,r,gamma", [
     (2000, 16, 128, 128, 1.0 / 16),     # the tiny workload's shape
     (1, 7, 1, 1, 0.3),

@@ -31,6 +31,8 @@ namespace lpd {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+template <int I>
+using SI = std::integral_constant<int, I>;
 
 enum { EPI_STORE = 0, EPI_GAUSS = 1 };
 
@@ -247,6 +249,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
         static_assert(ALIGNED, "the pipelined schedule is for the 16-byte aligned fast path");
         constexpr int MEMOPS = TM + TN + PA + PB + (EPI == EPI_GAUSS ? 1 : 0);   // + the load of the centre values
         constexpr int MPG = (4 * TM * TN) / MEMOPS > 0 ? (4 * TM * TN) / MEMOPS : 1;
+        constexpr bool WRITES_FIRST = NSET == 2;
         const int nfull = p.K / BK;
 
         if (nfull > 0) {
@@ -302,25 +305,43 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[j][t], acc[i][j], 0, 0, 0);
             };
             // One k-tile.  Register set S holds tile kt+1 on entry and is refilled with tile kt+1+NSET, so with
-            // two sets (PIPE == 2) a global load has a whole iteration and a half to arrive instead of half of
-            // one: what streams from HBM rather than from L2 (W of many landmarks) then never holds up phase A.
+            // two sets a global load has a whole iteration and a half to arrive instead of half of one: what
+            // streams from HBM rather than from L2 (W of many landmarks) then never holds up phase A.  (A third
+            // set measured no faster on the 256x256 tile, whose registers it overflows.)
             auto step = [&](int kt, auto S) {
                 const int cur = kt & 1;
                 // ---- phase A
+                // (program order matters too: the compiler keeps LDS reads and writes it cannot tell apart in it)
+                if constexpr (WRITES_FIRST) lstore_set(cur ^ 1, S);
                 fetch(a1, b1, cur, 1);
                 mma(a0, b0);
-                lstore_set(cur ^ 1, S);
+                if constexpr (!WRITES_FIRST) lstore_set(cur ^ 1, S);
+                // A wavefront drains its LDS traffic before the barrier and issues nothing meanwhile, so what
+                // it issued last should be long done by then: the writes go first where the staged tile has
+                // had time to arrive (two sets), the reads first where it may not have (one set).
+                if constexpr (WRITES_FIRST) {
+#pragma unroll
+                    for (int g = 0; g < PA + PB; ++g) {
+                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
+                        __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0); // MPG MFMAs
+                    }
+                }
 #pragma unroll
                 for (int g = 0; g < TM + TN; ++g) {
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-                    __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0); // MPG MFMAs
-                }
-#pragma unroll
-                for (int g = 0; g < PA + PB; ++g) {
-                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
                     __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0);
                 }
+                if constexpr (!WRITES_FIRST) {
+#pragma unroll
+                    for (int g = 0; g < PA + PB; ++g) {
+                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0);
+                    }
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 4 * TM * TN - MPG * (TM + TN + PA + PB), 0);   // the rest of the MFMAs
+                __builtin_amdgcn_sched_barrier(0);      // each phase is scheduled on its own
                 __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
                 // ---- phase B
                 gload_full(min(kt + 1 + NSET, nfull - 1), S);
                 fetch(a0, b0, cur ^ 1, 0);
@@ -335,30 +356,24 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0);
                 }
+                __builtin_amdgcn_sched_group_barrier(0x008, 4 * TM * TN - MPG * MEMOPS, 0);
+                __builtin_amdgcn_sched_barrier(0);
             };
-            using S0 = std::integral_constant<int, 0>;
-            using S1 = std::integral_constant<int, NSET - 1>;
-
-            gload_full(0, S0{});
-            lstore_set(0, S0{});
-            if constexpr (NSET == 2) {
-                gload_full(min(1, nfull - 1), S1{});
-                gload_full(min(2, nfull - 1), S0{});
-            } else {
-                gload_full(min(1, nfull - 1), S0{});
-            }
+            // tile j of the contraction travels in register set j % NSET
+            gload_full(0, SI<0>{});
+            lstore_set(0, SI<0>{});
+            gload_full(min(1, nfull - 1), SI<1 % NSET>{});
+            if constexpr (NSET > 1) gload_full(min(2, nfull - 1), SI<2 % NSET>{});
             __syncthreads();
             fetch(a0, b0, 0, 0);
 
-            if constexpr (NSET == 2) {
-                int kt = 0;
-                for (; kt + 1 < nfull; kt += 2) {
-                    step(kt, S1{});
-                    step(kt + 1, S0{});
-                }
-                if (kt < nfull) step(kt, S1{});
-            } else {
-                for (int kt = 0; kt < nfull; ++kt) step(kt, S0{});
+            int kt = 0;
+            for (; kt + NSET <= nfull; kt += NSET) {
+                step(kt, SI<1 % NSET>{});
+                if constexpr (NSET > 1) step(kt + 1, SI<2 % NSET>{});
+            }
+            if constexpr (NSET > 1) {
+                if (kt < nfull) step(kt++, SI<1 % NSET>{});
             }
             __syncthreads();
         }

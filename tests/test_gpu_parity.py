@@ -257,6 +257,9 @@ def test_streaming_factor_zero_fills_dropped_components(lpd, wls, dev):
     (300, 48, 288),        # 3 and 18 k-tiles (even)
     (513, 36, 340),        # a partial last k-tile in both products
     (260, 32, 260),        # 2 k-tiles and a partial one
+    (1100, 64, 1040),      # 65 k-tiles, several tiles of every shape, ragged edges in both directions
+    (256, 16, 16),         # a single k-tile in the whitening product
+    (300, 16, 48),         # 3 k-tiles
 ])
 def test_main_loop_schedules_agree_bit_for_bit(lpd, oracle, dev, n, d, B, tile):
     """The plain schedule, the pipelined one and the one with two staged tiles visit k in the same order."""

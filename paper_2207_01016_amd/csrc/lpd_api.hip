@@ -228,10 +228,11 @@ hipError_t launch_margins_lpr(const float *G, int64_t n_out, int r, int64_t ldg,
 {
     // A full sweep over long rows runs fastest with few rows open at once (about 128 MB of them): 512 workgroups
     // at 32 KB per row, one per CU at 64 KB.  Measured at 16,384 columns: 6.7 TB/s with 4,096 workgroups, 7.2 TB/s
-    // with 256.  Shorter rows and row lists (scattered rows) keep the large grid.
+    // with 256.  Shorter rows and row lists (scattered rows) keep a large grid; for a sweep that lasts only tens of
+    // microseconds (100,000 rows of 4 KB) one pass of 12,500 workgroups is 3 us faster than 4,096 taking three turns.
     const int forced = g_sweep_grid.load(std::memory_order_relaxed);
     const int64_t cap = (forced > 0 && !INDEXED) ? forced
-                        : (INDEXED || r < 8192) ? 4096 : std::max<int64_t>(256, (int64_t(4) << 20) / r);
+                        : INDEXED ? 4096 : r < 8192 ? 16384 : std::max<int64_t>(256, (int64_t(4) << 20) / r);
     const unsigned grid = row_grid(n_out, 256 / LPR * ROWS, cap);
     if (vec) hipLaunchKernelGGL((margins_kernel<LPR, true, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, n_rows_G, w, m, ms);
     else hipLaunchKernelGGL((margins_kernel<LPR, false, INDEXED, ROWS>), dim3(grid), dim3(256), 0, s, G, n_out, r, ldg, rows, n_rows_G, w, m, ms);

@@ -431,8 +431,13 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        crow[int64_t(e) * p.ldc + j * 32] = finish(acc[i][j][4 * g + e], nav[e], nbv[j]);
+                    for (int j = 0; j < TN; ++j) {
+                        const float out = finish(acc[i][j][4 * g + e], nav[e], nbv[j]);
+                        // G is not read again by this launch or the next: its stores need not stay in L2, where they
+                        // would push out operand strips and leave dirty lines to write back when the kernel ends
+                        if (EPI == EPI_STORE) __builtin_nontemporal_store(out, &crow[int64_t(e) * p.ldc + j * 32]);
+                        else crow[int64_t(e) * p.ldc + j * 32] = out;
+                    }
                 }
             }
         }
@@ -451,7 +456,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                     const int rl = wm * WM + i * 32 + 8 * (v >> 2) + row_in + (v & 3);
                     if (m0 + rl >= p.M) continue;
                     const float out = finish(acc[i][j][v], EPI == EPI_GAUSS ? nas[rl] : 0.0f, nbv);
-                    p.C[int64_t(m0 + rl) * p.ldc + cc] = live ? out : 0.0f;
+                    if (EPI == EPI_STORE) __builtin_nontemporal_store(live ? out : 0.0f, &p.C[int64_t(m0 + rl) * p.ldc + cc]);
+                    else p.C[int64_t(m0 + rl) * p.ldc + cc] = live ? out : 0.0f;
                 }
             }
         }

@@ -232,23 +232,26 @@ __global__ __launch_bounds__(256) void symv_kernel(const double *__restrict__ A,
 
 // The same product from the UPPER triangle alone: the trailing matrix is symmetric, so an element A[a, c],
 // c > a, serves row a (times v[c]) and row c (times v[a]) in one read, and the pass reads half the bytes.
-// Work item = a strip of 64 rows (16 per wavefront) times a segment of 2048 columns, walked in chunks of 128
-// columns; a lane holds 2 columns of the chunk and 16 row sums.  Row sums of a segment go to
+// Work item = a strip of 64 rows (16 per wavefront) times a segment of `nch` chunks of 128 columns (4 chunks;
+// 2 once the trailing matrix has 8,192 rows or fewer, so that the strips left still make enough workgroups and
+// each one's serial walk, a memory round trip per chunk, is short; 8 chunks measured 2 % slower at 16,384 rows); a lane holds 2 columns of the chunk and 16 row sums.  Row sums of a segment go to
 // rowpart[segment][row]; the column sums of a chunk are combined over the four wavefronts in LDS and go to
 // colpart[strip][column]; yfix_kernel adds both up in a fixed order (no atomics: the result does not depend
 // on the order in which workgroups finish).  Elements left of the diagonal are read with their chunk and
 // masked; they are never meant: the panel update (syr2k_kernel) maintains the upper triangle only.
 // blockIdx.y >= n_strips: the panel dots, as in symv_kernel.
-constexpr int SY_ROWS = 64, SY_WR = 16, SY_CH = 128, SY_NCH = 8, SY_SEG = SY_CH * SY_NCH;
+constexpr int SY_ROWS = 64, SY_WR = 16, SY_CH = 128, SY_NCH = 4, SY_SEG = SY_CH * SY_NCH;
+constexpr int SY_SMALL = 8192, SY_NCH_SMALL = 2;     // trailing matrices of up to SY_SMALL rows: segments of 2 chunks
 
 template <bool VEC>
 __global__ __launch_bounds__(256) void symv_upper_kernel(const double *__restrict__ A, int n, int j, int n_strips,
                                                          const double *__restrict__ v, double *__restrict__ rowpart,
                                                          double *__restrict__ colpart, const double *__restrict__ Vp,
-                                                         const double *__restrict__ Wp, double *__restrict__ coef)
+                                                         const double *__restrict__ Wp, double *__restrict__ coef, int nch)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: row addresses stay scalar
+    const int seg = nch * SY_CH;
     if (int(blockIdx.y) >= n_strips) {
         if (blockIdx.x != 0) return;
         __shared__ double red[16];
@@ -268,7 +271,7 @@ __global__ __launch_bounds__(256) void symv_upper_kernel(const double *__restric
     __shared__ double cpart[4][SY_SEG];
     const int strip = (j + 1) / SY_ROWS + blockIdx.y;          // absolute strip: rows 64 strip .. 64 strip + 63
     const int c_first = (strip * SY_ROWS) & ~(SY_CH - 1);      // chunk that holds the strip's first diagonal element
-    const int seg0 = c_first + blockIdx.x * SY_SEG;
+    const int seg0 = c_first + blockIdx.x * seg;
     if (seg0 >= n) return;
     const int a_base = strip * SY_ROWS + wave * SY_WR;
     // Rows outside (j, n) are read from a row inside it and carry no weight: every lane issues the same 16 loads
@@ -287,7 +290,7 @@ __global__ __launch_bounds__(256) void symv_upper_kernel(const double *__restric
     // not fit the register file; requesting the next chunk before summing the current one was tried and costs
     // more in occupancy than it gains); a wavefront parks its column sums in its own LDS row, no barrier until the end
 #pragma unroll 1
-    for (int ch = 0; ch < SY_NCH; ++ch) {
+    for (int ch = 0; ch < nch; ++ch) {
         const int c = seg0 + ch * SY_CH + 2 * lane;
         const int cl = VEC ? min(c, n - 2) : min(c, n - 1);     // a column inside the row for lanes past its end
         const double v0 = (c > j && c < n) ? v[c] : 0.0;
@@ -318,7 +321,7 @@ __global__ __launch_bounds__(256) void symv_upper_kernel(const double *__restric
         cpart[wave][ch * SY_CH + 2 * lane + 1] = c1;
     }
     __syncthreads();
-    for (int t = threadIdx.x; t < SY_SEG; t += 256)
+    for (int t = threadIdx.x; t < seg; t += 256)
         if (seg0 + t < n)
             colpart[int64_t(blockIdx.y) * n + seg0 + t] = (cpart[0][t] + cpart[1][t]) + (cpart[2][t] + cpart[3][t]);
 #pragma unroll
@@ -334,8 +337,9 @@ __global__ __launch_bounds__(256) void symv_upper_kernel(const double *__restric
 __global__ __launch_bounds__(256) void yfix_kernel(int n, int j, int i, const double *__restrict__ rowpart,
                                                    const double *__restrict__ colpart, const double *__restrict__ Vp,
                                                    const double *__restrict__ Wp, const double *__restrict__ coef,
-                                                   double *__restrict__ y)
+                                                   double *__restrict__ y, int seg)
 {
+    // seg: columns per segment of the pass that wrote the partial sums
     // 64 columns per workgroup; the strips (up to n / 64 of them) are dealt round-robin to its four wavefronts,
     // four sums in flight each, and met in LDS in a fixed order
     __shared__ double part[4][64];
@@ -359,7 +363,7 @@ __global__ __launch_bounds__(256) void yfix_kernel(int n, int j, int i, const do
     if (w != 0 || c >= n) return;
     double v = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
     const int c_first = (strip * SY_ROWS) & ~(SY_CH - 1);
-    const int nseg = (n - c_first + SY_SEG - 1) / SY_SEG;
+    const int nseg = (n - c_first + seg - 1) / seg;
     for (int g = 0; g < nseg; ++g) v += rowpart[int64_t(g) * n + c];
     for (int k = 0; k < i; ++k) v -= Vp[int64_t(k) * n + c] * coef[2 * k] + Wp[int64_t(k) * n + c] * coef[2 * k + 1];
     y[c] = v;
@@ -1096,7 +1100,10 @@ DevCarve dev_carve(int64_t n)
     c.off_G = o; o += n >= kDcMin ? nn : 0;
     c.off_dc = o; o += 14 * vec;
     c.off_uq = o; o += extra * vec;
-    c.off_rowpart = o; o += (size_t(n) / SY_SEG + 2) * vec;
+    // segments per row: n / 512 of the long ones, or, once the trailing matrix has SY_SMALL rows or fewer (its first
+    // chunk then starts no more than SY_SMALL + SY_CH columns from the end), that many columns in short ones
+    c.off_rowpart = o;
+    o += (std::max(size_t(n) / SY_SEG, std::min(size_t(n), size_t(SY_SMALL + SY_CH)) / (SY_NCH_SMALL * SY_CH)) + 2) * vec;
     c.off_colpart = o; o += (size_t(n) / SY_ROWS + 2) * vec;
     c.off_Y = o; o += round_up(size_t(5) * size_t(std::max<int64_t>(n, 1)) * 32 * 8, kAlign);
     c.bytes = o;
@@ -1450,15 +1457,17 @@ extern "C" int lpd_whiten(const float *L, int64_t B, int64_t d, int64_t ldl, dou
                     const int s_first = (j + 1) / SY_ROWS;
                     const int n_strips = (n - 1) / SY_ROWS - s_first + 1;
                     const int c_first = (s_first * SY_ROWS) & ~(SY_CH - 1);
-                    const int nseg = (n - c_first + SY_SEG - 1) / SY_SEG;
+                    const int nch = rows <= SY_SMALL ? SY_NCH_SMALL : SY_NCH;
+                    const int seg = nch * SY_CH;
+                    const int nseg = (n - c_first + seg - 1) / seg;
                     if (even)
                         hipLaunchKernelGGL((symv_upper_kernel<true>), dim3(nseg, n_strips + i), dim3(256), 0, s, A, n, j,
-                                           n_strips, vi, rowpart, colpart, Vp, Wp, coef);
+                                           n_strips, vi, rowpart, colpart, Vp, Wp, coef, nch);
                     else
                         hipLaunchKernelGGL((symv_upper_kernel<false>), dim3(nseg, n_strips + i), dim3(256), 0, s, A, n, j,
-                                           n_strips, vi, rowpart, colpart, Vp, Wp, coef);
+                                           n_strips, vi, rowpart, colpart, Vp, Wp, coef, nch);
                     hipLaunchKernelGGL(yfix_kernel, dim3((rows + 63) / 64), dim3(256), 0, s, n, j, i, rowpart, colpart, Vp,
-                                       Wp, coef, y);
+                                       Wp, coef, y, seg);
                 } else {
                     const int row_blocks = std::min(512, even ? ((rows + 1) / 2 + 3) / 4 : (rows + 3) / 4);
                     if (even)

@@ -56,7 +56,7 @@ def parse_args():
                          "cnn for predict and whiten, digit for stream and sparse")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tile", default="auto", choices=["auto", "128x128", "256x128", "256x256"])
+    ap.add_argument("--tile", default="auto", choices=["auto", "128x128", "256x128", "256x256", "64x128"])
     ap.add_argument("--workspace-mult", type=float, default=1.0)
     ap.add_argument("--panel-rows", type=int, default=0,
                     help="factor: size the workspace for kernel-block panels of this many rows (a multiple of 256; "

@@ -92,7 +92,7 @@ const char *lpd_strerror(int status);
  * change takes effect from the next launch on (results do not depend on them
  * beyond rounding, see the tile-independence tests).
  *   LPD_OPT_GEMM_TILE  workgroup tile of the two MFMA products:
- *                      0 = choose by shape, 1 = 128x128, 2 = 256x128, 3 = 256x256
+ *                      0 = choose by shape, 1 = 128x128, 2 = 256x128, 3 = 256x256, 4 = 64x128
  *   LPD_OPT_GEMM_PIPELINE  main-loop schedule of the MFMA products: 0 = plain load/compute/store,
  *                      1 = software-pipelined across the barrier, 2 (default) = as 1, and the
  *                      whitening product keeps two k-tiles in flight from memory instead of one

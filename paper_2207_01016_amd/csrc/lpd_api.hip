@@ -85,7 +85,7 @@ StreamCarve stream_carve(int64_t chunk_rows, int64_t d, int64_t B)
 
 // ---------------------------------------------------------------- GEMM launch
 
-enum TileId { TILE_AUTO = 0, TILE_128x128 = 1, TILE_256x128 = 2, TILE_256x256 = 3 };
+enum TileId { TILE_AUTO = 0, TILE_128x128 = 1, TILE_256x128 = 2, TILE_256x256 = 3, TILE_64x128 = 4 };
 
 // Tuning knobs of lpd_set_option.  Atomic, so that setting one while other threads are inside the library is
 // well defined: every launch reads the value once.
@@ -96,10 +96,11 @@ std::atomic<int> g_sweep_grid{0};             // LPD_OPT_SWEEP_GRID: 0 = by row 
 std::atomic<int> g_small_path{1};             // LPD_OPT_SMALL_PATH: 1 = one-launch factor for B <= 256, 0 = panel schedule
 
 // Estimated duration of a launch with BM x BN tiles, in units of (CUs x tile elements): a CU holds `per_cu`
-// workgroups (registers: 3 of the 128x128 tile, 2 of the 256x128 tile of the plain product, else 1), a launch
-// runs in rounds of 256 x per_cu tiles, and a last round that leaves CUs with fewer workgroups than they can
-// hold goes faster, though not in proportion (a lone 4-wavefront workgroup cannot keep a CU's MFMA pipes
-// full).  `speed` is the measured main-loop advantage of the larger tiles (less LDS and L2 traffic per FLOP).
+// workgroups (registers and LDS: 5 of the 64x128 tile, 3 of the 128x128 tile, 2 of the 256x128 tile of the plain
+// product, else 1), a launch runs in rounds of 256 x per_cu tiles, and a last round that leaves CUs with fewer
+// workgroups than they can hold goes faster, though not in proportion (a lone 4-wavefront workgroup cannot keep a
+// CU's MFMA pipes full).  `speed` is the measured main-loop rate relative to the 128x128 tile (larger tiles
+// move less through LDS and L2 per FLOP).
 double launch_cost(const GemmArgs &a, int bm, int bn, int per_cu, double speed)
 {
     const int64_t tiles = int64_t((a.M + bm - 1) / bm) * ((a.n_store + bn - 1) / bn);
@@ -108,24 +109,44 @@ double launch_cost(const GemmArgs &a, int bm, int bn, int per_cu, double speed)
     double rounds = double(tiles / slots);
     if (rem > 0) {
         const int64_t deep = (rem + 255) / 256;          // workgroups on the fullest CU in the last round
-        static const double part3[4] = {0.0, 0.45, 0.75, 1.0}, part2[3] = {0.0, 0.6, 1.0};
-        rounds += per_cu == 3 ? part3[deep] : per_cu == 2 ? part2[deep] : 1.0;
+        rounds += deep >= per_cu ? 1.0 : 0.2 + 0.8 * double(deep) / per_cu;
     }
     return rounds * double(slots) * bm * bn / speed;
+}
+
+// Main-loop-plus-write-out rate of a tile relative to the 128x128 tile, measured on launches that fill the chip
+// evenly.  The plain product: larger tiles move less through LDS and L2 per FLOP.  The kernel block: the same for
+// long contractions; for short ones the write-out of Z weighs as much as the MFMAs, and small tiles, of which a
+// CU holds five, overlap the two better than one large workgroup that does one after the other.
+double tile_speed(int tile, int epi, int K)
+{
+    if (epi != EPI_GAUSS)       // (the small tile re-reads its operands most: worse where W streams from HBM, K beyond 4,096)
+        return tile == TILE_256x256 ? 1.04 : tile == TILE_256x128 ? 1.03 : tile == TILE_64x128 ? (K > 4096 ? 0.88 : 0.95) : 1.0;
+    switch (tile) {
+    case TILE_256x256: return K >= 512 ? 1.07 : K >= 256 ? 1.04 : K >= 128 ? 1.02 : K >= 64 ? 0.95 : 0.85;
+    case TILE_256x128: return K >= 128 ? 1.03 : 0.95;
+    case TILE_64x128: return K >= 1024 ? 0.96 : K >= 256 ? 0.975 : K >= 128 ? 1.0 : K >= 64 ? 1.1 : 1.25;
+    default: return 1.0;
+    }
 }
 
 int tile_choice(const GemmArgs &a, int epi)
 {
     const int forced = g_tile_option.load(std::memory_order_relaxed);
     if (forced != TILE_AUTO) return forced;
-    // Larger tiles run the main loop a few per cent faster at any contraction length (measured, both
-    // products, K from 128 to 16,384); what decides is how evenly the tile count fills the chip.
+    // What decides, besides the tiles' own rates, is how evenly the tile count fills the chip.  The smallest
+    // tile is for launches of few rows (a ragged last panel, a small batch to predict), which the others would
+    // spread over a fraction of the CUs, and for kernel blocks over very few features.
     const bool gauss = epi == EPI_GAUSS;
-    const double c1 = launch_cost(a, 128, 128, 3, 1.0);
-    const double c2 = launch_cost(a, 256, 128, gauss ? 1 : 2, 1.03);
-    const double c3 = launch_cost(a, 256, 256, 1, gauss ? 1.07 : 1.04);
-    if (c3 <= c1 && c3 <= c2) return TILE_256x256;
-    return c2 <= c1 ? TILE_256x128 : TILE_128x128;
+    const double cost[5] = {0.0,
+                            launch_cost(a, 128, 128, 3, tile_speed(TILE_128x128, epi, a.K)),
+                            launch_cost(a, 256, 128, gauss ? 1 : 2, tile_speed(TILE_256x128, epi, a.K)),
+                            launch_cost(a, 256, 256, 1, tile_speed(TILE_256x256, epi, a.K)),
+                            launch_cost(a, 64, 128, gauss ? 5 : 4, tile_speed(TILE_64x128, epi, a.K))};
+    int best = TILE_128x128;
+    for (int t : {TILE_256x128, TILE_256x256, TILE_64x128})
+        if (cost[t] < cost[best]) best = t;
+    return best;
 }
 
 template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI, int PIPE>
@@ -177,6 +198,7 @@ hipError_t launch_gemm(const GemmArgs &a, int epi, hipStream_t s)
     switch (tile_choice(a, epi)) {
     case TILE_256x256: return launch_tile<256, 256, 4, 2>(a, aligned, epi, s);
     case TILE_256x128: return launch_tile<256, 128, 4, 2>(a, aligned, epi, s);
+    case TILE_64x128: return launch_tile<64, 128, 2, 2>(a, aligned, epi, s);
     default: return launch_tile<128, 128, 2, 2>(a, aligned, epi, s);
     }
 }
@@ -597,7 +619,7 @@ const char *lpd_strerror(int status)
 
 int lpd_set_option(int option, int64_t value)
 {
-    if (option == LPD_OPT_GEMM_TILE && value >= TILE_AUTO && value <= TILE_256x256) {
+    if (option == LPD_OPT_GEMM_TILE && value >= TILE_AUTO && value <= TILE_64x128) {
         g_tile_option.store(int(value), std::memory_order_relaxed);
         return LPD_OK;
     }

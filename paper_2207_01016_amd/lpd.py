@@ -142,7 +142,7 @@ LPD_OPT_WHITEN_UPPER = 6
 LPD_OPT_SWEEP_GRID = 7
 CSR_ROUTES = {"auto": 0, "dense": 1, "gather": 2}
 GEMM_PIPELINE_DEFAULT = 2
-GEMM_TILES = {"auto": 0, "128x128": 1, "256x128": 2, "256x256": 3}
+GEMM_TILES = {"auto": 0, "128x128": 1, "256x128": 2, "256x256": 3, "64x128": 4}
 
 
 def lpd_set_option(option: int, value: int) -> None:

@@ -130,8 +130,8 @@ def test_margins_and_kernel_block_argument_errors(L):
     assert L.lpd_kernel_block(p, 4, 4, 4, p, 8, 4, 0.5, p, 7, p, 4096, None) == -3
     assert L.lpd_kernel_block(p, 4, 4, 4, p, 8, 4, 0.5, p, 8, None, 0, None) == -4
     assert L.lpd_kernel_block(p, 0, 4, 4, p, 8, 4, 0.5, p, 8, None, 0, None) == 0
-    assert L.lpd_set_option(1, 3) == 0 and L.lpd_set_option(1, 0) == 0
-    assert L.lpd_set_option(1, 9) == -2 and L.lpd_set_option(77, 0) == -2
+    assert L.lpd_set_option(1, 3) == 0 and L.lpd_set_option(1, 4) == 0 and L.lpd_set_option(1, 0) == 0
+    assert L.lpd_set_option(1, 5) == -2 and L.lpd_set_option(1, 9) == -2 and L.lpd_set_option(77, 0) == -2
 
 
 def test_solver_and_predict_argument_errors(L):

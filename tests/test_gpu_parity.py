@@ -68,7 +68,7 @@ def _factor(lpd, X, L, gamma, W, rank, ws_bytes=None):
     (513, 128, 260, 1.0 / 128),
     (130, 1, 129, 0.5),
 ])
-@pytest.mark.parametrize("tile", ["128x128", "256x128", "256x256"])
+@pytest.mark.parametrize("tile", ["128x128", "256x128", "256x256", "64x128"])
 def test_kernel_block_matches_oracle(lpd, oracle, dev, n, d, B, gamma, tile):
     g = torch.Generator().manual_seed(1000 + n + d + B)
     X = torch.randn((n, d), generator=g).to(dev)
@@ -184,7 +184,7 @@ def test_factor_is_deterministic_and_tile_independent(lpd, wls, dev):
     wl = wls.WORKLOADS["small"].with_shape(n=3000, B=384)
     X, idx, L, W, eig, rank = _prepare(lpd, wls, wl, dev)
     outs = {}
-    for tile in ["128x128", "256x128", "256x256"]:
+    for tile in ["128x128", "256x128", "256x256", "64x128"]:
         lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, lpd.GEMM_TILES[tile])
         try:
             a = _factor(lpd, X, L, wl.gamma, W, rank)
@@ -251,7 +251,7 @@ def test_streaming_factor_zero_fills_dropped_components(lpd, wls, dev):
     assert relfro(host.numpy(), G_dev.numpy()) <= 1e-6
 
 
-@pytest.mark.parametrize("tile", ["128x128", "256x128", "256x256"])
+@pytest.mark.parametrize("tile", ["128x128", "256x128", "256x256", "64x128"])
 @pytest.mark.parametrize("n,d,B", [
     (700, 16, 272),        # one k-tile in the kernel block, 17 in the whitening product (odd: the peeled last step)
     (300, 48, 288),        # 3 and 18 k-tiles (even)

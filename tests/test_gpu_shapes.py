@@ -22,7 +22,7 @@ def _cases(count, seed):
         B = int(rng.integers(1, 600))
         r = int(rng.integers(1, B + 1))
         pads = [int(rng.choice([0, 1, 3, 4, 8])) for _ in range(4)]
-        tile = ["auto", "128x128", "256x128", "256x256"][int(rng.integers(0, 4))]
+        tile = ["auto", "128x128", "256x128", "256x256", "64x128"][int(rng.integers(0, 5))]
         out.append(pytest.param(n, d, B, r, pads, tile, i, id=f"{i}-n{n}-d{d}-B{B}-r{r}-{tile}"))
     return out
 

@@ -288,7 +288,10 @@ def bench_predict(args):
         "config": {"workload": wl.name + " (first rows as new points)", "n_test": n_test, "d": wl.d, "B": wl.B,
                    "rank": rank, "classifiers": c, "gamma": wl.gamma},
         "whiten_s": None if args.random_w else t_whiten,
-        "roofline": {"kernel": "lpd_predict: gemm_nt_kernel<EPI_GAUSS> panels + consumer", "bound": "mfma",
+        "roofline": {"kernel": ("lpd_predict: gemm_nt_kernel<EPI_GAUSS_DOT> (kernel block contracted with the folded weights "
+                                "in its own launch) + the pass that adds the tile columns' shares" if c <= 32 else
+                                "lpd_predict: gemm_nt_kernel<EPI_GAUSS> panels + MFMA product with the folded weights"),
+                     "bound": "mfma",
                      "achieved": tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / FP32_MFMA_PEAK_TFLOPS, "flop_per_launch": flop, "avg_launch_ms": ms,
                      "traffic": None},

@@ -104,6 +104,9 @@ const char *lpd_strerror(int status);
  *   LPD_OPT_WHITEN_DC  lpd_whiten for B >= 512: 1 (default) = the tridiagonal problem is torn in two,
  *                      the halves solved concurrently and merged on the device; 0 = one QL
  *                      iteration over the whole matrix
+ *   LPD_OPT_FUSED_SCORES prediction with up to 16 classifiers: 1 (default) = the kernel block is multiplied by
+ *                      the folded weights in the write-out of its own launch and never stored; 0 = a panel of it
+ *                      is stored and swept
  *   LPD_OPT_SWEEP_GRID workgroups of a full margin sweep: 0 (default) = chosen by the row length,
  *                      1..65536 = that many (each takes rows in a grid-stride loop)
  *   LPD_OPT_WHITEN_UPPER  lpd_whiten's reduction to tridiagonal form: 1 (default) = reads and updates the
@@ -112,7 +115,7 @@ const char *lpd_strerror(int status);
  */
 typedef enum { LPD_OPT_GEMM_TILE = 1, LPD_OPT_GEMM_PIPELINE = 2, LPD_OPT_CSR_ROUTE = 3,
                LPD_OPT_SMALL_PATH = 4, LPD_OPT_WHITEN_DC = 5, LPD_OPT_WHITEN_UPPER = 6,
-               LPD_OPT_SWEEP_GRID = 7 } lpd_option;
+               LPD_OPT_SWEEP_GRID = 7, LPD_OPT_FUSED_SCORES = 8 } lpd_option;
 int lpd_set_option(int option, int64_t value);
 
 /*

@@ -37,7 +37,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 template <int I>
 using SI = std::integral_constant<int, I>;
 
-enum { EPI_STORE = 0, EPI_GAUSS = 1 };
+enum { EPI_STORE = 0, EPI_GAUSS = 1, EPI_GAUSS_DOT = 2 };
+constexpr int GEMM_DOT_MAX = 32;     // weight vectors the EPI_GAUSS_DOT write-out takes at once
 
 struct GemmArgs {
     const float *A;  // M x K
@@ -54,19 +55,31 @@ struct GemmArgs {
     // distance itself instead of the size of ||x||^2, which is what their fp32 rounding scales with.
     const float *na, *nb, *cen;
     float scale;
+    // EPI_GAUSS_DOT: the kernel block is not written; its tile is multiplied at once by nv <= GEMM_DOT_MAX weight
+    // vectors (rows of V, nv x N, leading dimension ldv) and the tile's share of the scores goes to
+    // P[tile column][row][vector] (tiles_n x M x nv floats); a pass over the tile columns adds them up.
+    const float *V;
+    int64_t ldv;
+    int nv;
+    float *P;
 };
 
 constexpr int GEMM_BK = 16;
 constexpr int GEMM_LDK = GEMM_BK + 4;
 
-// two stages of operand tiles, then the BM + BN squared norms of the tile's rows and columns (EPI_GAUSS)
-template <int BM, int BN>
-constexpr size_t gemm_lds_bytes() { return (size_t(2) * (BM + BN) * GEMM_LDK + (BM + BN)) * sizeof(float); }
+// two stages of operand tiles, then the BM + BN squared norms of the tile's rows and columns (EPI_GAUSS),
+// then the tile's columns of the weight vectors (EPI_GAUSS_DOT)
+template <int BM, int BN, int EPI = EPI_STORE>
+constexpr size_t gemm_lds_bytes()
+{
+    return (size_t(2) * (BM + BN) * GEMM_LDK + (BM + BN) + (EPI == EPI_GAUSS_DOT ? GEMM_DOT_MAX * BN : 0)) * sizeof(float);
+}
 
 template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI, int PIPE>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
 {
     constexpr int BK = GEMM_BK, LDK = GEMM_LDK;
+    constexpr bool GAUSS = EPI != EPI_STORE;      // the kernel block, written out (EPI_GAUSS) or contracted at once (EPI_GAUSS_DOT)
     constexpr int NT = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -141,7 +154,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                 for (int q = 0; q < PA; ++q) ra[q] = *reinterpret_cast<const f32x4 *>(ga[q] + k0);
 #pragma unroll
                 for (int q = 0; q < PB; ++q) rb[q] = *reinterpret_cast<const f32x4 *>(gb[q] + k0);
-                if (EPI == EPI_GAUSS) rc = *reinterpret_cast<const f32x4 *>(p.cen + k);
+                if (GAUSS) rc = *reinterpret_cast<const f32x4 *>(p.cen + k);
             } else {
 #pragma unroll
                 for (int q = 0; q < PA; ++q) ra[q] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -158,7 +171,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
             for (int q = 0; q < PB; ++q)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) rb[q][e] = (k + e < p.K) ? gb[q][k0 + e] : 0.0f;
-            if (EPI == EPI_GAUSS) {
+            if (GAUSS) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) rc[e] = (k + e < p.K) ? p.cen[k + e] : 0.0f;
             }
@@ -169,18 +182,27 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
         float *Bs = As + BM * LDK;
 #pragma unroll
         for (int q = 0; q < PA; ++q)
-            *reinterpret_cast<f32x4 *>(&As[(lrow + q * RPP) * LDK + lch * 4]) = EPI == EPI_GAUSS ? ra[q] - rc : ra[q];
+            *reinterpret_cast<f32x4 *>(&As[(lrow + q * RPP) * LDK + lch * 4]) = GAUSS ? ra[q] - rc : ra[q];
 #pragma unroll
         for (int q = 0; q < PB; ++q)
-            *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) = EPI == EPI_GAUSS ? rb[q] - rc : rb[q];
+            *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) = GAUSS ? rb[q] - rc : rb[q];
     };
 
     // The squared norms the epilogue needs go to LDS now, so that after the main loop nothing waits for
     // global memory: a load there would also wait for every store issued before it (one counter orders both).
     float *nas = lds + 2 * STAGE, *nbs = nas + BM;
-    if (EPI == EPI_GAUSS) {
+    if (GAUSS) {
         for (int e = tid; e < BM + BN; e += NT)
             nas[e] = e < BM ? p.na[min(m0 + e, p.M - 1)] : p.nb[min(n0 + e - BM, p.N - 1)];
+    }
+    // EPI_GAUSS_DOT: the tile's columns of the weight vectors, zero past column N, so that a column outside the
+    // matrix adds nothing whatever its accumulator holds
+    float *vs = nbs + BN;
+    if constexpr (EPI == EPI_GAUSS_DOT) {
+        for (int e = tid; e < p.nv * BN; e += NT) {
+            const int q = e / BN, cl = e - q * BN;
+            vs[e] = n0 + cl < p.N ? p.V[int64_t(q) * p.ldv + n0 + cl] : 0.0f;
+        }
     }
 
     f32x16 acc[TM][TN];
@@ -250,7 +272,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
         static_assert(PIPE == 1 || PIPE == 2, "schedules: 0 plain, 1 pipelined, 2 pipelined with two staged tiles");
         static_assert(BK == 16, "the pipelined schedule assumes two chunks per tile");
         static_assert(ALIGNED, "the pipelined schedule is for the 16-byte aligned fast path");
-        constexpr int MEMOPS = TM + TN + PA + PB + (EPI == EPI_GAUSS ? 1 : 0);   // + the load of the centre values
+        constexpr int MEMOPS = TM + TN + PA + PB + (GAUSS ? 1 : 0);   // + the load of the centre values
         constexpr int MPG = (4 * TM * TN) / MEMOPS > 0 ? (4 * TM * TN) / MEMOPS : 1;
         constexpr bool WRITES_FIRST = NSET == 2;
         const int nfull = p.K / BK;
@@ -273,7 +295,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                 for (int q = 0; q < PA; ++q) ra_[st][q] = *reinterpret_cast<const f32x4 *>(pa + oa[q]);
 #pragma unroll
                 for (int q = 0; q < PB; ++q) rb_[st][q] = *reinterpret_cast<const f32x4 *>(pb + ob[q]);
-                if (EPI == EPI_GAUSS) rc_[st] = *reinterpret_cast<const f32x4 *>(p.cen + tile * BK + lch * 4);
+                if (GAUSS) rc_[st] = *reinterpret_cast<const f32x4 *>(p.cen + tile * BK + lch * 4);
             };
             auto lstore_set = [&](int buf, auto S) {
                 constexpr int st = decltype(S)::value;
@@ -282,11 +304,11 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
 #pragma unroll
                 for (int q = 0; q < PA; ++q)
                     *reinterpret_cast<f32x4 *>(&As[(lrow + q * RPP) * LDK + lch * 4]) =
-                        EPI == EPI_GAUSS ? ra_[st][q] - rc_[st] : ra_[st][q];
+                        GAUSS ? ra_[st][q] - rc_[st] : ra_[st][q];
 #pragma unroll
                 for (int q = 0; q < PB; ++q)
                     *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) =
-                        EPI == EPI_GAUSS ? rb_[st][q] - rc_[st] : rb_[st][q];
+                        GAUSS ? rb_[st][q] - rc_[st] : rb_[st][q];
             };
             f32x4 a0[TM], b0[TN], a1[TM], b1[TN];
             auto fetch = [&](f32x4(&a)[TM], f32x4(&b)[TN], int buf, int kc) {
@@ -350,7 +372,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                 fetch(a0, b0, cur ^ 1, 0);
                 mma(a1, b1);
 #pragma unroll
-                for (int g = 0; g < PA + PB + (EPI == EPI_GAUSS ? 1 : 0); ++g) {
+                for (int g = 0; g < PA + PB + (GAUSS ? 1 : 0); ++g) {
                     __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
                     __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0);
                 }
@@ -409,24 +431,90 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
     // ---- epilogue: accumulator register v of lane l is C[8*(v/4) + 4*(l/32) + v%4][l%32]
     const int col_in = lane & 31;
     const int row_in = (lane >> 5) * 4;
-    if (EPI == EPI_GAUSS) __syncthreads();      // the norms in LDS (no barrier lies behind when K = 0)
+    if (GAUSS) __syncthreads();      // the norms in LDS (no barrier lies behind when K = 0)
     auto finish = [&](float accv, float nav, float nbv) __attribute__((always_inline)) -> float {
-        if (EPI != EPI_GAUSS) return accv;
+        if (!GAUSS) return accv;
         const float dist = fmaxf(nav + nbv - 2.0f * accv, 0.0f);
         return __builtin_amdgcn_exp2f(p.scale * dist);
     };
-    if (m0 + BM <= p.M && n0 + BN <= p.N) {
+    if constexpr (EPI == EPI_GAUSS_DOT) {
+        // Scores of the tile's rows against nv weight vectors, straight from the accumulators (prediction, Section 4
+        // "Algorithm Overview": K(x, L) times the folded weights; the kernel block never leaves the registers).
+        //   1. z in place of the accumulators (rows past M are never written out, columns past N meet zero weights);
+        //   2. per vector: a lane's 32 row slots times its TN columns, then a reduce-scatter over the 32 lanes that
+        //      hold the same rows (after the five halving steps lane l holds the total of slot l), then one LDS add
+        //      per lane into the tile's scores (the WGN wavefronts side by side add into the same entries: with at
+        //      most two of them the sum does not depend on who comes first);
+        //   3. the tile's BM x nv scores go to P.
+        constexpr int NSL = TM * 16;                      // row slots per lane: 32, or 16 for a wavefront of 32 rows
+        static_assert(WGN <= 2 && (NSL == 32 || NSL == 16), "two wavefronts across at most; 16 or 32 row slots per lane");
+        float *ft = lds;                                   // BM x GEMM_DOT_MAX, over the operand stages (all done with)
+        for (int e = tid; e < BM * GEMM_DOT_MAX; e += NT) ft[e] = 0.0f;
+        float nbv[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) nbv[j] = nbs[wn * WN + j * 32 + col_in];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float nav = nas[wm * WM + i * 32 + 8 * (v >> 2) + row_in + (v & 3)];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j][v] = finish(acc[i][j][v], nav, nbv[j]);
+            }
+        __syncthreads();                                   // ft is zero everywhere
+        for (int q = 0; q < p.nv; ++q) {
+            float vq[TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) vq[j] = vs[q * BN + wn * WN + j * 32 + col_in];
+            float t[NSL];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) sum += acc[i][j][v] * vq[j];
+                    t[i * 16 + v] = sum;
+                }
+            if constexpr (NSL == 16) {                     // 16 slots over 32 lanes: lanes l and l ^ 16 first join
+#pragma unroll
+                for (int sl = 0; sl < 16; ++sl) t[sl] += __shfl_xor(t[sl], 16, 64);
+            }
+#pragma unroll
+            for (int k = NSL / 2; k >= 1; k >>= 1) {
+                const bool up = (lane & k) != 0;           // this lane keeps the upper half of the slots
+#pragma unroll
+                for (int sl = 0; sl < k; ++sl) {
+                    // both slots are read into values first: a choice between two array elements would be turned
+                    // into a per-lane index, and an array indexed per lane cannot live in registers
+                    const float lo = t[sl], hi = t[sl + k];
+                    const float keep = up ? hi : lo;
+                    const float send = up ? lo : hi;
+                    t[sl] = keep + __shfl_xor(send, k, 64);
+                }
+            }
+            // lane l now holds slot l % NSL = 16 i + v of its half-wavefront's rows (with 16 slots, twice over)
+            const int sl = lane & (NSL - 1);
+            const int rl = wm * WM + (sl >> 4) * 32 + 8 * ((sl & 15) >> 2) + row_in + (sl & 3);
+            if (NSL == 32 || (lane & 16) == 0) atomicAdd(&ft[rl * GEMM_DOT_MAX + q], t[0]);
+        }
+        __syncthreads();
+        for (int e = tid; e < BM * p.nv; e += NT) {
+            const int rl = e / p.nv, q = e - rl * p.nv;
+            if (m0 + rl < p.M) p.P[(int64_t(tn) * p.M + m0 + rl) * p.nv + q] = ft[rl * GEMM_DOT_MAX + q];
+        }
+    } else if (m0 + BM <= p.M && n0 + BN <= p.N) {
         // interior tile: no bounds to check, one row pointer per group of four rows
         float nbv[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) nbv[j] = EPI == EPI_GAUSS ? nbs[wn * WN + j * 32 + col_in] : 0.0f;
+        for (int j = 0; j < TN; ++j) nbv[j] = GAUSS ? nbs[wn * WN + j * 32 + col_in] : 0.0f;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int rl = wm * WM + i * 32 + 8 * g + row_in;      // row within the tile, a multiple of 4
                 f32x4 nav = {0.f, 0.f, 0.f, 0.f};
-                if (EPI == EPI_GAUSS) nav = *reinterpret_cast<const f32x4 *>(&nas[rl]);
+                if (GAUSS) nav = *reinterpret_cast<const f32x4 *>(&nas[rl]);
                 float *crow = p.C + int64_t(m0 + rl) * p.ldc + (n0 + wn * WN + col_in);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -448,14 +536,14 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
             const int cc = n0 + cl;
             if (cc >= p.n_store) continue;
             const bool live = cc < p.N;
-            const float nbv = EPI == EPI_GAUSS ? nbs[cl] : 0.0f;
+            const float nbv = GAUSS ? nbs[cl] : 0.0f;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int rl = wm * WM + i * 32 + 8 * (v >> 2) + row_in + (v & 3);
                     if (m0 + rl >= p.M) continue;
-                    const float out = finish(acc[i][j][v], EPI == EPI_GAUSS ? nas[rl] : 0.0f, nbv);
+                    const float out = finish(acc[i][j][v], GAUSS ? nas[rl] : 0.0f, nbv);
                     if (EPI == EPI_STORE) __builtin_nontemporal_store(live ? out : 0.0f, &p.C[int64_t(m0 + rl) * p.ldc + cc]);
                     else p.C[int64_t(m0 + rl) * p.ldc + cc] = live ? out : 0.0f;
                 }

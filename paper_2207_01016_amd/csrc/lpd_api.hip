@@ -94,10 +94,11 @@ std::atomic<int> g_tile_option{TILE_AUTO};   // LPD_OPT_GEMM_TILE
 std::atomic<int> g_csr_route{0};              // LPD_OPT_CSR_ROUTE: 0 by density, 1 dense panel, 2 gather
 std::atomic<int> g_sweep_grid{0};             // LPD_OPT_SWEEP_GRID: 0 = by row length, else the number of workgroups of a full sweep
 std::atomic<int> g_small_path{1};             // LPD_OPT_SMALL_PATH: 1 = one-launch factor for B <= 256, 0 = panel schedule
+std::atomic<int> g_fused_scores{1};           // LPD_OPT_FUSED_SCORES: 1 = prediction with up to 16 weight vectors contracts the kernel block in its launch
 
 // Estimated duration of a launch with BM x BN tiles, in units of (CUs x tile elements): a CU holds `per_cu`
 // workgroups (registers and LDS: 5 of the 64x128 tile, 3 of the 128x128 tile, 2 of the 256x128 tile of the plain
-// product, else 1), a launch runs in rounds of 256 x per_cu tiles, and a last round that leaves CUs with fewer
+// product, else 1; fewer where the write-out holds the scores as well), a launch runs in rounds of 256 x per_cu tiles, and a last round that leaves CUs with fewer
 // workgroups than they can hold goes faster, though not in proportion (a lone 4-wavefront workgroup cannot keep a
 // CU's MFMA pipes full).  `speed` is the measured main-loop rate relative to the 128x128 tile (larger tiles
 // move less through LDS and L2 per FLOP).
@@ -120,8 +121,11 @@ double launch_cost(const GemmArgs &a, int bm, int bn, int per_cu, double speed)
 // CU holds five, overlap the two better than one large workgroup that does one after the other.
 double tile_speed(int tile, int epi, int K)
 {
-    if (epi != EPI_GAUSS)       // (the small tile re-reads its operands most: worse where W streams from HBM, K beyond 4,096)
+    if (epi == EPI_STORE)       // (the small tile re-reads its operands most: worse where W streams from HBM, K beyond 4,096)
         return tile == TILE_256x256 ? 1.04 : tile == TILE_256x128 ? 1.03 : tile == TILE_64x128 ? (K > 4096 ? 0.88 : 0.95) : 1.0;
+    // (contracted at once with weight vectors: the write-out's cross-lane sums cost the same per tile whatever its
+    // size, so the large tile keeps its edge at any K)
+    if (epi == EPI_GAUSS_DOT) return tile == TILE_256x256 ? 1.07 : tile == TILE_64x128 ? 0.9 : 1.0;
     switch (tile) {
     case TILE_256x256: return K >= 512 ? 1.07 : K >= 256 ? 1.04 : K >= 128 ? 1.02 : K >= 64 ? 0.95 : 0.85;
     case TILE_256x128: return K >= 128 ? 1.03 : 0.95;
@@ -137,22 +141,22 @@ int tile_choice(const GemmArgs &a, int epi)
     // What decides, besides the tiles' own rates, is how evenly the tile count fills the chip.  The smallest
     // tile is for launches of few rows (a ragged last panel, a small batch to predict), which the others would
     // spread over a fraction of the CUs, and for kernel blocks over very few features.
-    const bool gauss = epi == EPI_GAUSS;
+    const bool gauss = epi != EPI_STORE;
     const double cost[5] = {0.0,
-                            launch_cost(a, 128, 128, 3, tile_speed(TILE_128x128, epi, a.K)),
+                            launch_cost(a, 128, 128, epi == EPI_GAUSS_DOT ? 2 : 3, tile_speed(TILE_128x128, epi, a.K)),
                             launch_cost(a, 256, 128, gauss ? 1 : 2, tile_speed(TILE_256x128, epi, a.K)),
                             launch_cost(a, 256, 256, 1, tile_speed(TILE_256x256, epi, a.K)),
-                            launch_cost(a, 64, 128, gauss ? 5 : 4, tile_speed(TILE_64x128, epi, a.K))};
+                            launch_cost(a, 64, 128, epi == EPI_GAUSS_DOT ? 3 : gauss ? 5 : 4, tile_speed(TILE_64x128, epi, a.K))};
     int best = TILE_128x128;
     for (int t : {TILE_256x128, TILE_256x256, TILE_64x128})
-        if (cost[t] < cost[best]) best = t;
+        if (cost[t] < cost[best] && !(t == TILE_256x128 && epi == EPI_GAUSS_DOT)) best = t;    // (not built for that write-out)
     return best;
 }
 
 template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI, int PIPE>
 hipError_t launch_one(GemmArgs a, hipStream_t s)
 {
-    constexpr size_t lds = gemm_lds_bytes<BM, BN>();
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, EPI>();
     auto kern = gemm_nt_kernel<BM, BN, WGM, WGN, ALIGNED, EPI, PIPE>;
     // once per instantiation (initialisation of a function-local static is thread-safe): these kernels use
     // more dynamic LDS than the default limit
@@ -176,6 +180,15 @@ hipError_t launch_tile(const GemmArgs &a, bool aligned, int epi, hipStream_t s)
     const int opt = g_pipe_option.load(std::memory_order_relaxed);
     const bool pipe = opt != 0 && aligned && int64_t(BM) * a.lda * 4 < (int64_t(1) << 31) &&
                       int64_t(BN) * a.ldb * 4 < (int64_t(1) << 31);
+    if (epi == EPI_GAUSS_DOT) {
+        if constexpr (!(BM == 256 && BN == 128)) {
+            if (pipe) return launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS_DOT, 1>(a, s);
+            return aligned ? launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS_DOT, 0>(a, s)
+                           : launch_one<BM, BN, WGM, WGN, false, EPI_GAUSS_DOT, 0>(a, s);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     if (epi == EPI_GAUSS) {
         // (two staged tiles cost this variant, which also carries the origin, wavefronts per SIMD or spills)
         if (pipe) return launch_one<BM, BN, WGM, WGN, true, EPI_GAUSS, 1>(a, s);
@@ -192,15 +205,41 @@ hipError_t launch_tile(const GemmArgs &a, bool aligned, int epi, hipStream_t s)
                    : launch_one<BM, BN, WGM, WGN, false, EPI_STORE, 0>(a, s);
 }
 
-hipError_t launch_gemm(const GemmArgs &a, int epi, hipStream_t s)
+// tiles_n (optional): receives the number of tile columns of the launch (the layout of GemmArgs::P depends on it)
+hipError_t launch_gemm(const GemmArgs &a, int epi, hipStream_t s, int *tiles_n = nullptr)
 {
     const bool aligned = aligned16(a.A) && aligned16(a.B) && a.lda % 4 == 0 && a.ldb % 4 == 0 && a.K % 4 == 0;
-    switch (tile_choice(a, epi)) {
+    int tile = tile_choice(a, epi);
+    if (tile == TILE_256x128 && epi == EPI_GAUSS_DOT) tile = TILE_128x128;     // a forced tile this write-out is not built for
+    if (tiles_n) *tiles_n = (a.n_store + (tile == TILE_256x256 ? 256 : 128) - 1) / (tile == TILE_256x256 ? 256 : 128);
+    switch (tile) {
     case TILE_256x256: return launch_tile<256, 256, 4, 2>(a, aligned, epi, s);
     case TILE_256x128: return launch_tile<256, 128, 4, 2>(a, aligned, epi, s);
     case TILE_64x128: return launch_tile<64, 128, 2, 2>(a, aligned, epi, s);
     default: return launch_tile<128, 128, 2, 2>(a, aligned, epi, s);
     }
+}
+
+// F[row, q] = sum over the tile columns of P[t][row][q], in tile order
+__global__ __launch_bounds__(256) void dot_reduce_kernel(const float *__restrict__ P, int tiles_n, int64_t rows, int nv,
+                                                         float *__restrict__ F, int64_t ldf)
+{
+    const int64_t total = rows * nv;
+    for (int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x; e < total; e += int64_t(gridDim.x) * 256) {
+        float s = 0.0f;
+        for (int t = 0; t < tiles_n; ++t) s += P[int64_t(t) * total + e];
+        const int64_t row = e / nv;
+        F[row * ldf + (e - row * nv)] = s;
+    }
+}
+
+hipError_t launch_dot_reduce(const float *P, int tiles_n, int64_t rows, int nv, float *F, int64_t ldf, hipStream_t s)
+{
+    const int64_t total = rows * nv;
+    if (total <= 0) return hipSuccess;
+    const unsigned grid = unsigned(std::min<int64_t>((total + 255) / 256, 4096));
+    hipLaunchKernelGGL(dot_reduce_kernel, dim3(grid), dim3(256), 0, s, P, tiles_n, rows, nv, F, ldf);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------- row kernels
@@ -406,6 +445,7 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
 
     EventLog log;
     log.on = prof != nullptr;
+    bool fused_scores = false;
 
     // Few landmarks: the whole of step 1d in one launch (fused_small.hip.h); the workspace is not touched.
     if (out_cols == B && B <= SM_MAXB && d <= SM_MAXD && g_small_path.load(std::memory_order_relaxed) != 0) {
@@ -432,6 +472,15 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
     LPD_HIP(launch_centred_norms(X, n, d, ldx, L, B, ldl, cen, nx, nl, s));
     LPD_HIP(log.end(s));
 
+    // (the shares of the scores, one per 128 landmarks at most, must fit a panel row's place in the workspace)
+    fused_scores = out_cols != B && r > 0 && r <= GEMM_DOT_MAX && g_fused_scores.load(std::memory_order_relaxed) != 0 &&
+                   ((B + 127) / 128) * r <= c.ldz;
+    if (fused_scores && panel < n) {
+        // no panel of the kernel block is stored, so a launch can take as many rows as their shares of the scores
+        // fit the workspace: fewer launches, fewer ragged ends
+        const int64_t fit = int64_t((workspace_bytes - c.off_z) / 4) / (((B + 127) / 128) * r);
+        panel = std::min<int64_t>(n, std::max<int64_t>(panel, fit / 256 * 256));
+    }
     for (int64_t p0 = 0; p0 < n; p0 += panel) {
         const int64_t rows = std::min<int64_t>(panel, n - p0);
         GemmArgs k1{};
@@ -441,6 +490,21 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
         k1.M = int(rows); k1.N = int(B); k1.K = int(d); k1.n_store = int(B);
         k1.na = nx + p0; k1.nb = nl; k1.cen = cen;
         k1.scale = -gamma * 1.44269504088896340736f;
+        if (fused_scores) {
+            // prediction with few weight vectors: the kernel block is contracted with them in the write-out of
+            // the same launch and never written; the panel's place in the workspace takes the per-tile-column
+            // shares of the scores, which one small pass adds up
+            k1.C = nullptr;
+            k1.V = W; k1.ldv = ldw; k1.nv = int(r); k1.P = Z;
+            int tiles_n = 0;
+            LPD_HIP(log.begin(1, s));
+            LPD_HIP(launch_gemm(k1, EPI_GAUSS_DOT, s, &tiles_n));
+            LPD_HIP(log.end(s));
+            LPD_HIP(log.begin(2, s));
+            LPD_HIP(launch_dot_reduce(Z, tiles_n, rows, int(r), G + p0 * ldg, ldg, s));
+            LPD_HIP(log.end(s));
+            continue;
+        }
         LPD_HIP(log.begin(1, s));
         LPD_HIP(launch_gemm(k1, EPI_GAUSS, s));
         LPD_HIP(log.end(s));
@@ -637,6 +701,10 @@ int lpd_set_option(int option, int64_t value)
     }
     if (option == LPD_OPT_WHITEN_DC && (value == 0 || value == 1)) {
         lpd_host::set_divide_and_conquer(int(value));
+        return LPD_OK;
+    }
+    if (option == LPD_OPT_FUSED_SCORES && (value == 0 || value == 1)) {
+        g_fused_scores.store(int(value), std::memory_order_relaxed);
         return LPD_OK;
     }
     if (option == LPD_OPT_SMALL_PATH && (value == 0 || value == 1)) {

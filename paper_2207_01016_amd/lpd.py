@@ -140,6 +140,7 @@ LPD_OPT_SMALL_PATH = 4
 LPD_OPT_WHITEN_DC = 5
 LPD_OPT_WHITEN_UPPER = 6
 LPD_OPT_SWEEP_GRID = 7
+LPD_OPT_FUSED_SCORES = 8
 CSR_ROUTES = {"auto": 0, "dense": 1, "gather": 2}
 GEMM_PIPELINE_DEFAULT = 2
 GEMM_TILES = {"auto": 0, "128x128": 1, "256x128": 2, "256x256": 3, "64x128": 4}

@@ -72,6 +72,49 @@ def test_predict_matches_oracle(lpd, oracle, dev, name, n, B, n_test, c):
     assert relfro(Fh, ref) <= 1e-4
 
 
+@pytest.mark.parametrize("tile", ["auto", "128x128", "256x256", "64x128", "256x128"])
+@pytest.mark.parametrize("n,d,B,c,aligned", [
+    (777, 20, 130, 1, True),        # one and a bit tile columns, ragged rows
+    (1000, 64, 333, 5, True),       # B and n no multiple of anything
+    (513, 19, 257, 7, False),       # d % 4 != 0: element-wise loader, plain schedule
+    (300, 48, 64, 32, True),        # the most weight vectors the write-out takes
+    (2100, 16, 1040, 17, True),     # several tile rows and columns of every tile
+    (260, 0, 96, 3, True),          # no features: z = 1, the scores are the row sums of V
+    (50, 8, 3, 2, True),            # three landmarks
+    (40, 8, 9, 9, True),            # as many weight vectors as landmarks (the most the entry point accepts)
+])
+def test_scores_contracted_in_the_kernel_block_launch_match_the_panel_route(lpd, oracle, dev, n, d, B, c, aligned, tile):
+    """Prediction with few weight vectors multiplies the kernel block by them in the write-out of its own launch
+    (Z never stored); the route that stores a panel of Z and sweeps it must give the same scores, and both the
+    oracle's."""
+    g = torch.Generator().manual_seed(n + 7 * B + c)
+    ldx = d + (0 if aligned else 1)
+    Xf = torch.randn((n, max(ldx, 1)), generator=g)
+    Lf = torch.randn((B, max(ldx, 1)), generator=g)
+    X, L = Xf.to(dev)[:, :d], Lf.to(dev)[:, :d]
+    V = (torch.randn((c, B), generator=g) / B ** 0.5).to(dev)
+    gamma = 0.5 / max(d, 1)
+    _, mn = lpd.lpd_nystrom_factor_workspace(n, d, B)
+    ws = lpd.alloc_workspace(n, d, B, dev, mn * 2)              # a few panels
+    out = []
+    lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, lpd.GEMM_TILES[tile])
+    try:
+        for fused in (1, 0):
+            lpd.lpd_set_option(lpd.LPD_OPT_FUSED_SCORES, fused)
+            F = torch.full((n, c), float("nan"), dtype=torch.float32, device=dev)
+            lpd.lpd_predict(X, L, gamma, V, F, ws)
+            torch.cuda.synchronize()
+            out.append(F.cpu().numpy())
+    finally:
+        lpd.lpd_set_option(lpd.LPD_OPT_FUSED_SCORES, 1)
+        lpd.lpd_set_option(lpd.LPD_OPT_GEMM_TILE, 0)
+    Z = oracle.kernel_block(np.ascontiguousarray(Xf[:, :d].numpy()), np.ascontiguousarray(Lf[:, :d].numpy()), gamma)
+    ref = Z @ V.cpu().numpy().astype(np.float64).T
+    assert np.all(np.isfinite(out[0])) and np.all(np.isfinite(out[1]))
+    assert relfro(out[0], ref) <= 1e-5 and relfro(out[1], ref) <= 1e-5
+    assert relfro(out[0], out[1]) <= 2e-6
+
+
 def test_predict_on_training_rows_equals_margins_of_the_factor(lpd, dev):
     from paper_2207_01016_amd import workloads
     wl = workloads.WORKLOADS["small"].with_shape(n=3000, B=256)

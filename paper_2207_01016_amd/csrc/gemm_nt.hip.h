@@ -85,9 +85,10 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int CPR = BK / 4;        // 16-byte chunks per tile row
     constexpr int RPP = NT / CPR;      // tile rows filled per pass of the workgroup
-    constexpr int PA = BM / RPP, PB = BN / RPP;
+    constexpr int PA = BM / RPP, PB = BN >= RPP ? BN / RPP : 1;
+    constexpr bool BPART = BN < RPP;   // a narrow tile: only the first BN loader rows carry rows of B (whole wavefronts: 16 rows each)
     constexpr int STAGE = (BM + BN) * LDK;
-    static_assert(BM % RPP == 0 && BN % RPP == 0, "tile rows must be a multiple of the loader pass");
+    static_assert(BM % RPP == 0 && (BN % RPP == 0 || (BN < RPP && BN % 16 == 0)), "tile rows must be a multiple of the loader pass");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 MFMA tiles");
 
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -185,7 +186,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
             *reinterpret_cast<f32x4 *>(&As[(lrow + q * RPP) * LDK + lch * 4]) = GAUSS ? ra[q] - rc : ra[q];
 #pragma unroll
         for (int q = 0; q < PB; ++q)
-            *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) = GAUSS ? rb[q] - rc : rb[q];
+            if (!BPART || lrow < BN)
+                *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) = GAUSS ? rb[q] - rc : rb[q];
     };
 
     // The squared norms the epilogue needs go to LDS now, so that after the main loop nothing waits for
@@ -307,8 +309,9 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                         GAUSS ? ra_[st][q] - rc_[st] : ra_[st][q];
 #pragma unroll
                 for (int q = 0; q < PB; ++q)
-                    *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) =
-                        GAUSS ? rb_[st][q] - rc_[st] : rb_[st][q];
+                    if (!BPART || lrow < BN)
+                        *reinterpret_cast<f32x4 *>(&Bs[(lrow + q * RPP) * LDK + lch * 4]) =
+                            GAUSS ? rb_[st][q] - rc_[st] : rb_[st][q];
             };
             f32x4 a0[TM], b0[TN], a1[TM], b1[TN];
             auto fetch = [&](f32x4(&a)[TM], f32x4(&b)[TN], int buf, int kc) {

@@ -205,10 +205,28 @@ hipError_t launch_tile(const GemmArgs &a, bool aligned, int epi, hipStream_t s)
                    : launch_one<BM, BN, WGM, WGN, false, EPI_STORE, 0>(a, s);
 }
 
+// The narrow tiles (256 x 32 and 256 x 64, four wavefronts down the rows), plain product only.
+template <int BN>
+hipError_t launch_narrow(const GemmArgs &a, bool aligned, hipStream_t s)
+{
+    const bool pipe = g_pipe_option.load(std::memory_order_relaxed) != 0 && aligned &&
+                      int64_t(256) * a.lda * 4 < (int64_t(1) << 31) && int64_t(BN) * a.ldb * 4 < (int64_t(1) << 31);
+    if (pipe) return launch_one<256, BN, 4, 1, true, EPI_STORE, 1>(a, s);
+    return aligned ? launch_one<256, BN, 4, 1, true, EPI_STORE, 0>(a, s)
+                   : launch_one<256, BN, 4, 1, false, EPI_STORE, 0>(a, s);
+}
+
 // tiles_n (optional): receives the number of tile columns of the launch (the layout of GemmArgs::P depends on it)
 hipError_t launch_gemm(const GemmArgs &a, int epi, hipStream_t s, int *tiles_n = nullptr)
 {
     const bool aligned = aligned16(a.A) && aligned16(a.B) && a.lda % 4 == 0 && a.ldb % 4 == 0 && a.K % 4 == 0;
+    // a plain product with at most 64 columns (a few dozen weight vectors against the rows of G, which it reads
+    // once): a narrow tile does a quarter or half of the MFMA work a 128-wide tile would pad it to, and the pass
+    // is bound by reading G (33 GB against 9 to 32 vectors: 6.9 ms instead of 15.9)
+    if (epi == EPI_STORE && a.n_store <= 64 && g_tile_option.load(std::memory_order_relaxed) == TILE_AUTO) {
+        if (tiles_n) *tiles_n = 1;
+        return a.n_store <= 32 ? launch_narrow<32>(a, aligned, s) : launch_narrow<64>(a, aligned, s);
+    }
     int tile = tile_choice(a, epi);
     if (tile == TILE_256x128 && epi == EPI_GAUSS_DOT) tile = TILE_128x128;     // a forced tile this write-out is not built for
     if (tiles_n) *tiles_n = (a.n_store + (tile == TILE_256x256 ? 256 : 128) - 1) / (tile == TILE_256x256 ? 256 : 128);

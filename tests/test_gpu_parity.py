@@ -450,7 +450,11 @@ def test_margins_on_factor_output_tiny(lpd, wls, oracle, dev):
 
 
 @pytest.mark.parametrize("n,r,ld,k", [(700, 300, 300, 1), (1000, 1024, 1024, 3), (513, 1001, 1004, 8),
-                                       (301, 517, 517, 5), (2000, 640, 640, 9), (900, 260, 264, 150)])
+                                       (301, 517, 517, 5), (2000, 640, 640, 9), (900, 260, 264, 150),
+                                       # the narrow MFMA tiles (up to 32 and up to 64 vectors), aligned and not,
+                                       # rows not a multiple of the tile, and the first count past them
+                                       (1500, 512, 512, 16), (777, 333, 333, 32), (1030, 400, 400, 33),
+                                       (600, 1024, 1028, 64), (515, 256, 256, 65)])
 def test_margins_multi_match_oracle(lpd, oracle, dev, n, r, ld, k):
     g = torch.Generator().manual_seed(n + r + k)
     Gfull = torch.randn((n, ld), generator=g).to(dev)

@@ -211,6 +211,7 @@ hipError_t launch_narrow(const GemmArgs &a, bool aligned, hipStream_t s)
 {
     const bool pipe = g_pipe_option.load(std::memory_order_relaxed) != 0 && aligned &&
                       int64_t(256) * a.lda * 4 < (int64_t(1) << 31) && int64_t(BN) * a.ldb * 4 < (int64_t(1) << 31);
+    if (pipe && g_pipe_option.load(std::memory_order_relaxed) == 2) return launch_one<256, BN, 4, 1, true, EPI_STORE, 2>(a, s);
     if (pipe) return launch_one<256, BN, 4, 1, true, EPI_STORE, 1>(a, s);
     return aligned ? launch_one<256, BN, 4, 1, true, EPI_STORE, 0>(a, s)
                    : launch_one<256, BN, 4, 1, false, EPI_STORE, 0>(a, s);

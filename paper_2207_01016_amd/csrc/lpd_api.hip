@@ -197,7 +197,11 @@ hipError_t launch_tile(const GemmArgs &a, bool aligned, int epi, hipStream_t s)
     }
     // two staged tiles: +1.5 % on the 256x256 tile at any K, more on the 128x128 tile at K about 1,000; the
     // 256x128 tile would lose a wavefront per SIMD to the extra registers
-    if constexpr (!(BM == 256 && BN == 128)) {
+    if constexpr (BM == 256 && BN == 256) {
+        // the plain product's large tile runs as four wavefronts of 128 x 128 (256 accumulator registers each, one
+        // wavefront per SIMD): half the LDS fragment reads per MFMA of the eight-wavefront layout, +1 % at K >= 8,192
+        if (pipe && opt == 2) return launch_one<256, 256, 2, 2, true, EPI_STORE, 2>(a, s);
+    } else if constexpr (!(BM == 256 && BN == 128)) {
         if (pipe && opt == 2) return launch_one<BM, BN, WGM, WGN, true, EPI_STORE, 2>(a, s);
     }
     if (pipe) return launch_one<BM, BN, WGM, WGN, true, EPI_STORE, 1>(a, s);

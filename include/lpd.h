@@ -95,7 +95,8 @@ const char *lpd_strerror(int status);
  *                      0 = choose by shape, 1 = 128x128, 2 = 256x128, 3 = 256x256, 4 = 64x128
  *   LPD_OPT_GEMM_PIPELINE  main-loop schedule of the MFMA products: 0 = plain load/compute/store,
  *                      1 = software-pipelined across the barrier, 2 (default) = as 1, and the
- *                      whitening product keeps two k-tiles in flight from memory instead of one
+ *                      whitening product keeps two k-tiles in flight from memory instead of one,
+ *                      products with at most 64 columns four, requested two at a time
  *                      (all three visit k in the same order: identical results)
  *   LPD_OPT_CSR_ROUTE  route of the compressed-row entry points: 0 (default) = by density,
  *                      1 = dense panels, 2 = gather; set it before the workspace query

@@ -141,7 +141,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
 
     // rc: the four centre values of this thread's k columns (all its rows share them).  They are loaded with
     // the tile and subtracted on the way into LDS, so that nothing waits for a global load before it must.
-    constexpr int NSET = PIPE == 2 ? 2 : 1;        // register sets of staged tiles (see the pipelined schedule)
+    constexpr int NSET = PIPE == 2 ? 2 : PIPE == 4 ? 4 : 1;   // register sets of staged tiles (see the pipelined schedule)
     f32x4 ra_[NSET][PA], rb_[NSET][PB], rc_[NSET];
     f32x4(&ra)[PA] = ra_[0];
     f32x4(&rb)[PB] = rb_[0];
@@ -271,12 +271,13 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
         // Buffer (kt+1)&1 is overwritten in phase A of iteration kt; its previous tile kt-1 was last
         // read before the barrier of iteration kt-1, and each wavefront drains its LDS reads before a
         // barrier.  A partial last tile (K % 16 != 0) is handled after the loop by the plain schedule.
-        static_assert(PIPE == 1 || PIPE == 2, "schedules: 0 plain, 1 pipelined, 2 pipelined with two staged tiles");
+        static_assert(PIPE == 1 || PIPE == 2 || PIPE == 4,
+                      "schedules: 0 plain, 1 pipelined, 2 and 4 pipelined with that many staged tiles");
         static_assert(BK == 16, "the pipelined schedule assumes two chunks per tile");
         static_assert(ALIGNED, "the pipelined schedule is for the 16-byte aligned fast path");
         constexpr int MEMOPS = TM + TN + PA + PB + (GAUSS ? 1 : 0);   // + the load of the centre values
         constexpr int MPG = (4 * TM * TN) / MEMOPS > 0 ? (4 * TM * TN) / MEMOPS : 1;
-        constexpr bool WRITES_FIRST = NSET == 2;
+        constexpr bool WRITES_FIRST = NSET >= 2;
         const int nfull = p.K / BK;
 
         if (nfull > 0) {
@@ -298,6 +299,28 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
 #pragma unroll
                 for (int q = 0; q < PB; ++q) rb_[st][q] = *reinterpret_cast<const f32x4 *>(pb + ob[q]);
                 if (GAUSS) rc_[st] = *reinterpret_cast<const f32x4 *>(p.cen + tile * BK + lch * 4);
+            };
+            // Two consecutive k-tiles at once, into sets S0 and S1: a row's 64 bytes of an even tile and of the odd
+            // tile behind it are the two halves of one 128-byte line (rows aligned to that), and asking for both
+            // in the same breath is what keeps the line from being fetched twice (see the four-set schedule).
+            auto gload_pair = [&](int tile0, int tile1, auto S0, auto S1) {
+                constexpr int s0 = decltype(S0)::value, s1 = decltype(S1)::value;
+                const char *pa0 = baseA + size_t(tile0) * (BK * 4), *pa1 = baseA + size_t(tile1) * (BK * 4);
+                const char *pb0 = baseB + size_t(tile0) * (BK * 4), *pb1 = baseB + size_t(tile1) * (BK * 4);
+#pragma unroll
+                for (int q = 0; q < PA; ++q) {
+                    ra_[s0][q] = *reinterpret_cast<const f32x4 *>(pa0 + oa[q]);
+                    ra_[s1][q] = *reinterpret_cast<const f32x4 *>(pa1 + oa[q]);
+                }
+#pragma unroll
+                for (int q = 0; q < PB; ++q) {
+                    rb_[s0][q] = *reinterpret_cast<const f32x4 *>(pb0 + ob[q]);
+                    rb_[s1][q] = *reinterpret_cast<const f32x4 *>(pb1 + ob[q]);
+                }
+                if (GAUSS) {
+                    rc_[s0] = *reinterpret_cast<const f32x4 *>(p.cen + tile0 * BK + lch * 4);
+                    rc_[s1] = *reinterpret_cast<const f32x4 *>(p.cen + tile1 * BK + lch * 4);
+                }
             };
             auto lstore_set = [&](int buf, auto S) {
                 constexpr int st = decltype(S)::value;
@@ -336,7 +359,17 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
             // two sets a global load has a whole iteration and a half to arrive instead of half of one: what
             // streams from HBM rather than from L2 (W of many landmarks) then never holds up phase A.  (A third
             // set measured no faster on the 256x256 tile, whose registers it overflows.)
-            auto step = [&](int kt, auto S) {
+            // Four sets, for the narrow tiles (at most 64 columns against the rows of a matrix far larger than the
+            // caches, read once): more tiles in flight buy nothing by themselves, but a row's 64 bytes of an even
+            // and of the following odd k-tile are one 128-byte line, and with some 200,000 rows in flight on the
+            // chip the L2s lose the line between two separate visits (a third more bytes fetched than the matrix
+            // holds).  So the two are requested together, every other step.
+            // LD: k-tiles requested in this step.  1 with one or two sets; with four sets 2 and 0 in turn: an even step
+            // requests tiles kt+4 and kt+5 together, into the set the previous step emptied and the one this step
+            // empties.
+            auto step = [&](int kt, auto S, auto LD) {
+                constexpr int nld = decltype(LD)::value;
+                constexpr int st = decltype(S)::value;
                 const int cur = kt & 1;
                 // ---- phase A
                 // (program order matters too: the compiler keeps LDS reads and writes it cannot tell apart in it)
@@ -371,12 +404,15 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
                 // ---- phase B
-                gload_full(min(kt + 1 + NSET, nfull - 1), S);
+                if constexpr (nld == 1) gload_full(min(kt + 1 + NSET, nfull - 1), S);
+                if constexpr (nld == 2)
+                    gload_pair(min(kt + NSET, nfull - 1), min(kt + 1 + NSET, nfull - 1), SI<(st + NSET - 1) % NSET>{}, S);
                 fetch(a0, b0, cur ^ 1, 0);
                 mma(a1, b1);
+                constexpr int LOADGROUPS = nld == 0 ? 0 : PA + PB + (GAUSS ? 1 : 0);
 #pragma unroll
-                for (int g = 0; g < PA + PB + (GAUSS ? 1 : 0); ++g) {
-                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+                for (int g = 0; g < LOADGROUPS; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x020, nld, 0);   // one global load (a pair with four sets)
                     __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0);
                 }
 #pragma unroll
@@ -384,24 +420,36 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x008, MPG, 0);
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, 4 * TM * TN - MPG * MEMOPS, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4 * TM * TN - MPG * (TM + TN + LOADGROUPS), 0);
                 __builtin_amdgcn_sched_barrier(0);
             };
             // tile j of the contraction travels in register set j % NSET
+            using LD_EVEN = SI<NSET == 4 ? 2 : 1>;
+            using LD_ODD = SI<NSET == 4 ? 0 : 1>;
             gload_full(0, SI<0>{});
             lstore_set(0, SI<0>{});
             gload_full(min(1, nfull - 1), SI<1 % NSET>{});
             if constexpr (NSET > 1) gload_full(min(2, nfull - 1), SI<2 % NSET>{});
+            if constexpr (NSET > 2) gload_full(min(3, nfull - 1), SI<3 % NSET>{});
             __syncthreads();
             fetch(a0, b0, 0, 0);
 
             int kt = 0;
             for (; kt + NSET <= nfull; kt += NSET) {
-                step(kt, SI<1 % NSET>{});
-                if constexpr (NSET > 1) step(kt + 1, SI<2 % NSET>{});
+                step(kt, SI<1 % NSET>{}, LD_EVEN{});
+                if constexpr (NSET > 1) step(kt + 1, SI<2 % NSET>{}, LD_ODD{});
+                if constexpr (NSET > 2) step(kt + 2, SI<3 % NSET>{}, LD_EVEN{});
+                if constexpr (NSET > 3) step(kt + 3, SI<4 % NSET>{}, LD_ODD{});
             }
+            // (kt is a multiple of NSET here: tile kt+1+i sits in set (i+1) % NSET)
             if constexpr (NSET > 1) {
-                if (kt < nfull) step(kt++, SI<1 % NSET>{});
+                if (kt < nfull) step(kt++, SI<1 % NSET>{}, LD_EVEN{});
+            }
+            if constexpr (NSET > 2) {
+                if (kt < nfull) step(kt++, SI<2 % NSET>{}, LD_ODD{});
+            }
+            if constexpr (NSET > 3) {
+                if (kt < nfull) step(kt++, SI<3 % NSET>{}, LD_EVEN{});
             }
             __syncthreads();
         }

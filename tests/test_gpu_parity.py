@@ -286,6 +286,34 @@ def test_main_loop_schedules_agree_bit_for_bit(lpd, oracle, dev, n, d, B, tile):
     assert np.array_equal(out[0], out[1]) and np.array_equal(out[0], out[2])
 
 
+@pytest.mark.parametrize("k", [9, 32, 33, 64])
+@pytest.mark.parametrize("n,r", [
+    (300, 16), (300, 32), (257, 48), (300, 64),     # 1 to 4 k-tiles: fewer than the staged tiles of the schedule
+    (513, 80), (300, 96), (300, 112), (300, 128),   # every remainder of the loop that is unrolled four times
+    (700, 144), (1000, 1040),                       # several workgroups, a ragged last one
+    (300, 100),                                     # a partial last k-tile
+])
+def test_narrow_tile_schedules_agree_bit_for_bit(lpd, oracle, dev, n, r, k):
+    """9 to 64 weight vectors take the narrow tiles, whose default schedule keeps four k-tiles in flight and
+    requests them in pairs; the plain and the one-tile schedules visit k in the same order."""
+    g = torch.Generator().manual_seed(77 + n + r + k)
+    G = torch.randn((n, r), generator=g).to(dev)
+    Ws = torch.randn((k, r), generator=g).to(dev)
+    out = []
+    try:
+        for schedule in (0, 1, 2):
+            lpd.lpd_set_option(lpd.LPD_OPT_GEMM_PIPELINE, schedule)
+            M = torch.full((n, k), float("nan"), device=dev)
+            lpd.lpd_margins_multi(G, Ws, M)
+            torch.cuda.synchronize()
+            out.append(M.cpu().numpy())
+    finally:
+        lpd.lpd_set_option(lpd.LPD_OPT_GEMM_PIPELINE, lpd.GEMM_PIPELINE_DEFAULT)
+    ref = np.stack([oracle.margins(G.cpu().numpy(), Ws[q].cpu().numpy(), r) for q in range(k)], axis=1)
+    assert relfro(out[0], ref) <= 1e-5
+    assert np.array_equal(out[0], out[1]) and np.array_equal(out[0], out[2])
+
+
 @pytest.mark.parametrize("n,d,B,r,gamma", [
     (2000, 16, 128, 128, 1.0 / 16),     # the tiny workload's shape
     (1, 7, 1, 1, 0.3),

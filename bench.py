@@ -62,13 +62,15 @@ def parse_args():
                     help="factor: size the workspace for kernel-block panels of this many rows (a multiple of 256; "
                          "0 = the library's recommendation)")
     ap.add_argument("--path", default="factor", choices=["factor", "solver", "predict", "stream", "whiten", "sparse",
-                                                         "calibrate"],
+                                                         "multi", "calibrate"],
                     help="factor: Nystrom factor + margin sweep (default); solver: batched dual coordinate ascent "
                          "on G; predict: scores of new points; stream: the factor copied to pinned host memory as it is made; whiten: the one-off preparation "
-                         "(steps 1a-1c) on the device; sparse: the factor from X in compressed-row form; calibrate: a "
+                         "(steps 1a-1c) on the device; sparse: the factor from X in compressed-row form; multi: one pass over G "
+                         "against --vectors weight vectors; calibrate: a "
                          "plain 1 GiB device-to-device copy, the known traffic the FETCH_SIZE / WRITE_SIZE counters "
                          "are scaled by")
     ap.add_argument("--classifiers", type=int, default=10, help="predict: number of classifiers scored at once")
+    ap.add_argument("--vectors", type=int, default=32, help="multi: weight vectors swept at once")
     ap.add_argument("--whiten", default="device", choices=["device", "host"],
                     help="steps 1a-1c (one-off preparation, outside the timed region): lpd_whiten on the GPU, or the "
                          "host routine")
@@ -523,6 +525,43 @@ def bench_calibrate(args):
                       "kib_per_copy_each_way": 4 * n // 1024}))
 
 
+def bench_multi(args):
+    """Margins of --vectors weight vectors at once (folds, C values, class pairs sharing one G): one pass of
+    lpd_margins_multi over a synthetic G of the workload's shape (rows capped at 32 GiB of G)."""
+    import torch
+    from paper_2207_01016_amd import lpd, workloads
+    dev = torch.device("cuda:0")
+    wl = workloads.WORKLOADS[args.workload]
+    r = wl.B
+    n = min(wl.n, (32 << 30) // (4 * r))
+    g = torch.Generator(device=dev).manual_seed(5)
+    G = torch.randn((n, r), generator=g, device=dev)
+    k = args.vectors
+    Ws = torch.randn((k, r), generator=g, device=dev) / r ** 0.5
+    M = torch.empty((n, k), dtype=torch.float32, device=dev)
+    for _ in range(args.warmup):
+        lpd.lpd_margins_multi(G, Ws, M)
+    evs = []
+    for _ in range(args.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        lpd.lpd_margins_multi(G, Ws, M)
+        e1.record()
+        evs.append((e0, e1))
+    torch.cuda.synchronize()
+    ms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
+    gbps = 4.0 * n * r / ms / 1e6
+    tflops = 2.0 * n * r * k / ms / 1e9
+    print(json.dumps({"metric": "multi_vector_sweep_rows_per_s", "value": n / ms * 1e3, "unit": "rows/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+                      "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": args.workload, "rows": n, "r": r, "vectors": k},
+                      "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                   "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
+                                   "kernel": "one pass over G (4 n r bytes)"},
+                      "mfma_tflops": tflops, "mfma_frac_of_fp32_peak": tflops / FP32_MFMA_PEAK_TFLOPS}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -551,6 +590,9 @@ def main():
         return
     if args.path == "sparse":
         bench_sparse(args)
+        return
+    if args.path == "multi":
+        bench_multi(args)
         return
     if args.path == "calibrate":
         bench_calibrate(args)

@@ -360,7 +360,9 @@ int lpd_margins_rows(const float *G, int64_t n, int64_t r, int64_t ldg,
 /*
  * Step 2a for several weight vectors that share G (the classifiers of a C grid, of the folds, of the
  * class pairs; Section 4):  M[i, q] = sum_{j<r} G[i,j] * Ws[q,j],  q < k.
- * Up to 8 vectors are served by one bandwidth-bound pass over G, more by the MFMA product G Ws^T.
+ * Up to 4 vectors are served by one pass over G with vector FMAs, more by the MFMA product G Ws^T on a
+ * narrow tile, which reads G once as well (5 to 8 vectors take it when G, Ws, ldg, ldws and r allow 16-byte
+ * loads, else the FMA pass).
  *   G device in n x r (ldg);  Ws device in k x r (ldws), one vector per row;  M device out n x k (ldm)
  * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE, LPD_ERR_LD, LPD_ERR_HIP.
  */

@@ -286,7 +286,7 @@ def test_main_loop_schedules_agree_bit_for_bit(lpd, oracle, dev, n, d, B, tile):
     assert np.array_equal(out[0], out[1]) and np.array_equal(out[0], out[2])
 
 
-@pytest.mark.parametrize("k", [9, 32, 33, 64])
+@pytest.mark.parametrize("k", [5, 9, 32, 33, 64])
 @pytest.mark.parametrize("n,r", [
     (300, 16), (300, 32), (257, 48), (300, 64),     # 1 to 4 k-tiles: fewer than the staged tiles of the schedule
     (513, 80), (300, 96), (300, 112), (300, 128),   # every remainder of the loop that is unrolled four times
@@ -294,7 +294,7 @@ def test_main_loop_schedules_agree_bit_for_bit(lpd, oracle, dev, n, d, B, tile):
     (300, 100),                                     # a partial last k-tile
 ])
 def test_narrow_tile_schedules_agree_bit_for_bit(lpd, oracle, dev, n, r, k):
-    """9 to 64 weight vectors take the narrow tiles, whose default schedule keeps four k-tiles in flight and
+    """5 to 64 weight vectors take the narrow tiles, whose default schedule keeps four k-tiles in flight and
     requests them in pairs; the plain and the one-tile schedules visit k in the same order."""
     g = torch.Generator().manual_seed(77 + n + r + k)
     G = torch.randn((n, r), generator=g).to(dev)
@@ -479,6 +479,8 @@ def test_margins_on_factor_output_tiny(lpd, wls, oracle, dev):
 
 @pytest.mark.parametrize("n,r,ld,k", [(700, 300, 300, 1), (1000, 1024, 1024, 3), (513, 1001, 1004, 8),
                                        (301, 517, 517, 5), (2000, 640, 640, 9), (900, 260, 264, 150),
+                                       # five to eight vectors: MFMA tile when 16-byte loads apply, else the plain kernel
+                                       (1000, 1024, 1024, 5), (700, 640, 644, 8), (900, 512, 512, 4), (640, 250, 252, 7),
                                        # the narrow MFMA tiles (up to 32 and up to 64 vectors), aligned and not,
                                        # rows not a multiple of the tile, and the first count past them
                                        (1500, 512, 512, 16), (777, 333, 333, 32), (1030, 400, 400, 33),

@@ -230,7 +230,7 @@ hipError_t launch_gemm(const GemmArgs &a, int epi, hipStream_t s, int *tiles_n =
     const bool aligned = aligned16(a.A) && aligned16(a.B) && a.lda % 4 == 0 && a.ldb % 4 == 0 && a.K % 4 == 0;
     // a plain product with at most 64 columns (a few dozen weight vectors against the rows of G, which it reads
     // once): a narrow tile does a quarter or half of the MFMA work a 128-wide tile would pad it to, and the pass
-    // is bound by reading G (33 GB against 9 to 32 vectors: 6.9 ms instead of 15.9)
+    // is bound by reading G (33 GB against up to 32 vectors: 6.0 ms instead of 15.9)
     if (epi == EPI_STORE && a.n_store <= 64 && g_tile_option.load(std::memory_order_relaxed) == TILE_AUTO) {
         if (tiles_n) *tiles_n = 1;
         return a.n_store <= 32 ? launch_narrow<32>(a, aligned, s) : launch_narrow<64>(a, aligned, s);

@@ -291,7 +291,7 @@ def bench_predict(args):
                    "rank": rank, "classifiers": c, "gamma": wl.gamma},
         "whiten_s": None if args.random_w else t_whiten,
         "roofline": {"kernel": ("lpd_predict: gemm_nt_kernel<EPI_GAUSS_DOT> (kernel block contracted with the folded weights "
-                                "in its own launch) + the pass that adds the tile columns' shares" if c <= 32 else
+                                "in its own launch) + the pass that adds the tile columns' shares" if c <= 64 else
                                 "lpd_predict: gemm_nt_kernel<EPI_GAUSS> panels + MFMA product with the folded weights"),
                      "bound": "mfma",
                      "achieved": tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -380,9 +380,10 @@ int lpd_margins_multi(const float *G, int64_t n, int64_t r, int64_t ldg,
  *   W device in r x B (ldw);  Ws device in c x r (ldws), one classifier per row;  V device out c x B (ldv)
  * lpd_predict:       F[i, j] = sum_b V[j, b] * exp(-gamma ||x_i - l_b||^2)     (n x c),  c <= B
  *   X device in n x d (ldx);  L device in B x d (ldl);  V device in c x B (ldv);  F device out n x c (ldf)
- *   workspace: as for lpd_nystrom_factor (lpd_nystrom_factor_workspace(n, d, B)); the kernel block is
- *   produced panel by panel and consumed at once, by multi-vector sweeps (8 classifiers each) for c <= 32, by the MFMA
- *   product otherwise.
+ *   workspace: as for lpd_nystrom_factor (lpd_nystrom_factor_workspace(n, d, B)).  Up to 64 classifiers the
+ *   kernel block is contracted with V in the write-out of its own launch and never stored (the workspace
+ *   holds per-tile shares of the scores); with more, or with few landmarks and a dozen classifiers or more,
+ *   it is produced panel by panel and consumed at once by the MFMA product with V.
  * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE (incl. c > B), LPD_ERR_LD, LPD_ERR_WORKSPACE, LPD_ERR_HIP.
  */
 int lpd_fold_weights(const float *W, int64_t r, int64_t B, int64_t ldw,

@@ -38,7 +38,7 @@ template <int I>
 using SI = std::integral_constant<int, I>;
 
 enum { EPI_STORE = 0, EPI_GAUSS = 1, EPI_GAUSS_DOT = 2 };
-constexpr int GEMM_DOT_MAX = 32;     // weight vectors the EPI_GAUSS_DOT write-out takes at once
+constexpr int GEMM_DOT_MAX = 64;     // weight vectors the EPI_GAUSS_DOT write-out takes at once
 
 struct GemmArgs {
     const float *A;  // M x K
@@ -69,10 +69,11 @@ constexpr int GEMM_LDK = GEMM_BK + 4;
 
 // two stages of operand tiles, then the BM + BN squared norms of the tile's rows and columns (EPI_GAUSS),
 // then the tile's columns of the weight vectors (EPI_GAUSS_DOT)
+// (nv: the weight vectors of the launch; their slots are the last thing in LDS, so a launch with fewer asks for less)
 template <int BM, int BN, int EPI = EPI_STORE>
-constexpr size_t gemm_lds_bytes()
+constexpr size_t gemm_lds_bytes(int nv = GEMM_DOT_MAX)
 {
-    return (size_t(2) * (BM + BN) * GEMM_LDK + (BM + BN) + (EPI == EPI_GAUSS_DOT ? GEMM_DOT_MAX * BN : 0)) * sizeof(float);
+    return (size_t(2) * (BM + BN) * GEMM_LDK + (BM + BN) + (EPI == EPI_GAUSS_DOT ? nv * BN : 0)) * sizeof(float);
 }
 
 template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI, int PIPE>
@@ -499,8 +500,12 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
         //   3. the tile's BM x nv scores go to P.
         constexpr int NSL = TM * 16;                      // row slots per lane: 32, or 16 for a wavefront of 32 rows
         static_assert(WGN <= 2 && (NSL == 32 || NSL == 16), "two wavefronts across at most; 16 or 32 row slots per lane");
-        float *ft = lds;                                   // BM x GEMM_DOT_MAX, over the operand stages (all done with)
-        for (int e = tid; e < BM * GEMM_DOT_MAX; e += NT) ft[e] = 0.0f;
+        // (a row of the tile's scores is padded by one float: the 32 lanes that add one vector's sums of 32 rows
+        // then hit 32 banks instead of one)
+        constexpr int FLD = GEMM_DOT_MAX + 1;
+        static_assert(BM * FLD <= 2 * STAGE, "the tile's scores take the place of the operand stages");
+        float *ft = lds;                                   // BM x FLD, over the operand stages (all done with)
+        for (int e = tid; e < BM * FLD; e += NT) ft[e] = 0.0f;
         float nbv[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) nbv[j] = nbs[wn * WN + j * 32 + col_in];
@@ -547,12 +552,12 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
             // lane l now holds slot l % NSL = 16 i + v of its half-wavefront's rows (with 16 slots, twice over)
             const int sl = lane & (NSL - 1);
             const int rl = wm * WM + (sl >> 4) * 32 + 8 * ((sl & 15) >> 2) + row_in + (sl & 3);
-            if (NSL == 32 || (lane & 16) == 0) atomicAdd(&ft[rl * GEMM_DOT_MAX + q], t[0]);
+            if (NSL == 32 || (lane & 16) == 0) atomicAdd(&ft[rl * FLD + q], t[0]);
         }
         __syncthreads();
         for (int e = tid; e < BM * p.nv; e += NT) {
             const int rl = e / p.nv, q = e - rl * p.nv;
-            if (m0 + rl < p.M) p.P[(int64_t(tn) * p.M + m0 + rl) * p.nv + q] = ft[rl * GEMM_DOT_MAX + q];
+            if (m0 + rl < p.M) p.P[(int64_t(tn) * p.M + m0 + rl) * p.nv + q] = ft[rl * FLD + q];
         }
     } else if (m0 + BM <= p.M && n0 + BN <= p.N) {
         // interior tile: no bounds to check, one row pointer per group of four rows

@@ -6,6 +6,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstring>
+#include <numeric>
 #include <vector>
 
 #include "../../include/lpd.h"
@@ -94,7 +95,7 @@ std::atomic<int> g_tile_option{TILE_AUTO};   // LPD_OPT_GEMM_TILE
 std::atomic<int> g_csr_route{0};              // LPD_OPT_CSR_ROUTE: 0 by density, 1 dense panel, 2 gather
 std::atomic<int> g_sweep_grid{0};             // LPD_OPT_SWEEP_GRID: 0 = by row length, else the number of workgroups of a full sweep
 std::atomic<int> g_small_path{1};             // LPD_OPT_SMALL_PATH: 1 = one-launch factor for B <= 256, 0 = panel schedule
-std::atomic<int> g_fused_scores{1};           // LPD_OPT_FUSED_SCORES: 1 = prediction with up to 16 weight vectors contracts the kernel block in its launch
+std::atomic<int> g_fused_scores{1};           // LPD_OPT_FUSED_SCORES: 1 = prediction with up to GEMM_DOT_MAX weight vectors contracts the kernel block in its launch
 
 // Estimated duration of a launch with BM x BN tiles, in units of (CUs x tile elements): a CU holds `per_cu`
 // workgroups (registers and LDS: 5 of the 64x128 tile, 3 of the 128x128 tile, 2 of the 256x128 tile of the plain
@@ -146,7 +147,7 @@ int tile_choice(const GemmArgs &a, int epi)
                             launch_cost(a, 128, 128, epi == EPI_GAUSS_DOT ? 2 : 3, tile_speed(TILE_128x128, epi, a.K)),
                             launch_cost(a, 256, 128, gauss ? 1 : 2, tile_speed(TILE_256x128, epi, a.K)),
                             launch_cost(a, 256, 256, 1, tile_speed(TILE_256x256, epi, a.K)),
-                            launch_cost(a, 64, 128, epi == EPI_GAUSS_DOT ? 3 : gauss ? 5 : 4, tile_speed(TILE_64x128, epi, a.K))};
+                            launch_cost(a, 64, 128, epi == EPI_GAUSS_DOT ? (a.nv > GEMM_DOT_MAX / 2 ? 2 : 3) : gauss ? 5 : 4, tile_speed(TILE_64x128, epi, a.K))};
     int best = TILE_128x128;
     for (int t : {TILE_256x128, TILE_256x256, TILE_64x128})
         if (cost[t] < cost[best] && !(t == TILE_256x128 && epi == EPI_GAUSS_DOT)) best = t;    // (not built for that write-out)
@@ -168,7 +169,9 @@ hipError_t launch_one(GemmArgs a, hipStream_t s)
     const int64_t wgs = int64_t(a.tiles_m) * a.tiles_n;
     if (wgs <= 0) return hipSuccess;
     if (wgs > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3(unsigned(wgs)), dim3(WGM * WGN * 64), lds, s, a);
+    // (up to 32 weight vectors ask for half the slots: the smaller tiles then fit one more workgroup to a CU)
+    const size_t lds_launch = EPI == EPI_GAUSS_DOT && a.nv <= GEMM_DOT_MAX / 2 ? gemm_lds_bytes<BM, BN, EPI>(GEMM_DOT_MAX / 2) : lds;
+    hipLaunchKernelGGL(kern, dim3(unsigned(wgs)), dim3(WGM * WGN * 64), lds_launch, s, a);
     return hipGetLastError();
 }
 
@@ -225,13 +228,13 @@ hipError_t launch_narrow(const GemmArgs &a, bool aligned, hipStream_t s)
 }
 
 // tiles_n (optional): receives the number of tile columns of the launch (the layout of GemmArgs::P depends on it)
-hipError_t launch_gemm(const GemmArgs &a, int epi, hipStream_t s, int *tiles_n = nullptr)
+hipError_t launch_gemm(const GemmArgs &a, int epi, hipStream_t s, int *tiles_n = nullptr, bool allow_narrow = true)
 {
     const bool aligned = aligned16(a.A) && aligned16(a.B) && a.lda % 4 == 0 && a.ldb % 4 == 0 && a.K % 4 == 0;
     // a plain product with at most 64 columns (a few dozen weight vectors against the rows of G, which it reads
     // once): a narrow tile does a quarter or half of the MFMA work a 128-wide tile would pad it to, and the pass
     // is bound by reading G (33 GB against up to 32 vectors: 6.0 ms instead of 15.9)
-    if (epi == EPI_STORE && a.n_store <= 64 && g_tile_option.load(std::memory_order_relaxed) == TILE_AUTO) {
+    if (epi == EPI_STORE && a.n_store <= 64 && allow_narrow && g_tile_option.load(std::memory_order_relaxed) == TILE_AUTO) {
         if (tiles_n) *tiles_n = 1;
         return a.n_store <= 32 ? launch_narrow<32>(a, aligned, s) : launch_narrow<64>(a, aligned, s);
     }
@@ -421,16 +424,36 @@ int static_scratch(void **out)
     return LPD_OK;
 }
 
-constexpr int64_t kSweepClassifiers = 32;   // up to here prediction consumes a panel by sweeps, above by MFMA
+// Prediction, how a panel of the kernel block meets the classifiers' weights.  Contracted in the write-out of the
+// kernel-block launch (no panel stored) the cost grows with the classifiers, 1.7 us per classifier and 256x256
+// tile; a stored panel consumed by an MFMA product costs 30-45 us per tile whatever their number, provided the
+// panel has rows for enough workgroups, which it has with few landmarks (rows = 32 Mi / B): from kNarrowRows
+// on for the narrow tiles (256 rows each), from kLongPanelRows on for 128-wide tiles of 64 rows.  Short panels
+// (many landmarks) leave most compute units idle in that product, and the contracted write-out wins up to its
+// limit of GEMM_DOT_MAX classifiers.
+constexpr int64_t kSweepClassifiers = 32;   // up to here a short stored panel is consumed by sweeps, above by MFMA
+constexpr int64_t kNarrowRows = 32768;
+constexpr int64_t kLongPanelRows = 16384;
+// classifiers up to which the contracted write-out beats a stored panel of that many rows (measured crossings:
+// 1,024 landmarks about 12, 2,048 about 24, 4,096 about 44; 8,192 landmarks and more: beyond GEMM_DOT_MAX)
+int64_t contract_limit(int64_t panel_rows)
+{
+    return panel_rows >= kNarrowRows ? 12 : panel_rows >= kLongPanelRows ? 24 : panel_rows >= 8192 ? 44 : GEMM_DOT_MAX;
+}
 
 // What follows a panel of the kernel block: Z (rows x B) times W^T into `out` (factor: out_cols = B, zero fill
 // past r; prediction: out_cols = r classifiers, by sweeps of 8 while they are few, else by the MFMA product).
 hipError_t consume_panel(const float *Z, int64_t rows, int64_t ldz, int64_t B, const float *W, int64_t r, int64_t ldw,
                          float *out, int64_t ldo, int64_t out_cols, hipStream_t s)
 {
-    if (out_cols != B && r <= kSweepClassifiers) {
+    // (16-byte loads for the MFMA tiles' fast path)
+    const bool fast = aligned16(Z) && aligned16(W) && ldz % 4 == 0 && ldw % 4 == 0 && B % 4 == 0;
+    const bool narrow_pays = fast && rows >= kNarrowRows;
+    const bool mfma_pays = fast && rows >= kLongPanelRows;
+    if (out_cols != B && (r <= 4 || (r <= 8 && !narrow_pays) || (r <= kSweepClassifiers && !mfma_pays))) {
         // a few classifiers: bandwidth-bound passes over the panel, 8 classifiers each, instead of an
-        // MFMA tile that would be three quarters padding or more
+        // MFMA tile that would be three quarters padding or more; from five classifiers on a narrow MFMA tile
+        // reads the panel faster, provided the panel has rows for enough such tiles (few landmarks)
         for (int64_t q0 = 0; q0 < r; q0 += 8) {
             const hipError_t e = launch_margins_multi(Z, rows, B, ldz, W + q0 * ldw, std::min<int64_t>(8, r - q0), ldw,
                                                       out + q0, ldo, s);
@@ -443,7 +466,9 @@ hipError_t consume_panel(const float *Z, int64_t rows, int64_t ldz, int64_t B, c
     k2.B = W; k2.ldb = ldw;
     k2.C = out; k2.ldc = ldo;
     k2.M = int(rows); k2.N = int(r); k2.K = int(B); k2.n_store = int(out_cols);
-    return launch_gemm(k2, EPI_STORE, s);
+    // (33 to 64 classifiers against a short panel: a 128-wide tile of 64 rows, half of it padding, still spreads
+    // over four times as many workgroups as the narrow tile)
+    return launch_gemm(k2, EPI_STORE, s, nullptr, out_cols == B || narrow_pays);
 }
 
 // Shared schedule of the factor (out_cols = B: G = Z W^T with zero fill of columns r..B-1) and of
@@ -499,13 +524,19 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
     LPD_HIP(log.end(s));
 
     // (the shares of the scores, one per 128 landmarks at most, must fit a panel row's place in the workspace)
+    // (a long stored panel beats the contracted write-out from a dozen or two classifiers on, see kNarrowRows:
+    // 100,000 points against 1,024 landmarks, 32 classifiers, 0.46 ms against 0.84)
     fused_scores = out_cols != B && r > 0 && r <= GEMM_DOT_MAX && g_fused_scores.load(std::memory_order_relaxed) != 0 &&
-                   ((B + 127) / 128) * r <= c.ldz;
+                   ((B + 127) / 128) * r <= c.ldz &&
+                   r <= contract_limit(panel);
     if (fused_scores && panel < n) {
         // no panel of the kernel block is stored, so a launch can take as many rows as their shares of the scores
         // fit the workspace: fewer launches, fewer ragged ends
-        const int64_t fit = int64_t((workspace_bytes - c.off_z) / 4) / (((B + 127) / 128) * r);
-        panel = std::min<int64_t>(n, std::max<int64_t>(panel, fit / 256 * 256));
+        int64_t fit = int64_t((workspace_bytes - c.off_z) / 4) / (((B + 127) / 128) * r) / 256 * 256;
+        // (whole rounds of 256x256 tiles over the 256 CUs where the rows allow: tile rows x tile columns a multiple of 256)
+        const int64_t even = 256 * (256 / std::gcd<int64_t>(256, (B + 255) / 256));
+        if (fit >= even) fit = fit / even * even;
+        panel = std::min<int64_t>(n, std::max<int64_t>(panel, fit));
     }
     for (int64_t p0 = 0; p0 < n; p0 += panel) {
         const int64_t rows = std::min<int64_t>(panel, n - p0);

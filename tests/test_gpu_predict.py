@@ -77,7 +77,9 @@ def test_predict_matches_oracle(lpd, oracle, dev, name, n, B, n_test, c):
     (777, 20, 130, 1, True),        # one and a bit tile columns, ragged rows
     (1000, 64, 333, 5, True),       # B and n no multiple of anything
     (513, 19, 257, 7, False),       # d % 4 != 0: element-wise loader, plain schedule
-    (300, 48, 64, 32, True),        # the most weight vectors the write-out takes
+    (300, 48, 64, 32, True),        # the most weight vectors that fit half the slots of the write-out
+    (700, 36, 300, 33, True),       # one more: the full set of slots
+    (1300, 64, 520, 64, True),      # the most weight vectors the write-out takes
     (2100, 16, 1040, 17, True),     # several tile rows and columns of every tile
     (260, 0, 96, 3, True),          # no features: z = 1, the scores are the row sums of V
     (50, 8, 3, 2, True),            # three landmarks
@@ -143,3 +145,39 @@ def test_predict_strided_output_and_zero_classifiers(lpd, dev):
     assert torch.all(Fbig[:, 2:] == 0) and bool(Fbig[:, :2].abs().sum() > 0)
     ref = torch.exp(-0.1 * torch.cdist(X.double(), L.double()) ** 2) @ V.double().T
     assert float((Fbig[:, :2].double() - ref).norm() / ref.norm()) <= 1e-5
+
+
+@pytest.mark.parametrize("n,d,B,c", [
+    (40000, 24, 300, 5),       # a stored panel of 40,000 rows: few classifiers are contracted in the kernel-block launch,
+    (40000, 24, 300, 13),      # a dozen and more meet the panel in a narrow MFMA tile
+    (40000, 24, 300, 64),
+    (20000, 20, 200, 30),      # 20,000 rows: from two dozen classifiers on a 128-wide tile consumes the panel
+    (20000, 20, 200, 20),      # below: contracted
+    (9000, 16, 130, 50),       # 9,000 rows: the same from 45 classifiers on
+])
+def test_routes_of_prediction_with_few_landmarks_match_the_oracle(lpd, oracle, dev, n, d, B, c):
+    """With few landmarks a stored panel of the kernel block is long, and which route meets the classifiers'
+    weights depends on their number; every route gives the oracle's scores, and the same as the contracted
+    route forced off."""
+    g = torch.Generator().manual_seed(3 * n + B + c)
+    Xf = torch.randn((n, d), generator=g)
+    Lf = torch.randn((B, d), generator=g)
+    V = (torch.randn((c, B), generator=g) / B ** 0.5).to(dev)
+    X, L = Xf.to(dev), Lf.to(dev)
+    gamma = 0.5 / d
+    ws = lpd.alloc_workspace(n, d, B, dev)
+    out = []
+    try:
+        for fused in (1, 0):
+            lpd.lpd_set_option(lpd.LPD_OPT_FUSED_SCORES, fused)
+            F = torch.full((n, c), float("nan"), dtype=torch.float32, device=dev)
+            lpd.lpd_predict(X, L, gamma, V, F, ws)
+            torch.cuda.synchronize()
+            out.append(F.cpu().numpy())
+    finally:
+        lpd.lpd_set_option(lpd.LPD_OPT_FUSED_SCORES, 1)
+    Z = oracle.kernel_block(Xf.numpy(), Lf.numpy(), gamma)
+    ref = Z @ V.cpu().numpy().astype(np.float64).T
+    assert np.all(np.isfinite(out[0])) and np.all(np.isfinite(out[1]))
+    assert relfro(out[0], ref) <= 1e-5 and relfro(out[1], ref) <= 1e-5
+    assert relfro(out[0], out[1]) <= 2e-6

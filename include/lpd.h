@@ -382,8 +382,8 @@ int lpd_margins_multi(const float *G, int64_t n, int64_t r, int64_t ldg,
  *   X device in n x d (ldx);  L device in B x d (ldl);  V device in c x B (ldv);  F device out n x c (ldf)
  *   workspace: as for lpd_nystrom_factor (lpd_nystrom_factor_workspace(n, d, B)).  Up to 64 classifiers the
  *   kernel block is contracted with V in the write-out of its own launch and never stored (the workspace
- *   holds per-tile shares of the scores); with more, or with few landmarks and a dozen classifiers or more,
- *   it is produced panel by panel and consumed at once by the MFMA product with V.
+ *   holds per-tile shares of the scores); with more it is produced panel by panel and consumed at once by
+ *   the MFMA product with V.
  * Errors: LPD_ERR_NULL, LPD_ERR_SHAPE (incl. c > B), LPD_ERR_LD, LPD_ERR_WORKSPACE, LPD_ERR_HIP.
  */
 int lpd_fold_weights(const float *W, int64_t r, int64_t B, int64_t ldw,

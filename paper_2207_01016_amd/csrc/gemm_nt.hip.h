@@ -39,6 +39,7 @@ using SI = std::integral_constant<int, I>;
 
 enum { EPI_STORE = 0, EPI_GAUSS = 1, EPI_GAUSS_DOT = 2 };
 constexpr int GEMM_DOT_MAX = 64;     // weight vectors the EPI_GAUSS_DOT write-out takes at once
+constexpr int GEMM_DOT_FMA_MAX = 6;  // up to here the write-out multiplies by them with vector FMAs, above on the MFMA units
 
 struct GemmArgs {
     const float *A;  // M x K
@@ -73,7 +74,7 @@ constexpr int GEMM_LDK = GEMM_BK + 4;
 template <int BM, int BN, int EPI = EPI_STORE>
 constexpr size_t gemm_lds_bytes(int nv = GEMM_DOT_MAX)
 {
-    return (size_t(2) * (BM + BN) * GEMM_LDK + (BM + BN) + (EPI == EPI_GAUSS_DOT ? nv * BN : 0)) * sizeof(float);
+    return (size_t(2) * (BM + BN) * GEMM_LDK + (BM + BN) + (EPI == EPI_GAUSS_DOT ? nv * (BN + 4) : 0)) * sizeof(float);
 }
 
 template <int BM, int BN, int WGM, int WGN, bool ALIGNED, int EPI, int PIPE>
@@ -200,11 +201,15 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
     }
     // EPI_GAUSS_DOT: the tile's columns of the weight vectors, zero past column N, so that a column outside the
     // matrix adds nothing whatever its accumulator holds
+    // (whole groups of 32 vectors, zero past the last one; rows padded like the operand stages: the write-out reads
+    // them as MFMA operand fragments)
+    constexpr int VLD = BN + 4;
     float *vs = nbs + BN;
     if constexpr (EPI == EPI_GAUSS_DOT) {
-        for (int e = tid; e < p.nv * BN; e += NT) {
+        const int nvpad = (p.nv + 31) / 32 * 32;
+        for (int e = tid; e < nvpad * BN; e += NT) {
             const int q = e / BN, cl = e - q * BN;
-            vs[e] = n0 + cl < p.N ? p.V[int64_t(q) * p.ldv + n0 + cl] : 0.0f;
+            vs[q * VLD + cl] = q < p.nv && n0 + cl < p.N ? p.V[int64_t(q) * p.ldv + n0 + cl] : 0.0f;
         }
     }
 
@@ -491,21 +496,23 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
     };
     if constexpr (EPI == EPI_GAUSS_DOT) {
         // Scores of the tile's rows against nv weight vectors, straight from the accumulators (prediction, Section 4
-        // "Algorithm Overview": K(x, L) times the folded weights; the kernel block never leaves the registers).
+        // "Algorithm Overview": K(x, L) times the folded weights; the kernel block never leaves the chip).
         //   1. z in place of the accumulators (rows past M are never written out, columns past N meet zero weights);
-        //   2. per vector: a lane's 32 row slots times its TN columns, then a reduce-scatter over the 32 lanes that
-        //      hold the same rows (after the five halving steps lane l holds the total of slot l), then one LDS add
-        //      per lane into the tile's scores (the WGN wavefronts side by side add into the same entries: with at
-        //      most two of them the sum does not depend on who comes first);
-        //   3. the tile's BM x nv scores go to P.
-        constexpr int NSL = TM * 16;                      // row slots per lane: 32, or 16 for a wavefront of 32 rows
-        static_assert(WGN <= 2 && (NSL == 32 || NSL == 16), "two wavefronts across at most; 16 or 32 row slots per lane");
-        // (a row of the tile's scores is padded by one float: the 32 lanes that add one vector's sums of 32 rows
-        // then hit 32 banks instead of one)
+        //   2. a wavefront's scores F_w = z_w V_w^T, its WM x WN block of z against its WN columns of the weight
+        //      vectors, on the MFMA units: 32 vectors at a time fill the output columns of a 32x32 tile.  z is in
+        //      accumulator layout (a lane holds one column), the A operand wants a lane to hold one row, so each
+        //      32x32 block of z passes through a patch of LDS that belongs to its wavefront alone (LDS serves a
+        //      wavefront's accesses in the order it issued them: no barrier, no wait);
+        //   3. the WGN wavefronts side by side hold shares of the same rows: the right one hands its share over
+        //      through LDS, the left one adds and writes the tile's BM x nv scores to P.  No atomics: the order of
+        //      every sum is fixed.
+        static_assert(WGN <= 2, "two wavefronts across at most");
+        constexpr int NVG = GEMM_DOT_MAX / 32;             // groups of 32 weight vectors
+        constexpr int PLD = 32 + 4;                        // patch rows padded like the operand stages
         constexpr int FLD = GEMM_DOT_MAX + 1;
-        static_assert(BM * FLD <= 2 * STAGE, "the tile's scores take the place of the operand stages");
-        float *ft = lds;                                   // BM x FLD, over the operand stages (all done with)
-        for (int e = tid; e < BM * FLD; e += NT) ft[e] = 0.0f;
+        static_assert(WGM * WGN * 32 * PLD <= 2 * STAGE && BM * FLD <= 2 * STAGE,
+                      "patches and handed-over scores take the place of the operand stages");
+        const int ngr = (p.nv + 31) / 32;
         float nbv[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) nbv[j] = nbs[wn * WN + j * 32 + col_in];
@@ -517,47 +524,124 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j][v] = finish(acc[i][j][v], nav, nbv[j]);
             }
-        __syncthreads();                                   // ft is zero everywhere
-        for (int q = 0; q < p.nv; ++q) {
-            float vq[TN];
+        __syncthreads();                                   // every wavefront is done with the operand stages
+        if (p.nv <= GEMM_DOT_FMA_MAX) {
+            // A handful of vectors: a 32-wide MFMA tile would be mostly padding and costs what ten vectors cost
+            // this way.  Per vector: a lane's row slots times its TN columns, then a reduce-scatter over the 32
+            // lanes that hold the same rows (after the five halving steps lane l holds the total of slot l), then
+            // one LDS add per lane into the tile's scores (the WGN wavefronts side by side add into the same
+            // entries: with at most two of them the sum does not depend on who comes first).
+            constexpr int NSL = TM * 16;                  // row slots per lane: 32, or 16 for a wavefront of 32 rows
+            static_assert(NSL == 32 || NSL == 16, "16 or 32 row slots per lane");
+            float *ft = lds;                               // BM x FLD, over the operand stages
+            for (int e = tid; e < BM * FLD; e += NT) ft[e] = 0.0f;
+            __syncthreads();                               // ft is zero everywhere
+            for (int q = 0; q < p.nv; ++q) {
+                float vq[TN];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) vq[j] = vs[q * BN + wn * WN + j * 32 + col_in];
-            float t[NSL];
+                for (int j = 0; j < TN; ++j) vq[j] = vs[q * VLD + wn * WN + j * 32 + col_in];
+                float t[NSL];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        float sum = 0.0f;
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) sum += acc[i][j][v] * vq[j];
+                        t[i * 16 + v] = sum;
+                    }
+                if constexpr (NSL == 16) {                     // 16 slots over 32 lanes: lanes l and l ^ 16 first join
+#pragma unroll
+                    for (int sl = 0; sl < 16; ++sl) t[sl] += __shfl_xor(t[sl], 16, 64);
+                }
+#pragma unroll
+                for (int k = NSL / 2; k >= 1; k >>= 1) {
+                    const bool up = (lane & k) != 0;           // this lane keeps the upper half of the slots
+#pragma unroll
+                    for (int sl = 0; sl < k; ++sl) {
+                        // both slots are read into values first: a choice between two array elements would be turned
+                        // into a per-lane index, and an array indexed per lane cannot live in registers
+                        const float lo = t[sl], hi = t[sl + k];
+                        const float keep = up ? hi : lo;
+                        const float send = up ? lo : hi;
+                        t[sl] = keep + __shfl_xor(send, k, 64);
+                    }
+                }
+                // lane l now holds slot l % NSL = 16 i + v of its half-wavefront's rows (with 16 slots, twice over)
+                const int sl = lane & (NSL - 1);
+                const int rl = wm * WM + (sl >> 4) * 32 + 8 * ((sl & 15) >> 2) + row_in + (sl & 3);
+                if (NSL == 32 || (lane & 16) == 0) atomicAdd(&ft[rl * FLD + q], t[0]);
+            }
+            __syncthreads();
+            for (int e = tid; e < BM * p.nv; e += NT) {
+                const int rl = e / p.nv, q = e - rl * p.nv;
+                if (m0 + rl < p.M) p.P[(int64_t(tn) * p.M + m0 + rl) * p.nv + q] = ft[rl * FLD + q];
+            }
+            return;
+        }
+        float *patch = lds + wave * (32 * PLD);
+        f32x16 fs[TM][NVG];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int g = 0; g < NVG; ++g)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) fs[i][g][v] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) patch[(8 * (v >> 2) + row_in + (v & 3)) * PLD + col_in] = acc[i][j][v];
+                __builtin_amdgcn_s_waitcnt(0xc07f);        // lgkmcnt(0): the block is in LDS before it is read back
+                __builtin_amdgcn_wave_barrier();           // (and the compiler keeps the reads behind the writes)
+#pragma unroll
+                for (int kc = 0; kc < 4; ++kc) {
+                    const f32x4 za = *reinterpret_cast<const f32x4 *>(&patch[col_in * PLD + 8 * kc + row_in]);
+#pragma unroll
+                    for (int g = 0; g < NVG; ++g) {
+                        if (g < ngr) {
+                            const f32x4 vb = *reinterpret_cast<const f32x4 *>(
+                                &vs[(g * 32 + col_in) * VLD + wn * WN + j * 32 + 8 * kc + row_in]);
+#pragma unroll
+                            for (int t = 0; t < 4; ++t)
+                                fs[i][g] = __builtin_amdgcn_mfma_f32_32x32x2f32(za[t], vb[t], fs[i][g], 0, 0, 0);
+                        }
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();           // (and the next block's writes behind these reads)
+            }
+        }
+        // fs[i][g][v] is the score of row wm*WM + 32 i + 8 (v/4) + 4 (l/32) + v%4 against vector 32 g + l%32
+        float *ft = lds;                                   // BM x FLD, over the patches
+        if constexpr (WGN == 2) {
+            __syncthreads();                               // all patches done with
+            if (wn == 1) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int g = 0; g < NVG; ++g)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            ft[(wm * WM + i * 32 + 8 * (v >> 2) + row_in + (v & 3)) * FLD + g * 32 + col_in] = fs[i][g][v];
+            }
+            __syncthreads();
+        }
+        if (wn == 0) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    float sum = 0.0f;
+                for (int g = 0; g < NVG; ++g) {
+                    const int q = g * 32 + col_in;
+                    if (q >= p.nv) continue;
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) sum += acc[i][j][v] * vq[j];
-                    t[i * 16 + v] = sum;
+                    for (int v = 0; v < 16; ++v) {
+                        const int rl = wm * WM + i * 32 + 8 * (v >> 2) + row_in + (v & 3);
+                        float sum = fs[i][g][v];
+                        if constexpr (WGN == 2) sum += ft[rl * FLD + q];
+                        if (m0 + rl < p.M) p.P[(int64_t(tn) * p.M + m0 + rl) * p.nv + q] = sum;
+                    }
                 }
-            if constexpr (NSL == 16) {                     // 16 slots over 32 lanes: lanes l and l ^ 16 first join
-#pragma unroll
-                for (int sl = 0; sl < 16; ++sl) t[sl] += __shfl_xor(t[sl], 16, 64);
-            }
-#pragma unroll
-            for (int k = NSL / 2; k >= 1; k >>= 1) {
-                const bool up = (lane & k) != 0;           // this lane keeps the upper half of the slots
-#pragma unroll
-                for (int sl = 0; sl < k; ++sl) {
-                    // both slots are read into values first: a choice between two array elements would be turned
-                    // into a per-lane index, and an array indexed per lane cannot live in registers
-                    const float lo = t[sl], hi = t[sl + k];
-                    const float keep = up ? hi : lo;
-                    const float send = up ? lo : hi;
-                    t[sl] = keep + __shfl_xor(send, k, 64);
-                }
-            }
-            // lane l now holds slot l % NSL = 16 i + v of its half-wavefront's rows (with 16 slots, twice over)
-            const int sl = lane & (NSL - 1);
-            const int rl = wm * WM + (sl >> 4) * 32 + 8 * ((sl & 15) >> 2) + row_in + (sl & 3);
-            if (NSL == 32 || (lane & 16) == 0) atomicAdd(&ft[rl * FLD + q], t[0]);
-        }
-        __syncthreads();
-        for (int e = tid; e < BM * p.nv; e += NT) {
-            const int rl = e / p.nv, q = e - rl * p.nv;
-            if (m0 + rl < p.M) p.P[(int64_t(tn) * p.M + m0 + rl) * p.nv + q] = ft[rl * FLD + q];
         }
     } else if (m0 + BM <= p.M && n0 + BN <= p.N) {
         // interior tile: no bounds to check, one row pointer per group of four rows

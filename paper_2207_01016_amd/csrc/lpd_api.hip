@@ -424,22 +424,14 @@ int static_scratch(void **out)
     return LPD_OK;
 }
 
-// Prediction, how a panel of the kernel block meets the classifiers' weights.  Contracted in the write-out of the
-// kernel-block launch (no panel stored) the cost grows with the classifiers, 1.7 us per classifier and 256x256
-// tile; a stored panel consumed by an MFMA product costs 30-45 us per tile whatever their number, provided the
-// panel has rows for enough workgroups, which it has with few landmarks (rows = 32 Mi / B): from kNarrowRows
-// on for the narrow tiles (256 rows each), from kLongPanelRows on for 128-wide tiles of 64 rows.  Short panels
-// (many landmarks) leave most compute units idle in that product, and the contracted write-out wins up to its
-// limit of GEMM_DOT_MAX classifiers.
+// Prediction with the contracted write-out switched off, or with more classifiers than it takes: how a stored
+// panel of the kernel block meets the classifiers' weights.  An MFMA product costs the same whatever their number,
+// provided the panel has rows for enough workgroups, which it has with few landmarks (rows = 32 Mi / B): from
+// kNarrowRows on for the narrow tiles (256 rows each), from kLongPanelRows on for 128-wide tiles of 64 rows.
+// Short panels and few classifiers are served by bandwidth-bound sweeps.
 constexpr int64_t kSweepClassifiers = 32;   // up to here a short stored panel is consumed by sweeps, above by MFMA
 constexpr int64_t kNarrowRows = 32768;
 constexpr int64_t kLongPanelRows = 16384;
-// classifiers up to which the contracted write-out beats a stored panel of that many rows (measured crossings:
-// 1,024 landmarks about 12, 2,048 about 24, 4,096 about 44; 8,192 landmarks and more: beyond GEMM_DOT_MAX)
-int64_t contract_limit(int64_t panel_rows)
-{
-    return panel_rows >= kNarrowRows ? 12 : panel_rows >= kLongPanelRows ? 24 : panel_rows >= 8192 ? 44 : GEMM_DOT_MAX;
-}
 
 // What follows a panel of the kernel block: Z (rows x B) times W^T into `out` (factor: out_cols = B, zero fill
 // past r; prediction: out_cols = r classifiers, by sweeps of 8 while they are few, else by the MFMA product).
@@ -524,11 +516,8 @@ int factor_impl(const float *X, int64_t n, int64_t d, int64_t ldx, const float *
     LPD_HIP(log.end(s));
 
     // (the shares of the scores, one per 128 landmarks at most, must fit a panel row's place in the workspace)
-    // (a long stored panel beats the contracted write-out from a dozen or two classifiers on, see kNarrowRows:
-    // 100,000 points against 1,024 landmarks, 32 classifiers, 0.46 ms against 0.84)
     fused_scores = out_cols != B && r > 0 && r <= GEMM_DOT_MAX && g_fused_scores.load(std::memory_order_relaxed) != 0 &&
-                   ((B + 127) / 128) * r <= c.ldz &&
-                   r <= contract_limit(panel);
+                   ((B + 127) / 128) * r <= c.ldz;
     if (fused_scores && panel < n) {
         // no panel of the kernel block is stored, so a launch can take as many rows as their shares of the scores
         // fit the workspace: fewer launches, fewer ragged ends

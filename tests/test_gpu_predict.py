@@ -148,17 +148,18 @@ def test_predict_strided_output_and_zero_classifiers(lpd, dev):
 
 
 @pytest.mark.parametrize("n,d,B,c", [
-    (40000, 24, 300, 5),       # a stored panel of 40,000 rows: few classifiers are contracted in the kernel-block launch,
-    (40000, 24, 300, 13),      # a dozen and more meet the panel in a narrow MFMA tile
+    (40000, 24, 300, 5),       # stored panel of 40,000 rows: sweeps up to 4 classifiers, a narrow MFMA tile from 5 on
+    (40000, 24, 300, 13),
     (40000, 24, 300, 64),
-    (20000, 20, 200, 30),      # 20,000 rows: from two dozen classifiers on a 128-wide tile consumes the panel
-    (20000, 20, 200, 20),      # below: contracted
-    (9000, 16, 130, 50),       # 9,000 rows: the same from 45 classifiers on
+    (20000, 20, 200, 30),      # 20,000 rows: a 128-wide MFMA tile from 9 classifiers on
+    (20000, 20, 200, 7),       #   sweeps below
+    (9000, 16, 130, 50),       # 9,000 rows: sweeps up to 32 classifiers, 128-wide tiles above
+    (9000, 16, 130, 20),
 ])
 def test_routes_of_prediction_with_few_landmarks_match_the_oracle(lpd, oracle, dev, n, d, B, c):
-    """With few landmarks a stored panel of the kernel block is long, and which route meets the classifiers'
-    weights depends on their number; every route gives the oracle's scores, and the same as the contracted
-    route forced off."""
+    """With few landmarks a stored panel of the kernel block is long; with the contracted write-out switched off,
+    which kernel consumes it depends on its rows and on the number of classifiers.  Every route gives the
+    oracle's scores, and the contracted write-out (FMA up to 6 classifiers, MFMA above) the same."""
     g = torch.Generator().manual_seed(3 * n + B + c)
     Xf = torch.randn((n, d), generator=g)
     Lf = torch.randn((B, d), generator=g)

@@ -579,7 +579,9 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
             }
             return;
         }
-        float *patch = lds + wave * (32 * PLD);
+        // (two blocks at a time where two patches per wavefront fit: half as many waits for LDS)
+        constexpr int NPB = (TN % 2 == 0 && 2 * WGM * WGN * 32 * PLD <= 2 * STAGE) ? 2 : 1;
+        float *patch = lds + wave * (NPB * 32 * PLD);
         f32x16 fs[TM][NVG];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -590,26 +592,32 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_nt_kernel(GemmArgs p)
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
+            for (int j0 = 0; j0 < TN; j0 += NPB) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) patch[(8 * (v >> 2) + row_in + (v & 3)) * PLD + col_in] = acc[i][j][v];
-                __builtin_amdgcn_s_waitcnt(0xc07f);        // lgkmcnt(0): the block is in LDS before it is read back
+                for (int u = 0; u < NPB; ++u)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        patch[u * 32 * PLD + (8 * (v >> 2) + row_in + (v & 3)) * PLD + col_in] = acc[i][j0 + u][v];
+                __builtin_amdgcn_s_waitcnt(0xc07f);        // lgkmcnt(0): the blocks are in LDS before they are read back
                 __builtin_amdgcn_wave_barrier();           // (and the compiler keeps the reads behind the writes)
 #pragma unroll
-                for (int kc = 0; kc < 4; ++kc) {
-                    const f32x4 za = *reinterpret_cast<const f32x4 *>(&patch[col_in * PLD + 8 * kc + row_in]);
+                for (int u = 0; u < NPB; ++u) {
 #pragma unroll
-                    for (int g = 0; g < NVG; ++g) {
-                        if (g < ngr) {
-                            const f32x4 vb = *reinterpret_cast<const f32x4 *>(
-                                &vs[(g * 32 + col_in) * VLD + wn * WN + j * 32 + 8 * kc + row_in]);
+                    for (int kc = 0; kc < 4; ++kc) {
+                        const f32x4 za = *reinterpret_cast<const f32x4 *>(&patch[u * 32 * PLD + col_in * PLD + 8 * kc + row_in]);
 #pragma unroll
-                            for (int t = 0; t < 4; ++t)
-                                fs[i][g] = __builtin_amdgcn_mfma_f32_32x32x2f32(za[t], vb[t], fs[i][g], 0, 0, 0);
+                        for (int g = 0; g < NVG; ++g) {
+                            if (g < ngr) {
+                                const f32x4 vb = *reinterpret_cast<const f32x4 *>(
+                                    &vs[(g * 32 + col_in) * VLD + wn * WN + (j0 + u) * 32 + 8 * kc + row_in]);
+#pragma unroll
+                                for (int t = 0; t < 4; ++t)
+                                    fs[i][g] = __builtin_amdgcn_mfma_f32_32x32x2f32(za[t], vb[t], fs[i][g], 0, 0, 0);
+                            }
                         }
                     }
                 }
-                __builtin_amdgcn_wave_barrier();           // (and the next block's writes behind these reads)
+                __builtin_amdgcn_wave_barrier();           // (and the next blocks' writes behind these reads)
             }
         }
         // fs[i][g][v] is the score of row wm*WM + 32 i + 8 (v/4) + 4 (l/32) + v%4 against vector 32 g + l%32

@@ -85,6 +85,44 @@ def test_full_size_workload(oracle, name):
     assert torch.equal(lpd.lpd_margins_rows(G, rd, w, r=rank), m[rd])
 
 
+def test_dropping_rule_at_size(oracle):
+    """The dropping rule of Section 4 (second bullet) on 4,096 landmarks of which 37 are copies of others: the
+    device preparation drops exactly those components, the factor keeps its columns from the rank on at zero, and
+    both parity and the kernel identity on the landmarks hold on the kept ones."""
+    from paper_2207_01016_amd import lpd, workloads
+    lpd.lib()
+    dev = torch.device("cuda:0")
+    wl = workloads.WORKLOADS["digit"].with_rows(262144)
+    dup = 37
+    torch.cuda.empty_cache()
+    X = workloads.make_X(wl, dev)
+    idx = workloads.landmark_indices(wl)
+    idx[wl.B - dup:] = idx[:dup]                              # the last 37 landmarks repeat the first 37
+    L = X[idx.to(dev)].contiguous()
+    Wd, eig, rank = lpd.lpd_whiten(L, wl.gamma)
+    assert rank == wl.B - dup
+    assert abs(float(eig.sum()) - wl.B) <= 1e-8 * wl.B       # trace of K_LL
+    assert float(eig[rank - 1]) > 1e-10 * float(eig[0]) >= abs(float(eig[rank]))
+    assert not bool(Wd[rank:].any())
+    torch.cuda.empty_cache()
+    G = torch.full((wl.n, wl.B), float("nan"), dtype=torch.float32, device=dev)
+    lpd.lpd_nystrom_factor(X, L, wl.gamma, Wd, G, lpd.alloc_workspace(wl.n, wl.d, wl.B, dev), r=rank)
+    torch.cuda.synchronize()
+    assert not bool(G[:, rank:].any())                        # exact zeros from the rank on
+    rows = workloads.sample_rows(wl, 192, include=torch.cat([idx[:32], idx[wl.B - dup:][:8], torch.tensor([0, wl.n - 1])]))
+    ref = oracle.nystrom_factor(X[rows.to(dev)].cpu().numpy(), L.cpu().numpy(), wl.gamma, Wd.cpu().numpy(), r=rank)
+    Gs = G[rows.to(dev)].cpu().numpy()
+    assert np.all(np.isfinite(Gs))
+    assert relfro(Gs[:, :rank], ref[:, :rank]) <= TOL_G
+    # landmark rows of G have norm 1; G_L G_L^T = K_LL on a block that holds copies
+    lm = G[idx.to(dev)].double()
+    assert torch.allclose((lm * lm).sum(dim=1), torch.ones(wl.B, dtype=torch.float64, device=dev), atol=1e-3)
+    sub = torch.cat([torch.arange(0, 96), torch.arange(wl.B - 32, wl.B)])
+    gl = lm[sub.to(dev)]
+    kll = oracle.kernel_block(L[sub.to(dev)].cpu().numpy(), L[sub.to(dev)].cpu().numpy(), wl.gamma)
+    assert relfro((gl @ gl.T).cpu().numpy(), kll) <= 1e-4
+
+
 def test_full_size_predict_cnn(oracle):
     """bench.py --path predict at its size: 262,144 new points of the cnn recipe, 10 classifiers; oracle on sampled points."""
     from paper_2207_01016_amd import lpd, workloads
